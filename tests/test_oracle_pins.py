@@ -1,0 +1,310 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something that is not the
+oracle - a hand-worked example, closed forms, scipy routines, exhaustive enumeration on tiny
+inputs, and the invariants a minimum spanning tree and a linkage must satisfy."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.cluster.hierarchy as sch
+import scipy.sparse.csgraph as csg
+from scipy.spatial.distance import cdist
+
+import oracle
+import slhc_inputs as gen
+
+
+# ----------------------------------------------------------------------------- helpers
+def all_pairs_f64(X):
+    """Every squared distance by explicit differences in float64 (numpy, no oracle code)."""
+    Xd = X.astype(np.float64)
+    diff = Xd[:, None, :] - Xd[None, :, :]
+    return np.einsum("ijt,ijt->ij", diff, diff)
+
+
+def exhaustive_knn(X, k):
+    D = all_pairs_f64(X)
+    N = X.shape[0]
+    idx = np.empty((N, k), dtype=np.int64)
+    dist = np.empty((N, k))
+    for i in range(N):
+        cand = [(D[i, j], j) for j in range(N) if j != i]
+        cand.sort()
+        idx[i] = [c[1] for c in cand[:k]]
+        dist[i] = [c[0] for c in cand[:k]]
+    return idx, dist
+
+
+def kruskal_all_pairs(X):
+    """Second MST algorithm: sort all N(N-1)/2 pairs by (w, lo, hi), union-find."""
+    D = all_pairs_f64(X)
+    N = X.shape[0]
+    iu, ju = np.triu_indices(N, 1)
+    w = D[iu, ju]
+    order = np.lexsort((ju, iu, w))
+    parent = list(range(N))
+
+    def find(a):
+        while parent[a] != a:
+            parent[a] = parent[parent[a]]
+            a = parent[a]
+        return a
+
+    edges = []
+    for e in order:
+        a, b = find(int(iu[e])), find(int(ju[e]))
+        if a != b:
+            parent[a] = b
+            edges.append((int(iu[e]), int(ju[e]), float(w[e])))
+            if len(edges) == N - 1:
+                break
+    return edges
+
+
+def as_edge_set(src, dst):
+    return {(min(int(a), int(b)), max(int(a), int(b))) for a, b in zip(src, dst)}
+
+
+def check_spanning_tree(src, dst, N):
+    assert len(src) == N - 1
+    parent = list(range(N))
+
+    def find(a):
+        while parent[a] != a:
+            parent[a] = parent[parent[a]]
+            a = parent[a]
+        return a
+
+    for a, b in zip(src, dst):
+        ra, rb = find(int(a)), find(int(b))
+        assert ra != rb, "cycle"
+        parent[ra] = rb
+    assert len({find(v) for v in range(N)}) == 1
+
+
+# ----------------------------------------------------------------------------- golden
+def test_five_points_knn(golden_five_points):
+    g = golden_five_points
+    X = np.array(g["points"], dtype=np.float32)
+    idx, dist = oracle.knn_graph(X, 2)
+    exp = np.array(g["knn2"])
+    assert idx.tolist() == exp[:, [0, 2]].astype(int).tolist()
+    assert dist.tolist() == exp[:, [1, 3]].tolist()
+
+
+def test_five_points_mst_and_dendrogram(golden_five_points):
+    g = golden_five_points
+    X = np.array(g["points"], dtype=np.float32)
+    out = oracle.slhc(X)
+    exp_mst = np.array(g["mst"])
+    assert out["src"].tolist() == exp_mst[:, 0].astype(int).tolist()
+    assert out["dst"].tolist() == exp_mst[:, 1].astype(int).tolist()
+    assert out["w"].tolist() == exp_mst[:, 2].tolist()
+    assert out["total_weight"] == 109.0
+    exp_d = np.array(g["dendrogram"])
+    assert out["children"].tolist() == exp_d[:, :2].astype(int).tolist()
+    assert out["heights"].tolist() == exp_d[:, 2].tolist()
+    assert out["sizes"].tolist() == exp_d[:, 3].astype(int).tolist()
+
+
+# ----------------------------------------------------------------------------- kNN
+@pytest.mark.parametrize("N,d,k", [(5, 1, 4), (17, 3, 5), (64, 16, 16), (33, 7, 32)])
+def test_knn_exhaustive_small(N, d, k):
+    X = np.random.default_rng(N * 100 + d).standard_normal((N, d)).astype(np.float32)
+    idx, dist = oracle.knn_graph(X, k)
+    eidx, edist = exhaustive_knn(X, k)
+    assert np.array_equal(idx, eidx)
+    np.testing.assert_allclose(dist, edist, rtol=1e-14, atol=0)
+
+
+def test_knn_vs_scipy_cdist():
+    X, _, k = gen.make("c1", n=1500)
+    idx, dist = oracle.knn_graph(X, k)
+    D = cdist(X.astype(np.float64), X.astype(np.float64), "sqeuclidean")
+    np.fill_diagonal(D, np.inf)
+    order = np.argsort(D, axis=1, kind="stable")[:, :k]
+    assert np.array_equal(idx, order)
+    np.testing.assert_allclose(dist, np.take_along_axis(D, order, 1), rtol=1e-12)
+
+
+def test_knn_sampled_rows_match_full():
+    X, _, k = gen.make("c2", n=3000)
+    rows = np.array([0, 7, 2999, 1234, 7], dtype=np.int64)
+    fi, fd = oracle.knn_graph(X, k)
+    si, sd = oracle.knn_rows(X, rows, k)
+    assert np.array_equal(si, fi[rows]) and np.array_equal(sd, fd[rows])
+
+
+def test_knn_lattice_closed_form():
+    # 5x5x5 integer lattice: all squared distances are exact small integers; ties everywhere.
+    X = gen.integer_lattice(5, 3, seed=3)
+    N, k = X.shape[0], 10
+    idx, dist = oracle.knn_graph(X, k)
+    Xi = X.astype(np.int64)
+    for i in range(N):
+        D = ((Xi - Xi[i]) ** 2).sum(1)
+        cand = sorted((int(D[j]), j) for j in range(N) if j != i)[:k]
+        assert idx[i].tolist() == [c[1] for c in cand]
+        assert dist[i].tolist() == [float(c[0]) for c in cand]
+    centre = int(np.where((Xi == 2).all(1))[0][0])
+    assert dist[centre, :6].tolist() == [1.0] * 6 and dist[centre, 6:].tolist() == [2.0] * 4
+
+
+def test_knn_invariants_and_duplicates():
+    X, _, k = gen.make("c5", n=3000)
+    N = X.shape[0]
+    idx, dist = oracle.knn_graph(X, k)
+    assert idx.min() >= 0 and idx.max() < N
+    assert not (idx == np.arange(N)[:, None]).any(), "self listed"
+    assert all(len(set(r)) == k for r in idx.tolist()), "repeat"
+    assert (np.diff(dist, axis=1) >= 0).all()
+    D = all_pairs_f64(X[:400])                       # selection bound on a corner of the matrix
+    full = cdist(X[:50].astype(np.float64), X.astype(np.float64), "sqeuclidean")
+    for i in range(50):
+        unlisted = np.setdiff1d(np.arange(N), np.append(idx[i], i))
+        assert full[i, unlisted].min() >= dist[i, -1]
+    # exact duplicates exist in this workload: they sit at distance exactly 0 and are listed
+    dup_rows = np.where(dist[:, 0] == 0.0)[0]
+    assert dup_rows.size > 0
+    for i in dup_rows[:20]:
+        assert np.array_equal(X[i], X[idx[i, 0]]) and idx[i, 0] != i
+    assert D.shape == (400, 400)
+
+
+def test_knn_bad_arguments():
+    X = np.zeros((4, 2), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.knn_graph(X, 4)          # k > N-1
+    with pytest.raises(ValueError):
+        oracle.knn_graph(X, 0)
+
+
+# ----------------------------------------------------------------------------- cross-colour 1-NN
+def test_cross_1nn_vs_numpy():
+    X, labels, _ = gen.make("c1", n=600)
+    colour = (labels % 3).astype(np.int32)
+    rows = np.arange(0, 600, 7, dtype=np.int64)
+    idx, dist = oracle.cross_1nn(X, colour, rows)
+    D = all_pairs_f64(X)
+    for q, i in enumerate(rows):
+        Dm = np.where(colour != colour[i], D[i], np.inf)
+        j = int(np.argmin(Dm))
+        assert idx[q] == j and dist[q] == pytest.approx(Dm[j], rel=1e-14)
+    one = np.zeros(600, dtype=np.int32)
+    idx, dist = oracle.cross_1nn(X, one, rows)
+    assert (idx == -1).all() and np.isinf(dist).all()
+
+
+# ----------------------------------------------------------------------------- MST
+@pytest.mark.parametrize("name,n", [("c1", 300), ("c2", 257), ("c4", 120)])
+def test_mst_vs_kruskal(name, n):
+    X, _, _ = gen.make(name, n=n)
+    src, dst, w = oracle.mst_prim(X)
+    check_spanning_tree(src, dst, n)
+    kr = kruskal_all_pairs(X)
+    assert as_edge_set(src, dst) == {(a, b) for a, b, _ in kr}
+    assert np.sum(np.sort(w)) == pytest.approx(sum(sorted(e[2] for e in kr)), rel=1e-13)
+    D = all_pairs_f64(X)
+    np.testing.assert_allclose(w, D[src, dst], rtol=1e-14)
+
+
+def test_mst_vs_scipy_csgraph():
+    X, _, _ = gen.make("c1", n=1200)       # tie-free and zero-free, so csgraph is usable
+    src, dst, w = oracle.mst_prim(X)
+    D = cdist(X.astype(np.float64), X.astype(np.float64), "sqeuclidean")
+    T = csg.minimum_spanning_tree(D).tocoo()
+    assert as_edge_set(src, dst) == as_edge_set(T.row, T.col)
+    assert np.sum(np.sort(w)) == pytest.approx(np.sum(np.sort(T.data)), rel=1e-12)
+
+
+@pytest.mark.parametrize("N", [4, 7, 10])
+def test_mst_cut_property_all_cuts(N):
+    X = np.random.default_rng(N).standard_normal((N, 3)).astype(np.float32)
+    src, dst, _ = oracle.mst_prim(X)
+    tree = as_edge_set(src, dst)
+    D = all_pairs_f64(X)
+    for r in range(1, N):
+        for rest in itertools.combinations(range(1, N), r - 1):
+            S = {0, *rest}
+            if len(S) == N:
+                continue
+            T = [v for v in range(N) if v not in S]
+            best = min(((D[a, b], min(a, b), max(a, b)) for a in S for b in T))
+            assert (best[1], best[2]) in tree
+
+
+def test_mst_increasing_gaps_closed_form():
+    N = 200
+    X, pos = gen.increasing_gaps_line(N, 3, seed=5)
+    src, dst, w = oracle.mst_prim(X)
+    order = np.argsort(pos)
+    expected = {(min(int(order[i]), int(order[i + 1])), max(int(order[i]), int(order[i + 1])))
+                for i in range(N - 1)}
+    assert as_edge_set(src, dst) == expected
+    assert sorted(w.tolist()) == [float((i + 1) ** 2) for i in range(N - 1)]
+
+
+def test_mst_unit_lattice_all_ties():
+    X = gen.integer_lattice(6, 2, seed=9)
+    src, dst, w = oracle.mst_prim(X)
+    check_spanning_tree(src, dst, 36)
+    assert (w == 1.0).all()
+
+
+def test_mst_knn_graph_is_not_enough_example():
+    # Seven points whose 2-NN graph is connected but does not contain the minimum spanning tree:
+    # two vertical triples half a unit apart and one far point that lists one point of each.
+    X = np.array([[0, 0], [0, -.1], [0, -.2], [.5, 0], [.5, -.1], [.5, -.2], [.2, 10]],
+                 dtype=np.float32)
+    out = oracle.slhc(X)
+    assert out["total_weight"] == pytest.approx(0.04 + 0.25 + 100.04, rel=1e-6)
+    assert (0, 3) in as_edge_set(out["src"], out["dst"])
+    idx, _ = oracle.knn_graph(X, 2)
+    listed = {(min(i, int(j)), max(i, int(j))) for i in range(7) for j in idx[i]}
+    assert (0, 3) not in listed
+
+
+def test_mst_two_far_blobs_last_edge():
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((150, 5))
+    B = rng.standard_normal((130, 5)) + 40.0
+    X = np.concatenate([A, B]).astype(np.float32)
+    out = oracle.slhc(X)
+    D = all_pairs_f64(X)
+    assert out["heights"][-1] == pytest.approx(D[:150, 150:].min(), rel=1e-14)
+    assert out["sizes"][-1] == 280
+
+
+# ----------------------------------------------------------------------------- dendrogram
+@pytest.mark.parametrize("name,n", [("c1", 800), ("c2", 500), ("c3", 700)])
+def test_dendrogram_vs_scipy_linkage(name, n):
+    X, _, _ = gen.make(name, n=n)
+    out = oracle.slhc(X)
+    Z = sch.linkage(X.astype(np.float64), method="single", metric="sqeuclidean")
+    np.testing.assert_allclose(out["heights"], Z[:, 2], rtol=1e-12)
+    assert np.array_equal(out["sizes"], Z[:, 3].astype(np.int32))
+    zc = np.sort(Z[:, :2].astype(np.int32), axis=1)
+    assert np.array_equal(out["children"], zc)
+
+
+def test_dendrogram_invariants_with_ties():
+    X, _, _ = gen.make("c5", n=2500)
+    N = X.shape[0]
+    out = oracle.slhc(X)
+    ch, h, sz = out["children"], out["heights"], out["sizes"]
+    assert (np.diff(h) >= 0).all()
+    assert sz[-1] == N
+    assert sorted(ch.ravel().tolist()) == list(range(2 * N - 2))     # every node is a child once
+    assert (ch[:, 0] < ch[:, 1]).all()
+    assert (ch < (N + np.arange(N - 1))[:, None]).all()
+    Z = sch.linkage(X.astype(np.float64), method="single", metric="sqeuclidean")
+    np.testing.assert_allclose(h, Z[:, 2], rtol=1e-12, atol=0)        # heights are unique as a multiset
+    assert h[0] == 0.0                                                  # duplicates merge first
+
+
+def test_dendrogram_rejects_cycle():
+    with pytest.raises(ValueError):
+        oracle.dendrogram([0, 1, 0], [1, 2, 2], [1.0, 2.0, 3.0], 4)
+
+
+def test_oracle_reports_threads():
+    assert oracle.num_threads() >= 1
