@@ -1,0 +1,142 @@
+/*
+ * slhc.h - C ABI of the MI355X (gfx950) single-linkage clustering library.
+ *
+ * The library implements the data-parallel path of cuSLINK (Nolet et al., "cuSLINK:
+ * Single-linkage Agglomerative Clustering on the GPU", ECML PKDD 2023):
+ *   fused brute-force k-NN graph  ->  Boruvka minimum spanning forest over the k-NN lists  ->
+ *   cross-component nearest-neighbour connection until the forest is the exact minimum spanning
+ *   tree  ->  weight-sorted edges  ->  dendrogram in scipy linkage layout.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are device memory of the current HIP device, owned by the caller
+ *     (for instance the data_ptr() of a torch tensor).  Pointers marked HOST are host memory.
+ *     The library never frees or keeps a caller pointer after the call returns, and it never
+ *     modifies an input.
+ *   - X is row-major float32 [N, d], finite values.  Distances are squared Euclidean.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - `workspace` is DEVICE scratch of at least the size the matching *_workspace_bytes call
+ *     reports, 256-byte aligned; its contents on entry are ignored and on exit unspecified.
+ *   - Every function returns an slhc_status.  No C++ exception crosses the boundary.  On any
+ *     status other than SLHC_OK the outputs are unspecified.  slhc_last_error() gives a
+ *     thread-local detail string for the last failing call of the calling thread.
+ *   - Calls that share a workspace must not overlap in time.  Calls on different streams with
+ *     different workspaces and outputs are independent.
+ */
+#ifndef SLHC_H
+#define SLHC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLHC_ABI_VERSION 1
+
+/* Largest k of the fused path: the selection keeps one list entry per lane of a 64-wide
+ * wavefront.  (The paper's fused k-NN has the same limit, Sec. 2 and Sec. 3.1.1: k <= 64.) */
+#define SLHC_MAX_K 64
+
+typedef enum slhc_status {
+    SLHC_OK = 0,
+    SLHC_INVALID_ARG = 1,        /* null pointer, N < 2, d < 1, k < 1, k > N-1, bad row index      */
+    SLHC_UNSUPPORTED = 2,        /* k > SLHC_MAX_K, or N*k / N*d beyond the 2^31-1 element indexing */
+    SLHC_WORKSPACE_TOO_SMALL = 3,
+    SLHC_HIP_ERROR = 4,          /* a HIP call failed; see slhc_last_error()                      */
+    SLHC_INTERNAL = 5            /* the connection loop did not reach one component in
+                                    ceil(log2 N) + 2 rounds (cannot happen for finite input)      */
+} slhc_status;
+
+/* Counters and stage times of one slhc_slhc call (HOST struct, filled when not NULL). */
+typedef struct slhc_stats {
+    int32_t boruvka_rounds;          /* rounds of min-edge + relabel                              */
+    int32_t connect_rounds;          /* rounds in which the cross-component 1-NN kernel ran        */
+    int32_t components_after_knn;    /* components when the k-NN lists alone could add no edge     */
+    int32_t reserved0;
+    int64_t knn_filter_survivors;    /* pairs that passed the MFMA filter in the k-NN sweep        */
+    int64_t connect_query_rows;      /* sum over connection rounds of queried rows                 */
+    int64_t connect_filter_survivors;
+    float ms_knn;                    /* norms + fused k-NN                                         */
+    float ms_boruvka;                /* all min-edge / commit / relabel kernels                    */
+    float ms_connect;                /* all cross-component 1-NN sweeps                            */
+    float ms_sort;                   /* edge sort                                                  */
+    float ms_dendrogram;             /* device->host copy, host union-find, host->device copy      */
+    float ms_total;
+} slhc_stats;
+
+int slhc_abi_version(void);
+const char* slhc_strerror(int status);          /* static string, never NULL */
+const char* slhc_last_error(void);              /* thread-local, never NULL  */
+
+/*
+ * k-NN graph (paper Sec. 3.1.1, Alg. "Fused k-NN" with its epilogues in Appendix A).
+ *
+ * For every row i the k rows j != i with the smallest (||x_i - x_j||^2, j), ascending.
+ * The distance tile x_i . x_j is computed on fp32 MFMA and only used to discard pairs that
+ * cannot enter a row's list; a pair that may enter is re-evaluated as sum_t (x_it - x_jt)^2
+ * in fp32, so the reported value of (i,j) equals that of (j,i) bit for bit and duplicates are at
+ * exactly 0.  A row is never its own neighbour (excluded by index, not by distance).
+ *
+ *   X         DEVICE in   [N*d]
+ *   nbr_idx   DEVICE out  [N*k] row-major int32
+ *   nbr_dist  DEVICE out  [N*k] row-major float32
+ * Asynchronous: work is enqueued on `stream`; outputs are complete when the stream reaches the
+ * end of that work.  Errors detected on the host are reported immediately.
+ */
+int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes /* HOST out */);
+int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k,
+                   int32_t* nbr_idx, float* nbr_dist,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cross-component 1-NN (paper Sec. 3.1.2, Alg. "Fused 1-NN", used by Alg. "connect_graph").
+ *
+ * For each query row rows[q], q < m: the row j with colour[j] != colour[rows[q]] that minimises
+ * (||x_rows[q] - x_j||^2, j).  out_idx[q] = -1 and out_dist[q] = +inf when every row has the
+ * query's colour.  Same filter-then-re-evaluate arithmetic as slhc_knn_graph.
+ *
+ *   X        DEVICE in  [N*d]       colour   DEVICE in  [N] int32
+ *   rows     DEVICE in  [m] int32   (each in [0, N); NULL means rows 0..m-1, then m <= N)
+ *   out_idx  DEVICE out [m] int32   out_dist DEVICE out [m] float32
+ * Asynchronous on `stream` like slhc_knn_graph.
+ */
+int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes /* HOST out */);
+int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour,
+                   const int32_t* rows, int64_t m, int32_t* out_idx, float* out_dist,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Single-linkage clustering (paper Alg. "cuSLINK Algorithm" without the final flat cut:
+ * k-NN graph, Sec. 3.1.1; MST by Boruvka with colours, Sec. 3.2, Alg. "MST Algorithm";
+ * connection of the forest, Sec. 3.1.2, Alg. "connect_graph"; sorted edges and dendrogram,
+ * Sec. 3.3.1).
+ *
+ * The tree returned is the exact minimum spanning tree of the complete squared-L2 graph under
+ * the strict edge order (weight, min endpoint, max endpoint), with weights evaluated as in
+ * slhc_knn_graph.  A component adds its lightest known outgoing edge only once that edge is
+ * proven lighter than every pair the k-NN lists do not cover; rows for which this cannot be
+ * proven are sent to the cross-component 1-NN.
+ *
+ *   X         DEVICE in   [N*d]
+ *   mst_src   DEVICE out  [N-1] int32   smaller endpoint
+ *   mst_dst   DEVICE out  [N-1] int32   larger endpoint
+ *   mst_w     DEVICE out  [N-1] float32 ascending by (w, src, dst)
+ *   children  DEVICE out  [(N-1)*2] int32: merge i joins nodes children[2i] < children[2i+1]
+ *                         into node N+i; ids below N are the input rows
+ *   heights   DEVICE out  [N-1] float32 = mst_w (merge i has the weight of sorted edge i)
+ *   sizes     DEVICE out  [N-1] int32 rows under node N+i
+ *   stats     HOST   out  optional
+ * Synchronous: returns after the outputs are complete (the dendrogram pass runs on the host, as
+ * in the paper, so the call has to wait for the device anyway).
+ */
+int slhc_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes /* HOST out */);
+int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k,
+              int32_t* mst_src, int32_t* mst_dst, float* mst_w,
+              int32_t* children, float* heights, int32_t* sizes,
+              slhc_stats* stats, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLHC_H */

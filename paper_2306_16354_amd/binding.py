@@ -1,0 +1,163 @@
+"""ctypes binding of libslhc.so.  Function names follow include/slhc.h without the prefix."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libslhc.so")
+_lib = None
+
+
+class SlhcError(RuntimeError):
+    def __init__(self, status, text, detail):
+        super().__init__(f"slhc status {status} ({text}): {detail}")
+        self.status = status
+
+
+class _Stats(ctypes.Structure):
+    _fields_ = [
+        ("boruvka_rounds", ctypes.c_int32), ("connect_rounds", ctypes.c_int32),
+        ("components_after_knn", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("knn_filter_survivors", ctypes.c_int64), ("connect_query_rows", ctypes.c_int64),
+        ("connect_filter_survivors", ctypes.c_int64),
+        ("ms_knn", ctypes.c_float), ("ms_boruvka", ctypes.c_float), ("ms_connect", ctypes.c_float),
+        ("ms_sort", ctypes.c_float), ("ms_dendrogram", ctypes.c_float), ("ms_total", ctypes.c_float),
+    ]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libslhc.so; raises if it has not been built.  Nothing here falls back to the CPU."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2306_16354_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.slhc_abi_version.restype = ctypes.c_int
+    lib.slhc_strerror.restype = ctypes.c_char_p
+    lib.slhc_strerror.argtypes = [ctypes.c_int]
+    lib.slhc_last_error.restype = ctypes.c_char_p
+    lib.slhc_knn_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
+    lib.slhc_knn_graph.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
+    lib.slhc_cross_1nn.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, sz, vp]
+    lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
+    lib.slhc_slhc.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats), vp, sz, vp]
+    for name in ("slhc_knn_workspace_bytes", "slhc_knn_graph", "slhc_cross_1nn_workspace_bytes",
+                 "slhc_cross_1nn", "slhc_workspace_bytes", "slhc_slhc"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        lib = load_library()
+        raise SlhcError(status, lib.slhc_strerror(status).decode(), lib.slhc_last_error().decode())
+
+
+def abi_version():
+    return int(load_library().slhc_abi_version())
+
+
+def _device_matrix(X):
+    if not (isinstance(X, torch.Tensor) and X.is_cuda and X.dtype == torch.float32 and X.dim() == 2
+            and X.is_contiguous()):
+        raise TypeError("X must be a contiguous float32 CUDA tensor [N, d]")
+    return X
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def knn_workspace_bytes(N, d, k):
+    out = ctypes.c_size_t(0)
+    _check(load_library().slhc_knn_workspace_bytes(N, d, k, ctypes.byref(out)))
+    return out.value
+
+
+def slhc_workspace_bytes(N, d, k):
+    out = ctypes.c_size_t(0)
+    _check(load_library().slhc_workspace_bytes(N, d, k, ctypes.byref(out)))
+    return out.value
+
+
+def knn_graph(X, k, out=None, workspace=None):
+    """slhc_knn_graph: returns (idx int32 [N,k], dist float32 [N,k]) device tensors.  Asynchronous
+    on the current stream."""
+    X = _device_matrix(X)
+    N, d = X.shape
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(knn_workspace_bytes(N, d, k), X.device)
+    if out is None:
+        idx = torch.empty((N, k), dtype=torch.int32, device=X.device)
+        dist = torch.empty((N, k), dtype=torch.float32, device=X.device)
+    else:
+        idx, dist = out
+    _check(lib.slhc_knn_graph(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), _stream()))
+    return idx, dist
+
+
+def cross_1nn(X, colour, rows=None, m=None):
+    """slhc_cross_1nn: nearest row of another colour for each query row."""
+    X = _device_matrix(X)
+    N, d = X.shape
+    if not (colour.is_cuda and colour.dtype == torch.int32 and colour.shape == (N,) and colour.is_contiguous()):
+        raise TypeError("colour must be a contiguous int32 CUDA tensor [N]")
+    if rows is not None:
+        if not (rows.is_cuda and rows.dtype == torch.int32 and rows.dim() == 1 and rows.is_contiguous()):
+            raise TypeError("rows must be a contiguous int32 CUDA tensor [m]")
+        m = rows.numel()
+    elif m is None:
+        m = N
+    lib = load_library()
+    need = ctypes.c_size_t(0)
+    _check(lib.slhc_cross_1nn_workspace_bytes(N, d, m, ctypes.byref(need)))
+    ws = _workspace(need.value, X.device)
+    idx = torch.empty(m, dtype=torch.int32, device=X.device)
+    dist = torch.empty(m, dtype=torch.float32, device=X.device)
+    _check(lib.slhc_cross_1nn(X.data_ptr(), N, d, colour.data_ptr(),
+                              rows.data_ptr() if rows is not None else None, m,
+                              idx.data_ptr(), dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return idx, dist
+
+
+def slhc(X, k, workspace=None):
+    """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
+    (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict)."""
+    X = _device_matrix(X)
+    N, d = X.shape
+    lib = load_library()
+    if workspace is None:
+        workspace = _workspace(slhc_workspace_bytes(N, d, k), X.device)
+    dev = X.device
+    out = dict(
+        mst_src=torch.empty(N - 1, dtype=torch.int32, device=dev),
+        mst_dst=torch.empty(N - 1, dtype=torch.int32, device=dev),
+        mst_w=torch.empty(N - 1, dtype=torch.float32, device=dev),
+        children=torch.empty((N - 1, 2), dtype=torch.int32, device=dev),
+        heights=torch.empty(N - 1, dtype=torch.float32, device=dev),
+        sizes=torch.empty(N - 1, dtype=torch.int32, device=dev),
+    )
+    st = _Stats()
+    _check(lib.slhc_slhc(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
+                         out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
+                         out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
+                         workspace.numel(), _stream()))
+    out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if name != "reserved0"}
+    return out

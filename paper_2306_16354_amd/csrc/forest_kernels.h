@@ -1,0 +1,52 @@
+// Launch interface of the Boruvka forest kernels and the edge sort (forest_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace slhc {
+
+// Device state of the minimum-spanning-forest construction.  Components are named by the index
+// of their root vertex ("colour", paper Sec. 3.2.3); per-component arrays are indexed by it.
+struct ForestState {
+    int N, k;
+    const int32_t* nbr_idx;      // [N, k] ascending by (dist, idx)
+    const float* nbr_dist;       // [N, k]
+    int32_t* colour;             // [N]
+    int32_t* ptr;                // [N] entries before ptr[v] are known to share v's colour
+    int32_t* ext_idx;            // [N] last cross-component 1-NN answer of v (-1: none yet)
+    float* ext_dist;             // [N]
+    float* cand_w;               // [N] weight of v's lightest outgoing edge, or a lower bound
+    int32_t* cand_u;             // [N] its other endpoint, or -1 when only the bound is known
+    uint32_t* best_w;            // [N] per component: min weight bits over exact candidates
+    unsigned long long* best_e;  // [N] per component: min (lo << 32 | hi) among those of best_w
+    uint32_t* min_lb;            // [N] per component: min lower-bound bits over unknown vertices
+    int32_t* hook;               // [N] per component: component it attaches to this round
+    int32_t* qlist;              // [N] rows sent to the cross-component 1-NN
+    int32_t* counters;           // [4]: 0 = queries this round, 1 = edges so far, 2 = jump flag,
+                                 //      3 = site of the first failed index check (0 = none)
+    int32_t* e_lo;               // [N-1] committed edges
+    int32_t* e_hi;
+    float* e_w;
+};
+
+hipError_t forest_init(const ForestState& f, hipStream_t s);
+hipError_t forest_round_reset(const ForestState& f, hipStream_t s);
+hipError_t forest_scan_lists(const ForestState& f, hipStream_t s);
+hipError_t forest_classify(const ForestState& f, hipStream_t s);
+hipError_t forest_apply_queries(const ForestState& f, const int32_t* q_idx, const float* q_dist,
+                                int nq, hipStream_t s);
+hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
+hipError_t forest_commit(const ForestState& f, hipStream_t s);
+hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step
+hipError_t forest_relabel(const ForestState& f, hipStream_t s);
+
+// Sort E edges ascending by (w, lo, hi).  keys/vals are scratch of E elements each; `temp` of
+// edge_sort_temp_bytes(E).  Result in out_lo/out_hi/out_w.
+size_t edge_sort_temp_bytes(int E);
+hipError_t edge_sort(const int32_t* lo, const int32_t* hi, const float* w, int E,
+                     unsigned long long* keys_a, unsigned long long* keys_b,
+                     uint32_t* vals_a, uint32_t* vals_b, void* temp, size_t temp_bytes,
+                     int32_t* out_lo, int32_t* out_hi, float* out_w, hipStream_t s);
+
+}  // namespace slhc

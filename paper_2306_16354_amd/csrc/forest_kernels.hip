@@ -1,0 +1,299 @@
+// Boruvka minimum spanning forest over cached sorted neighbour lists, with colours instead of
+// graph contraction (cuSLINK paper Sec. 3.2: Alg. "MST Algorithm", "Minimum incident edges",
+// "Label Propagation"), plus the weight sort of Sec. 3.3.1.
+//
+// Differences from the paper's kernels, all deliberate:
+//   * No weight alteration (Sec. 3.2.1).  Ties are broken by the strict order
+//     (weight, min endpoint, max endpoint) on undirected edges, which also handles zero weights
+//     and exact duplicates, where a random perturbation below the smallest weight gap cannot work.
+//     A component's minimum is found in two atomic passes: 32-bit min over weight bits, then
+//     64-bit min over (lo, hi) among the edges of that weight.
+//   * The lists are the directed k-NN lists, already ascending, so "minimum edge per vertex" is
+//     the first entry of another colour: one lane per entry, one ballot, no reduction tree.
+//   * A vertex whose whole list shares its colour contributes a lower bound (its k-th distance,
+//     or its last cross-component 1-NN distance) instead of an edge; the host commits a
+//     component's edge only when it beats every such bound, and queries the rest.  This is what
+//     makes the result the minimum spanning tree of the complete graph and not just of the
+//     k-NN graph.
+//   * Relabelling is pointer doubling over component roots, then one gather per vertex, instead
+//     of iterated atomicMin colour exchange (Alg. "min_pair_colors" / "update_colors").
+#include <hip/hip_runtime.h>
+#include <cstring>
+#include <rocprim/rocprim.hpp>
+#include <stdint.h>
+#include "forest_kernels.h"
+
+namespace slhc {
+
+constexpr uint32_t INF_BITS = 0x7f800000u;
+constexpr int TB = 256;
+
+static inline int blocks_for(long long n) { return (int)((n + TB - 1) / TB); }
+
+// Every index that comes out of device memory is range-checked before it is used as an address.
+// A failed check records its site in counters[3] (the host turns that into SLHC_INTERNAL) and the
+// access is skipped, so corrupt state can never become an out-of-bounds access.
+__device__ inline bool in_range(int i, int n) { return (unsigned int)i < (unsigned int)n; }
+__device__ inline void report(const ForestState& f, int site) { atomicCAS(&f.counters[3], 0, site); }
+
+__global__ void __launch_bounds__(TB) k_forest_init(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N) return;
+    f.colour[v] = v;
+    f.ptr[v] = 0;
+    f.ext_idx[v] = -1;
+    f.ext_dist[v] = 0.f;
+    if (v < 4) f.counters[v] = 0;
+}
+
+__global__ void __launch_bounds__(TB) k_round_reset(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N) return;
+    f.best_w[v] = INF_BITS;
+    f.best_e[v] = ~0ull;
+    f.min_lb[v] = INF_BITS;
+    if (v == 0) f.counters[0] = 0;
+}
+
+// G lanes per vertex (G = power of two >= k): lane j looks at list entry j.
+template <int G>
+__global__ void __launch_bounds__(TB) k_scan_lists(ForestState f)
+{
+    const int gid = (int)(((long long)blockIdx.x * TB + threadIdx.x) / G);
+    const int j = threadIdx.x & (G - 1);
+    const int lane = threadIdx.x & 63;
+    const bool live = gid < f.N;
+    const int v = live ? gid : 0;
+    const int c = f.colour[v];
+    const int p = f.ptr[v];
+    bool foreign = false;
+    if (live && j < f.k && j >= p) {
+        const int u = f.nbr_idx[(size_t)v * f.k + j];
+        if (in_range(u, f.N)) foreign = f.colour[u] != c;
+        else report(f, 1);
+    }
+    unsigned long long mask = __ballot(foreign);
+    if constexpr (G < 64) mask = (mask >> (lane & ~(G - 1))) & ((1ull << G) - 1ull);
+    if (!live || j != 0) return;
+    if (!in_range(c, f.N)) { report(f, 2); return; }
+    if (mask) {
+        const int pn = __builtin_ctzll(mask);
+        const float w = f.nbr_dist[(size_t)v * f.k + pn];
+        f.ptr[v] = pn;
+        f.cand_w[v] = w;
+        f.cand_u[v] = f.nbr_idx[(size_t)v * f.k + pn];
+        atomicMin(&f.best_w[c], __float_as_uint(w));
+        return;
+    }
+    f.ptr[v] = f.k;
+    const int eu = f.ext_idx[v];
+    const float ed = f.ext_dist[v];
+    if (eu >= f.N) { report(f, 3); return; }
+    if (eu >= 0 && f.colour[eu] != c) {          // cached answer still leads out of the component
+        f.cand_w[v] = ed;
+        f.cand_u[v] = eu;
+        atomicMin(&f.best_w[c], __float_as_uint(ed));
+        return;
+    }
+    float lb = f.nbr_dist[(size_t)v * f.k + f.k - 1];
+    if (eu >= 0 && ed > lb) lb = ed;
+    f.cand_w[v] = lb;
+    f.cand_u[v] = -1;
+    atomicMin(&f.min_lb[c], __float_as_uint(lb));
+}
+
+// Vertices that only know a lower bound and whose bound does not exceed their component's best
+// exact weight must be queried (<=, so that weight ties are resolved by the edge order).
+__global__ void __launch_bounds__(TB) k_classify(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    bool need = false;
+    if (v < f.N && f.cand_u[v] < 0) {
+        const int c = f.colour[v];
+        if (in_range(c, f.N)) need = __float_as_uint(f.cand_w[v]) <= f.best_w[c];
+        else report(f, 4);
+    }
+    const unsigned long long mask = __ballot(need);
+    if (!mask) return;
+    const int lane = threadIdx.x & 63;
+    const int leader = __builtin_ctzll(mask);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(&f.counters[0], __popcll(mask));
+    base = __shfl(base, leader);
+    if (need) {
+        const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+        if (in_range(base + pre, f.N)) f.qlist[base + pre] = v;
+        else report(f, 5);
+    }
+}
+
+__global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32_t* __restrict__ q_idx,
+                                                      const float* __restrict__ q_dist, int nq)
+{
+    const int q = blockIdx.x * TB + threadIdx.x;
+    if (q >= nq) return;
+    const int v = f.qlist[q];
+    const int u = q_idx[q];
+    const float w = q_dist[q];
+    if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) { report(f, 6); return; }
+    f.ext_idx[v] = u;
+    f.ext_dist[v] = w;
+    f.cand_u[v] = u;
+    f.cand_w[v] = w;
+    if (u >= 0) atomicMin(&f.best_w[f.colour[v]], __float_as_uint(w));
+}
+
+__global__ void __launch_bounds__(TB) k_select_edges(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N) return;
+    const int u = f.cand_u[v];
+    if (u < 0) return;
+    const int c = f.colour[v];
+    if (u >= f.N || !in_range(c, f.N)) { report(f, 7); return; }
+    if (__float_as_uint(f.cand_w[v]) != f.best_w[c]) return;
+    const unsigned int lo = (unsigned int)(v < u ? v : u), hi = (unsigned int)(v < u ? u : v);
+    atomicMin(&f.best_e[c], ((unsigned long long)lo << 32) | hi);
+}
+
+// One thread per component root: append the component's edge (once per undirected edge) and
+// record which component it attaches to.  Two components that chose the same edge keep the
+// smaller root.
+__global__ void __launch_bounds__(TB) k_commit(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N || f.colour[v] != v) return;
+    const uint32_t wb = f.best_w[v];
+    if (wb == INF_BITS) { f.hook[v] = v; return; }
+    const unsigned long long e = f.best_e[v];
+    const int lo = (int)(e >> 32), hi = (int)(e & 0xffffffffull);
+    if (!in_range(lo, f.N) || !in_range(hi, f.N)) { report(f, 8); f.hook[v] = v; return; }
+    const int clo = f.colour[lo], chi = f.colour[hi];
+    const int other = (clo == v) ? chi : clo;
+    if (!in_range(other, f.N) || other == v || (clo != v && chi != v)) { report(f, 9); f.hook[v] = v; return; }
+    const bool mutual = (f.best_w[other] == wb) && (f.best_e[other] == e);
+    if (!mutual || v < other) {
+        const int slot = atomicAdd(&f.counters[1], 1);
+        if (slot < f.N - 1) {
+            f.e_lo[slot] = lo;
+            f.e_hi[slot] = hi;
+            f.e_w[slot] = __uint_as_float(wb);
+        }
+    }
+    f.hook[v] = (mutual && v < other) ? v : other;
+}
+
+__global__ void __launch_bounds__(TB) k_jump(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N || f.colour[v] != v) return;
+    const int h = f.hook[v];
+    if (!in_range(h, f.N)) { report(f, 10); return; }
+    const int hh = f.hook[h];
+    if (!in_range(hh, f.N)) { report(f, 11); return; }
+    if (hh != h) {
+        f.hook[v] = hh;
+        f.counters[2] = 1;
+    }
+}
+
+__global__ void __launch_bounds__(TB) k_relabel(ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N) return;
+    const int c = f.colour[v];
+    if (!in_range(c, f.N)) { report(f, 12); return; }
+    const int r = f.hook[c];
+    if (!in_range(r, f.N)) { report(f, 13); return; }
+    f.colour[v] = r;
+}
+
+#define LAUNCH1(kern, n, s, ...)                                                       \
+    do {                                                                               \
+        hipLaunchKernelGGL(kern, dim3(blocks_for(n)), dim3(TB), 0, s, __VA_ARGS__);    \
+        return hipGetLastError();                                                      \
+    } while (0)
+
+hipError_t forest_init(const ForestState& f, hipStream_t s) { LAUNCH1(k_forest_init, f.N, s, f); }
+hipError_t forest_round_reset(const ForestState& f, hipStream_t s) { LAUNCH1(k_round_reset, f.N, s, f); }
+
+hipError_t forest_scan_lists(const ForestState& f, hipStream_t s)
+{
+    if (f.k <= 8) LAUNCH1(k_scan_lists<8>, (long long)f.N * 8, s, f);
+    if (f.k <= 16) LAUNCH1(k_scan_lists<16>, (long long)f.N * 16, s, f);
+    if (f.k <= 32) LAUNCH1(k_scan_lists<32>, (long long)f.N * 32, s, f);
+    LAUNCH1(k_scan_lists<64>, (long long)f.N * 64, s, f);
+}
+
+hipError_t forest_classify(const ForestState& f, hipStream_t s) { LAUNCH1(k_classify, f.N, s, f); }
+
+hipError_t forest_apply_queries(const ForestState& f, const int32_t* q_idx, const float* q_dist,
+                                int nq, hipStream_t s)
+{
+    LAUNCH1(k_apply_queries, nq, s, f, q_idx, q_dist, nq);
+}
+
+hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }
+hipError_t forest_commit(const ForestState& f, hipStream_t s) { LAUNCH1(k_commit, f.N, s, f); }
+hipError_t forest_jump(const ForestState& f, hipStream_t s) { LAUNCH1(k_jump, f.N, s, f); }
+hipError_t forest_relabel(const ForestState& f, hipStream_t s) { LAUNCH1(k_relabel, f.N, s, f); }
+
+// ------------------------------------------------------------------------------- edge sort
+__global__ void __launch_bounds__(TB) k_pack_edges(const int32_t* __restrict__ lo,
+                                                   const int32_t* __restrict__ hi,
+                                                   const float* __restrict__ w, int E,
+                                                   unsigned long long* __restrict__ keys,
+                                                   uint32_t* __restrict__ vals)
+{
+    const int i = blockIdx.x * TB + threadIdx.x;
+    if (i >= E) return;
+    keys[i] = ((unsigned long long)(unsigned int)lo[i] << 32) | (unsigned int)hi[i];
+    vals[i] = __float_as_uint(w[i]);
+}
+
+__global__ void __launch_bounds__(TB) k_unpack_edges(const unsigned long long* __restrict__ ends,
+                                                     const uint32_t* __restrict__ wbits, int E,
+                                                     int32_t* __restrict__ lo, int32_t* __restrict__ hi,
+                                                     float* __restrict__ w)
+{
+    const int i = blockIdx.x * TB + threadIdx.x;
+    if (i >= E) return;
+    lo[i] = (int32_t)(ends[i] >> 32);
+    hi[i] = (int32_t)(ends[i] & 0xffffffffull);
+    w[i] = __uint_as_float(wbits[i]);
+}
+
+size_t edge_sort_temp_bytes(int E)
+{
+    size_t a = 0, b = 0;
+    unsigned long long* k64 = nullptr;
+    uint32_t* k32 = nullptr;
+    (void)rocprim::radix_sort_pairs(nullptr, a, k64, k64, k32, k32, (size_t)E, 0, 64, (hipStream_t)0);
+    (void)rocprim::radix_sort_pairs(nullptr, b, k32, k32, k64, k64, (size_t)E, 0, 32, (hipStream_t)0);
+    return ((a > b ? a : b) + 255) & ~(size_t)255;
+}
+
+// Two stable least-significant-digit passes: by (lo, hi), then by the weight bits (non-negative
+// floats order like their bit patterns).
+hipError_t edge_sort(const int32_t* lo, const int32_t* hi, const float* w, int E,
+                     unsigned long long* keys_a, unsigned long long* keys_b,
+                     uint32_t* vals_a, uint32_t* vals_b, void* temp, size_t temp_bytes,
+                     int32_t* out_lo, int32_t* out_hi, float* out_w, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_pack_edges, dim3(blocks_for(E)), dim3(TB), 0, s, lo, hi, w, E, keys_a, vals_a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    size_t tb = temp_bytes;
+    e = rocprim::radix_sort_pairs(temp, tb, keys_a, keys_b, vals_a, vals_b, (size_t)E, 0, 64, s);
+    if (e != hipSuccess) return e;
+    tb = temp_bytes;
+    e = rocprim::radix_sort_pairs(temp, tb, vals_b, vals_a, keys_b, keys_a, (size_t)E, 0, 32, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_unpack_edges, dim3(blocks_for(E)), dim3(TB), 0, s, keys_a, vals_a, E, out_lo, out_hi, out_w);
+    return hipGetLastError();
+}
+
+}  // namespace slhc

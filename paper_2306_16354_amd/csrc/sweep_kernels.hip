@@ -1,0 +1,511 @@
+// Fused distance + selection sweeps for gfx950 (MI355X).
+//
+// One kernel template serves the two nearest-neighbour primitives of the cuSLINK paper:
+//   - fused k-NN      (Sec. 3.1.1, Alg. "Fused k-NN"; epilogues of Appendix A)
+//   - fused 1-NN restricted to points of another colour (Sec. 3.1.2, Alg. "Fused 1-NN")
+//
+// Structure (our own design for 64-wide wavefronts, not the paper's CUDA tiling):
+//   * a workgroup (4 wavefronts) owns a panel of 128 query rows and sweeps all N candidate rows
+//     in tiles of 128; workgroups are persistent and all sweep the candidates in the same order,
+//     so a candidate tile is fetched from HBM about once per XCD and then served by that L2;
+//   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32.  Candidates are the A
+//     operand and queries the B operand, so a lane's 16 accumulators of a 32x32 block belong to
+//     ONE query: the query's threshold is a per-lane scalar;
+//   * the accumulator starts at -h_c with h = (1-c)/2 * ||x||^2, so after the K loop it holds
+//     x_c.x_q - h_c and the filter "expanded distance <= threshold (+ rounding slack)" is the
+//     single compare  acc >= h_q - threshold/2;
+//   * pairs that pass are stream-compacted into a per-wavefront LDS queue (the paper's
+//     compaction step, Sec. 3.1.1), re-evaluated exactly as sum_t (x_qt - x_ct)^2 by 16-lane
+//     groups, and inserted into the query's sorted list in LDS (one list entry per lane).
+//   Each wavefront owns its 32 queries outright (lists, thresholds, queue), so selection needs
+//   no synchronisation between wavefronts and no mutex in global memory (the paper's
+//   multi-block row epilogue, Appendix A, is not needed).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "sweep_kernels.h"
+
+namespace slhc {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int WG_THREADS = 256;
+constexpr int BM = 128;            // query rows per workgroup (32 per wavefront)
+constexpr int BN = 128;            // candidate rows per tile
+constexpr int KC = 32;             // feature columns staged per step
+constexpr int LDK = KC + 4;        // LDS row stride in floats (pad: conflict-free b128 reads)
+constexpr int QCAP = 1024;         // queue entries per wavefront (one 32x32 block can fill it)
+constexpr unsigned long long LIST_SENTINEL = 0x7f8000007fffffffull;   // (+inf, INT_MAX)
+
+__host__ __device__ inline size_t sweep_lds_bytes(int KL)
+{
+    return (size_t)(BM * LDK + BN * LDK + BN /*hc*/ + BN /*ccol*/ + BM /*negg*/ + BM /*qid*/ +
+                    BM /*hq*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
+}
+
+// sum_t (a_t - b_t)^2 over d features by a group of 16 adjacent lanes; every lane of the group
+// returns the total.  Lane g of the group owns features 4g..4g+3 of every 64-wide slab, adds them
+// in ascending t with fused multiply-adds, and the 16 partial sums are combined by an xor
+// butterfly.  (a-b)^2 == (b-a)^2 exactly, so the result is symmetric in its arguments bit for bit.
+template <bool VEC4>
+__device__ inline float group16_sqdist(const float* __restrict__ a, const float* __restrict__ b,
+                                       int d, int g, bool active)
+{
+    float s = 0.f;
+    if (active) {
+        if (VEC4) {
+            for (int t = 4 * g; t < d; t += 64) {
+                const v4f va = *reinterpret_cast<const v4f*>(a + t);
+                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
+                float e;
+                e = va[0] - vb[0]; s = __builtin_fmaf(e, e, s);
+                e = va[1] - vb[1]; s = __builtin_fmaf(e, e, s);
+                e = va[2] - vb[2]; s = __builtin_fmaf(e, e, s);
+                e = va[3] - vb[3]; s = __builtin_fmaf(e, e, s);
+            }
+        } else {
+            for (int t0 = 4 * g; t0 < d; t0 += 64) {
+                const int te = (t0 + 4 < d) ? t0 + 4 : d;
+                for (int t = t0; t < te; ++t) {
+                    const float e = a[t] - b[t];
+                    s = __builtin_fmaf(e, e, s);
+                }
+            }
+        }
+    }
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 4);
+    s += __shfl_xor(s, 8);
+    return s;
+}
+
+// h_i = (1-c)/2 * ||x_i||^2 ; one 16-lane group per row.
+template <bool VEC4>
+__global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict__ X, int N, int d,
+                                                        float scale, float* __restrict__ hn)
+{
+    const int lane16 = threadIdx.x & 15;
+    const long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
+    const bool active = row < N;
+    float s = 0.f;
+    if (active) {
+        const float* x = X + (size_t)row * d;
+        if (VEC4) {
+            for (int t = 4 * lane16; t < d; t += 64) {
+                const v4f v = *reinterpret_cast<const v4f*>(x + t);
+                s = __builtin_fmaf(v[0], v[0], s);
+                s = __builtin_fmaf(v[1], v[1], s);
+                s = __builtin_fmaf(v[2], v[2], s);
+                s = __builtin_fmaf(v[3], v[3], s);
+            }
+        } else {
+            for (int t0 = 4 * lane16; t0 < d; t0 += 64) {
+                const int te = (t0 + 4 < d) ? t0 + 4 : d;
+                for (int t = t0; t < te; ++t) s = __builtin_fmaf(x[t], x[t], s);
+            }
+        }
+    }
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 4);
+    s += __shfl_xor(s, 8);
+    if (active && lane16 == 0) hn[row] = scale * s;
+}
+
+__device__ inline unsigned long long make_key(float dist, int idx)
+{
+    return ((unsigned long long)__float_as_uint(dist) << 32) | (unsigned int)idx;
+}
+
+// Insert `key` into the ascending list of `k` 64-bit keys at `list` (LDS), dropping the last
+// entry; executed by a whole wavefront, lane l holding entry l.  Returns without change when the
+// key does not precede the last entry.  On change, the query's filter bound is refreshed:
+// bound = h_q - worst/2.
+__device__ inline void wave_list_insert(unsigned long long* list, int k, unsigned long long key,
+                                        float hq, float* bound_slot, int lane)
+{
+    const unsigned long long worst = list[k - 1];
+    if (key >= worst) return;
+    const unsigned long long old = (lane < k) ? list[lane] : ~0ull;
+    const bool less = (lane < k) && (old < key);
+    const int pos = __popcll(__ballot(less));
+    if (lane >= pos && lane < k - 1) list[lane + 1] = old;
+    if (lane == pos) list[pos] = key;
+    unsigned int hi;
+    if (pos == k - 1) {
+        hi = (unsigned int)(key >> 32);
+    } else {
+        hi = (unsigned int)__builtin_amdgcn_readlane((int)(old >> 32), k - 2);
+    }
+    if (lane == 0) *bound_slot = hq - 0.5f * __uint_as_float(hi);
+}
+
+// LDS layout of a sweep workgroup (dynamic shared memory).
+template <int KL>
+struct SweepLds {
+    float* Qs; float* Cs; float* hcs; int* ccol; float* bounds; int* qid; float* hqs;
+    unsigned long long* lists; unsigned short* queues;
+    __device__ explicit SweepLds(unsigned char* base)
+    {
+        Qs = reinterpret_cast<float*>(base);
+        Cs = Qs + BM * LDK;
+        hcs = Cs + BN * LDK;
+        ccol = reinterpret_cast<int*>(hcs + BN);
+        bounds = reinterpret_cast<float*>(ccol + BN);
+        qid = reinterpret_cast<int*>(bounds + BM);
+        hqs = reinterpret_cast<float*>(qid + BM);
+        lists = reinterpret_cast<unsigned long long*>(hqs + BM);
+        queues = reinterpret_cast<unsigned short*>(lists + BM * KL);
+    }
+};
+
+extern __shared__ __align__(16) unsigned char sweep_smem[];
+
+// Rare path of the tile epilogue for one 32x32 block of a wavefront (a real call, so that its
+// registers do not weigh on the multiply loop): compact the pairs that pass the filter into the
+// wavefront's queue, re-evaluate each exactly, insert into the query lists, refresh the bounds.
+// `t` holds the block's accumulators, `tag` the lane's query row (k-NN: to skip itself) or the
+// lane's query colour (cross-colour 1-NN: to skip its own component).  Returns the number of
+// pairs compacted (lane 0 only, 0 elsewhere).
+template <int KL, bool MASKED, bool VEC4>
+__device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
+                                                               int col0, const float* __restrict__ X,
+                                                               int N, int d, int k)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int lhalf = lane >> 5;
+    unsigned short* myq = L.queues + wave * QCAP;
+    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
+    int qcount = 0;
+    const bool real_query = L.qid[wave * 32 + l32] >= 0;    // padding rows of the last panel
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+        const int cg = col0 + cl;
+        bool pred = real_query && (t[r] >= bound) && (cg < N);
+        if (MASKED) pred = pred && (L.ccol[cl] != tag);
+        else pred = pred && (cg != tag);
+        const unsigned long long mask = __ballot(pred);
+        if (mask) {
+            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+            if (pred) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
+            qcount += __popcll(mask);
+        }
+    }
+    if (qcount == 0) return 0u;
+    __builtin_amdgcn_wave_barrier();
+    // exact re-evaluation, four queued pairs per pass (16 lanes each)
+    const int grp = lane >> 4, g16 = lane & 15;
+    for (int s = 0; s < qcount; s += 4) {
+        const int e = s + grp;
+        const bool valid = e < qcount;
+        const unsigned int ent = valid ? myq[e] : 0u;
+        const int ql = (int)(ent >> 8);
+        const int cg = col0 + (int)(ent & 255u);
+        const int qrow = L.qid[wave * 32 + ql];
+        const float* xa = X + (size_t)(valid ? qrow : 0) * d;
+        const float* xb = X + (size_t)(valid ? cg : 0) * d;
+        const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
+        const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
+        for (int g = 0; g < npass; ++g) {
+            const float dg = __shfl(dist, g * 16);
+            const int qlg = __shfl(ql, g * 16);
+            const int cgg = __shfl(cg, g * 16);
+            wave_list_insert(mylists + (size_t)qlg * KL, k, make_key(dg, cgg),
+                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    return lane == 0 ? (unsigned int)qcount : 0u;
+}
+
+template <int KL, bool MASKED, bool VEC4>
+__global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
+{
+    const SweepLds<KL> L(sweep_smem);
+    float* Qs = L.Qs; float* Cs = L.Cs; float* hcs = L.hcs; int* ccol = L.ccol;
+    float* bounds = L.bounds; int* qid = L.qid; float* hqs = L.hqs;
+    unsigned long long* lists = L.lists;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int lhalf = lane >> 5;
+    const int N = p.N, d = p.d, k = p.k;
+    const float* __restrict__ X = p.X;
+    const float* __restrict__ hn = p.hn;
+    const int nq = MASKED ? p.m : N;
+    const int npanels = (nq + BM - 1) / BM;
+    const int ntiles = (N + BN - 1) / BN;
+    const int nchunks = (d + KC - 1) / KC;
+    const int ld_row = tid >> 3;          // 0..31 (+32 i)
+    const int ld_col = (tid & 7) * 4;     // 0..28
+    unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
+    unsigned long long survivors = 0;
+
+    for (int panel = blockIdx.x; panel < npanels; panel += gridDim.x) {
+        __syncthreads();          // previous panel fully written out before its state is reused
+        if (tid < BM) {
+            const int qi = panel * BM + tid;
+            int row = -1;
+            if (qi < nq) row = (MASKED && p.rows) ? p.rows[qi] : qi;
+            if ((unsigned int)row >= (unsigned int)N) row = -1;      // never index X with a bad row
+            qid[tid] = row;
+            hqs[tid] = row >= 0 ? hn[row] : 0.f;
+            bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
+        }
+        for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
+        __syncthreads();
+
+        // Element offsets of the rows this thread stages.  Rows past the end are clamped to a
+        // valid row: such queries carry a +inf bound and such candidates a +inf h, so whatever
+        // is multiplied for them can never pass the filter.
+        unsigned int qoff[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = qid[ld_row + 32 * i];
+            qoff[i] = (unsigned int)(r >= 0 ? r : 0) * (unsigned int)d;
+        }
+        const int my_q_local = wave * 32 + l32;
+        const int my_qrow = qid[my_q_local];
+        int my_qcol = -1;
+        if (MASKED) my_qcol = my_qrow >= 0 ? p.colour[my_qrow] : -1;
+        float bound = bounds[my_q_local];
+
+        v4f qreg[4], creg[4];
+        float hreg = 0.f;
+        int colreg = 0;
+        auto gload = [&](int tile, int chunk) {
+            const int col = chunk * KC + ld_col;
+            const int crow0 = tile * BN + ld_row;
+            if (VEC4) {
+                const bool live = col < d;
+                const unsigned int c0 = live ? (unsigned int)col : 0u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int crow = crow0 + 32 * i;
+                    crow = crow < N ? crow : N - 1;
+                    qreg[i] = *reinterpret_cast<const v4f*>(X + (qoff[i] + c0));
+                    creg[i] = *reinterpret_cast<const v4f*>(X + ((unsigned int)crow * (unsigned int)d + c0));
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int crow = crow0 + 32 * i;
+                    crow = crow < N ? crow : N - 1;
+                    v4f q, c;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool live = col + e < d;
+                        const unsigned int ce = live ? (unsigned int)(col + e) : 0u;
+                        q[e] = X[qoff[i] + ce];
+                        c[e] = X[(unsigned int)crow * (unsigned int)d + ce];
+                    }
+                    qreg[i] = q;
+                    creg[i] = c;
+                }
+            }
+            if (chunk == 0 && tid < BN) {
+                const int crow = tile * BN + tid;
+                const int cr = crow < N ? crow : N - 1;
+                hreg = hn[cr];
+                if (MASKED) colreg = p.colour[cr];
+            }
+        };
+
+        v16f acc[4];
+        gload(0, 0);
+        for (int tile = 0; tile < ntiles; ++tile) {
+            const int col0 = tile * BN;
+            for (int chunk = 0; chunk < nchunks; ++chunk) {
+                __syncthreads();                       // everyone is done reading the staged step
+                // values staged past the last feature column are loaded from a clamped address
+                // and zeroed here, at the point of use, so the loads stay in flight until now
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v4f q = qreg[i], c = creg[i];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool live = chunk * KC + ld_col + (VEC4 ? 0 : e) < d;
+                        q[e] = live ? q[e] : 0.f;
+                        c[e] = live ? c[e] : 0.f;
+                    }
+                    *reinterpret_cast<v4f*>(Qs + (ld_row + 32 * i) * LDK + ld_col) = q;
+                    *reinterpret_cast<v4f*>(Cs + (ld_row + 32 * i) * LDK + ld_col) = c;
+                }
+                if (chunk == 0 && tid < BN) {
+                    const bool in_range = tile * BN + tid < N;
+                    hcs[tid] = in_range ? hreg : __builtin_inff();
+                    if (MASKED) ccol[tid] = in_range ? colreg : -1;
+                }
+                __syncthreads();
+                // prefetch the next step into registers while this one is multiplied
+                {
+                    int nt = tile, nc = chunk + 1;
+                    if (nc == nchunks) { nc = 0; nt = tile + 1; }
+                    if (nt < ntiles) gload(nt, nc);
+                }
+                if (chunk == 0) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const v4f h = *reinterpret_cast<const v4f*>(hcs + b * 32 + 8 * g + 4 * lhalf);
+                            acc[b][4 * g + 0] = -h[0];
+                            acc[b][4 * g + 1] = -h[1];
+                            acc[b][4 * g + 2] = -h[2];
+                            acc[b][4 * g + 3] = -h[3];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int kk = 0; kk < KC / 8; ++kk) {
+                    const v4f qf = *reinterpret_cast<const v4f*>(Qs + my_q_local * LDK + kk * 8 + 4 * lhalf);
+                    v4f cf[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        cf[b] = *reinterpret_cast<const v4f*>(Cs + (b * 32 + l32) * LDK + kk * 8 + 4 * lhalf);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(cf[b][e], qf[e], acc[b], 0, 0, 0);
+                    }
+                }
+            }
+
+            // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
+            unsigned int flagged = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                bool any = false;
+                if (MASKED) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int4 cc = *reinterpret_cast<const int4*>(ccol + b * 32 + 8 * g + 4 * lhalf);
+                        any |= (acc[b][4 * g + 0] >= bound) & (cc.x != my_qcol);
+                        any |= (acc[b][4 * g + 1] >= bound) & (cc.y != my_qcol);
+                        any |= (acc[b][4 * g + 2] >= bound) & (cc.z != my_qcol);
+                        any |= (acc[b][4 * g + 3] >= bound) & (cc.w != my_qcol);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) any |= (acc[b][r] >= bound);
+                }
+                if (__any(any)) flagged |= 1u << b;
+            }
+            if (__builtin_expect(flagged != 0, 0)) {
+                const int my_tag = MASKED ? my_qcol : my_qrow;
+                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, X, N, d, k);
+                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, X, N, d, k);
+                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, X, N, d, k);
+                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, X, N, d, k);
+                bound = bounds[my_q_local];
+            }
+        }
+
+        // ---- panel epilogue: lists are already ascending; write them out ----
+        __builtin_amdgcn_wave_barrier();
+        for (int ql = 0; ql < 32; ++ql) {
+            const int row = qid[wave * 32 + ql];
+            if (row < 0) continue;
+            if (lane < k) {
+                const unsigned long long key = mylists[(size_t)ql * KL + lane];
+                const float dist = __uint_as_float((unsigned int)(key >> 32));
+                int idx = (int)(unsigned int)(key & 0xffffffffull);
+                if (key == LIST_SENTINEL) idx = -1;
+                const size_t o = MASKED ? (size_t)(panel * BM + wave * 32 + ql)
+                                        : (size_t)row * k + lane;
+                p.out_idx[o] = idx;
+                p.out_dist[o] = dist;
+            }
+        }
+    }
+    if (p.survivors && lane == 0 && survivors) atomicAdd(p.survivors, survivors);
+}
+
+// ------------------------------------------------------------------------------- launchers
+static int g_num_cu = 0;
+
+static hipError_t device_cus(int* cus)
+{
+    if (g_num_cu == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        g_num_cu = v > 0 ? v : 1;
+    }
+    *cus = g_num_cu;
+    return hipSuccess;
+}
+
+float filter_slack_coefficient(int d)
+{
+    // The accumulator is a chain of d+1 round-to-nearest fused multiply-adds whose partial sums
+    // are bounded by ||x_q||^2 + ||x_c||^2, so it is off by at most (d+1) 2^-24 (n_q + n_c);
+    // the filter has c (n_q + n_c)/2 of slack.  c = (d+8) 2^-23 covers that chain plus the
+    // roundings of the norms, of h and of the bound.
+    return (float)(d + 8) * 1.1920928955078125e-07f;
+}
+
+hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream)
+{
+    const float scale = 0.5f * (1.0f - filter_slack_coefficient(d));
+    const long long threads = (long long)N * 16;
+    const int blocks = (int)((threads + 255) / 256);
+    const bool vec4 = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn);
+    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn);
+    return hipGetLastError();
+}
+
+template <int KL, bool MASKED>
+static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
+{
+    int cus = 0;
+    hipError_t e = device_cus(&cus);
+    if (e != hipSuccess) return e;
+    const int nq = MASKED ? p.m : p.N;
+    const int npanels = (nq + BM - 1) / BM;
+    const size_t lds = sweep_lds_bytes(KL);
+    const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+    int grid = cus * per_cu;
+    if (grid > npanels) grid = npanels;
+    const bool vec4 = (p.d % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    if (vec4) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_kernel<KL, MASKED, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((sweep_kernel<KL, MASKED, true>), dim3(grid), dim3(WG_THREADS), lds, stream, p);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_kernel<KL, MASKED, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((sweep_kernel<KL, MASKED, false>), dim3(grid), dim3(WG_THREADS), lds, stream, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream)
+{
+    if (p.k <= 8) return launch_sweep_t<8, false>(p, stream);
+    if (p.k <= 16) return launch_sweep_t<16, false>(p, stream);
+    if (p.k <= 32) return launch_sweep_t<32, false>(p, stream);
+    return launch_sweep_t<64, false>(p, stream);
+}
+
+hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream)
+{
+    return launch_sweep_t<1, true>(p, stream);
+}
+
+}  // namespace slhc
