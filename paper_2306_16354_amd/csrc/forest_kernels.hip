@@ -39,12 +39,12 @@ __device__ inline void report(const ForestState& f, int site) { atomicCAS(&f.cou
 __global__ void __launch_bounds__(TB) k_forest_init(ForestState f)
 {
     const int v = blockIdx.x * TB + threadIdx.x;
+    if (v < 4) f.counters[v] = 0;          // before the range test: N may be smaller than 4
     if (v >= f.N) return;
     f.colour[v] = v;
     f.ptr[v] = 0;
     f.ext_idx[v] = -1;
     f.ext_dist[v] = 0.f;
-    if (v < 4) f.counters[v] = 0;
 }
 
 __global__ void __launch_bounds__(TB) k_round_reset(ForestState f)

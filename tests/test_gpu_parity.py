@@ -213,11 +213,23 @@ def test_cross_1nn_single_colour_and_all_rows(lib):
 
 # ----------------------------------------------------------------------------- MST + dendrogram
 def cluster_signatures(children, N, seed=0):
-    """Order-independent description of a hierarchy: one 64-bit sum-hash per merged cluster."""
-    h = np.random.default_rng(seed).integers(1, 2 ** 62, size=2 * N - 1, dtype=np.int64)
-    for i, (a, b) in enumerate(children):
-        h[N + i] = h[a] + h[b]              # wraps; fine for a signature
-    return np.sort(h[N:])
+    """One 64-bit sum-hash per merged cluster (independent of the order of the merges)."""
+    h = np.random.default_rng(seed).integers(1, 2 ** 62, size=2 * N - 1, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        for i, (a, b) in enumerate(children):
+            h[N + i] = h[a] + h[b]          # wraps modulo 2^64; fine for a signature
+    return h[N:]
+
+
+def isolated_heights(heights, rtol):
+    """True where a merge height has no neighbour (in sorted order) within the tolerance band:
+    only there is the cluster formed by the merge uniquely defined across arithmetic."""
+    h = np.asarray(heights, dtype=np.float64)
+    gap_ok = np.ones(h.size, dtype=bool)
+    near = np.abs(np.diff(h)) <= rtol * np.maximum(np.abs(h[1:]), np.abs(h[:-1]))
+    gap_ok[1:] &= ~near
+    gap_ok[:-1] &= ~near
+    return gap_ok
 
 
 def check_slhc(X, out, tie_free):
@@ -254,11 +266,19 @@ def check_slhc(X, out, tie_free):
     assert (children[:, 0] < children[:, 1]).all()
     assert (children < (N + np.arange(N - 1))[:, None]).all()
     if tie_free:
-        assert np.array_equal(cluster_signatures(children, N), cluster_signatures(ref["children"], N))
-        assert np.array_equal(np.sort(sizes), np.sort(ref["sizes"]))
-        same = {(a, b) for a, b in zip(src.tolist(), dst.tolist())} == \
-               {(a, b) for a, b in zip(ref["src"].tolist(), ref["dst"].tolist())}
-        assert same, "edge set differs from the oracle's on tie-free data"
+        # Topology: every cluster that the oracle forms at a height with no near-tie next to it
+        # must be formed by the GPU hierarchy too, and the other way round.  (Two merges whose
+        # heights differ by less than float32 resolves may legitimately swap.)
+        sig_g, sig_o = cluster_signatures(children, N), cluster_signatures(ref["children"], N)
+        # band: a few float32 ulps, the accuracy of a directly summed squared distance
+        iso_o, iso_g = isolated_heights(ref["heights"], 1e-6), isolated_heights(heights, 1e-6)
+        assert iso_o.mean() > 0.9
+        assert np.isin(sig_o[iso_o], sig_g).all(), "an oracle cluster is missing from the GPU hierarchy"
+        assert np.isin(sig_g[iso_g], sig_o).all(), "a GPU cluster is missing from the oracle hierarchy"
+        assert np.array_equal(np.sort(sizes[iso_g & iso_o]), np.sort(ref["sizes"][iso_g & iso_o]))
+        eg = {(a, b) for a, b in zip(src.tolist(), dst.tolist())}
+        eo = {(a, b) for a, b in zip(ref["src"].tolist(), ref["dst"].tolist())}
+        assert len(eg ^ eo) <= 2 * max(1, (~iso_o).sum()), "edge set differs from the oracle's beyond near-ties"
     return out["stats"]
 
 
