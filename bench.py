@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the single-linkage hot path on one MI355X.
+
+A step is one pass of the whole path (half norms, fused MFMA k-NN sweep, Boruvka forest with
+cross-component 1-NN connection, edge sort, host dendrogram) over one synthetic workload that is
+already resident in HBM.  Prints ONE JSON line:
+
+  value      fused k-NN distance pairs per second = N^2 / (norm kernel + k-NN sweep kernel time),
+             kernel times taken with HIP events on the launch stream inside every timed step
+  ms_per_step   wall time of the whole step (the end-to-end single-linkage seconds x 1000)
+  roofline   the fused k-NN sweep against the fp32 MFMA peak (2*d FLOP per ordered pair)
+  cpu_baseline  the CPU oracle's brute-force k-NN on a bounded sample of query rows
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--rows", type=int, default=None, help="scale the workload to this many rows")
+    ap.add_argument("--knn-only", action="store_true", help="time slhc_knn_graph alone (kernel study)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here shards across "
+              "GPUs, see DESIGN.md for how the path would)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2306_16354_amd as slhc
+    import slhc_inputs as gen
+
+    if not os.path.exists(slhc.library_path()):
+        from paper_2306_16354_amd import build as libbuild
+        libbuild.build_library(verbose=False)
+    slhc.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    X, _, k = gen.make(args.workload, n=args.rows)
+    N, d = X.shape
+    gen_s = time.time() - t0
+    Xd = torch.from_numpy(X).to(dev)
+    torch.cuda.synchronize()
+
+    ws = torch.empty(slhc.slhc_workspace_bytes(N, d, k), dtype=torch.uint8, device=dev)
+    out = None
+    knn_out = None
+
+    def step():
+        nonlocal out, knn_out
+        if args.knn_only:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            knn_out = slhc.knn_graph(Xd, k, out=knn_out, workspace=ws)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            return dict(ms_knn_kernel=ms, ms_norm_kernel=0.0)
+        out = slhc.slhc(Xd, k, workspace=ws, out=out)
+        return out["stats"]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    stats = []
+    for _ in range(args.steps):
+        stats.append(step())
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_begin) * 1e3 / max(1, args.steps)
+
+    def mean(name):
+        return float(np.mean([s[name] for s in stats]))
+
+    knn_kernel_ms = mean("ms_knn_kernel")
+    knn_ms = knn_kernel_ms + mean("ms_norm_kernel")
+    pairs = float(N) * float(N)
+    value = pairs / (knn_ms * 1e-3)
+    flops = 2.0 * d * pairs
+    achieved_tflops = flops / (knn_kernel_ms * 1e-3) / 1e12
+
+    line = {
+        "metric": "fused kNN distance pairs/s (+ % FP32-MFMA peak; end-to-end SLHC seconds in slhc_seconds)",
+        "value": value,
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}: N={N} d={d} k={k} squared-L2 "
+                        + ("fused k-NN graph only" if args.knn_only else
+                           "k-NN graph + Boruvka/connect MST + sort + dendrogram"),
+            "step": "slhc_knn_graph" if args.knn_only else "slhc_slhc (whole hot path)",
+            "N": N, "d": d, "k": k,
+        },
+        "slhc_seconds": None if args.knn_only else ms_per_step / 1e3,
+        "pct_fp32_mfma_peak": 100.0 * achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
+        "roofline": {
+            "kernel": "sweep_kernel (fused distance tile + filter + top-k)",
+            "bound": "mfma",
+            "achieved": achieved_tflops,
+            "peak": PEAK_FP32_MFMA_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
+            "traffic": None,
+            "launch_ms": knn_kernel_ms,
+            "algorithmic_flop_per_launch": flops,
+        },
+        "input_generation_s": gen_s,
+    }
+    if not args.knn_only:
+        line["stages_ms"] = {n: mean(n) for n in ("ms_knn", "ms_norm_kernel", "ms_knn_kernel", "ms_boruvka",
+                                                  "ms_connect", "ms_connect_kernels", "ms_sort",
+                                                  "ms_dendrogram", "ms_total")}
+        s0 = stats[-1]
+        line["counters"] = {n: int(s0[n]) for n in ("boruvka_rounds", "connect_rounds", "components_after_knn",
+                                                    "knn_filter_survivors", "connect_query_rows",
+                                                    "connect_filter_survivors")}
+        cq = float(s0["connect_query_rows"])
+        if cq > 0 and mean("ms_connect_kernels") > 0:
+            ct = 2.0 * d * cq * N / (mean("ms_connect_kernels") * 1e-3) / 1e12
+            line["roofline_connect"] = {"kernel": "sweep_kernel (cross-component 1-NN)", "bound": "mfma",
+                                        "achieved": ct, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                                        "frac": ct / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
+
+    if not args.no_cpu_baseline:
+        import oracle                                     # cpu_baseline leg only
+        oracle.build()
+        rng = np.random.default_rng(12345)
+        m = args.cpu_sample_rows
+        if m is None:                                     # size the sample for about 12 s of CPU work
+            probe = rng.choice(N, size=min(N, 64), replace=False).astype(np.int64)
+            p0 = time.perf_counter()
+            oracle.knn_rows(X, probe, k)
+            per_row = (time.perf_counter() - p0) / probe.size
+            m = int(max(64, min(N, 12.0 / max(per_row, 1e-9))))
+        rows = rng.choice(N, size=min(m, N), replace=False).astype(np.int64)
+        c0 = time.perf_counter()
+        oracle.knn_rows(X, rows, k)
+        c1 = time.perf_counter()
+        line["cpu_baseline"] = {
+            "value": rows.size * float(N) / (c1 - c0),
+            "unit": "pairs/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"fp64 brute-force k-NN of {rows.size} seeded query rows against all {N} rows "
+                      f"of the same workload ({c1 - c0:.1f} s)",
+        }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -57,12 +57,16 @@ typedef struct slhc_stats {
     int64_t knn_filter_survivors;    /* pairs that passed the MFMA filter in the k-NN sweep        */
     int64_t connect_query_rows;      /* sum over connection rounds of queried rows                 */
     int64_t connect_filter_survivors;
-    float ms_knn;                    /* norms + fused k-NN                                         */
+    float ms_knn;                    /* norms + fused k-NN (host clock, includes the sync)         */
     float ms_boruvka;                /* all min-edge / commit / relabel kernels                    */
     float ms_connect;                /* all cross-component 1-NN sweeps                            */
     float ms_sort;                   /* edge sort                                                  */
     float ms_dendrogram;             /* device->host copy, host union-find, host->device copy      */
     float ms_total;
+    float ms_norm_kernel;            /* HIP-event time of the half-norm kernel                     */
+    float ms_knn_kernel;             /* HIP-event time of the fused k-NN sweep kernel alone        */
+    float ms_connect_kernels;        /* HIP-event time summed over the cross-component 1-NN sweeps */
+    float reserved1;
 } slhc_stats;
 
 int slhc_abi_version(void);

@@ -25,6 +25,8 @@ class _Stats(ctypes.Structure):
         ("connect_filter_survivors", ctypes.c_int64),
         ("ms_knn", ctypes.c_float), ("ms_boruvka", ctypes.c_float), ("ms_connect", ctypes.c_float),
         ("ms_sort", ctypes.c_float), ("ms_dendrogram", ctypes.c_float), ("ms_total", ctypes.c_float),
+        ("ms_norm_kernel", ctypes.c_float), ("ms_knn_kernel", ctypes.c_float),
+        ("ms_connect_kernels", ctypes.c_float), ("reserved1", ctypes.c_float),
     ]
 
 
@@ -137,16 +139,17 @@ def cross_1nn(X, colour, rows=None, m=None):
     return idx, dist
 
 
-def slhc(X, k, workspace=None):
+def slhc(X, k, workspace=None, out=None):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
-    (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict)."""
+    (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
+    ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory."""
     X = _device_matrix(X)
     N, d = X.shape
     lib = load_library()
     if workspace is None:
         workspace = _workspace(slhc_workspace_bytes(N, d, k), X.device)
     dev = X.device
-    out = dict(
+    out = out if out is not None else dict(
         mst_src=torch.empty(N - 1, dtype=torch.int32, device=dev),
         mst_dst=torch.empty(N - 1, dtype=torch.int32, device=dev),
         mst_w=torch.empty(N - 1, dtype=torch.float32, device=dev),
@@ -159,5 +162,5 @@ def slhc(X, k, workspace=None):
                          out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
                          out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
                          workspace.numel(), _stream()))
-    out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if name != "reserved0"}
+    out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out

@@ -73,6 +73,21 @@ __global__ void k_zero_words(uint32_t* p, int n)
     if (i < n) p[i] = 0u;
 }
 
+// Pinned host staging for device<->host copies (freed when the call returns).
+struct PinnedHost {
+    void* p = nullptr;
+    hipError_t alloc(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
+    ~PinnedHost() { if (p) (void)hipHostFree(p); }
+};
+
+// A pair of HIP events bracketing work on a stream.
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create() { hipError_t e = hipEventCreate(&a); return e != hipSuccess ? e : hipEventCreate(&b); }
+    ~EventPair() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+    float ms() const { float t = 0.f; return hipEventElapsedTime(&t, a, b) == hipSuccess ? t : -1.f; }
+};
+
 struct KnnWs {
     unsigned long long* survivors;
     float* hn;
@@ -117,28 +132,26 @@ struct SlhcWs {
 };
 
 int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
-            void* workspace, hipStream_t stream, unsigned long long** survivors_out)
+            void* workspace, hipStream_t stream, unsigned long long** survivors_out,
+            EventPair* ev_norm = nullptr, EventPair* ev_sweep = nullptr)
 {
     KnnWs ws(workspace, N);
     hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(ws.survivors), 64);
     HIP_TRY(hipGetLastError());
+    if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->a, stream));
     HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn, stream));
+    if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->b, stream));
+    if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->a, stream));
     slhc::SweepParams p{};
     p.X = X; p.hn = ws.hn; p.N = (int)N; p.d = d; p.k = k;
     p.out_idx = nbr_idx; p.out_dist = nbr_dist;
     p.colour = nullptr; p.rows = nullptr; p.m = 0;
     p.survivors = ws.survivors;
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
+    if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));
     if (survivors_out) *survivors_out = ws.survivors;
     return SLHC_OK;
 }
-
-// Pinned host staging for device<->host copies (freed when the call returns).
-struct PinnedHost {
-    void* p = nullptr;
-    hipError_t alloc(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
-    ~PinnedHost() { if (p) (void)hipHostFree(p); }
-};
 
 double now_ms()
 {
@@ -278,7 +291,11 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
 
     // ---- k-NN graph (Alg. "cuSLINK Algorithm", first step)
     unsigned long long* d_surv = nullptr;
-    rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, ws.knn_ws, s, &d_surv);
+    EventPair ev_norm, ev_knn, ev_conn;
+    HIP_TRY(ev_norm.create());
+    HIP_TRY(ev_knn.create());
+    HIP_TRY(ev_conn.create());
+    rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, ws.knn_ws, s, &d_surv, &ev_norm, &ev_knn);
     if (rc != SLHC_OK) return rc;
     PinnedHost pin_surv;
     HIP_TRY(pin_surv.alloc(64));
@@ -286,6 +303,8 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
     HIP_TRY(hipMemcpyAsync(h_surv, d_surv, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     st.knn_filter_survivors = (int64_t)h_surv[0];
+    st.ms_norm_kernel = ev_norm.ms();
+    st.ms_knn_kernel = ev_knn.ms();
     const double t_knn = now_ms();
     st.ms_knn = (float)(t_knn - t_begin);
 
@@ -329,9 +348,12 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
             p.out_idx = ws.q_idx; p.out_dist = ws.q_dist;
             p.colour = ws.colour; p.rows = ws.qlist; p.m = nq;
             p.survivors = kws.survivors + 1;
+            HIP_TRY(hipEventRecord(ev_conn.a, s));
             HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
+            HIP_TRY(hipEventRecord(ev_conn.b, s));
             HIP_TRY(slhc::forest_apply_queries(f, ws.q_idx, ws.q_dist, nq, s));
             HIP_TRY(hipStreamSynchronize(s));
+            st.ms_connect_kernels += ev_conn.ms();
             ms_connect += now_ms() - tc0;
         }
         HIP_TRY(slhc::forest_select_edges(f, s));
