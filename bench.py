@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--rows", type=int, default=None, help="scale the workload to this many rows")
     ap.add_argument("--knn-only", action="store_true", help="time slhc_knn_graph alone (kernel study)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy three times and exit (reference for HBM counters)")
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -56,6 +58,15 @@ def main():
     slhc.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": a.numel() * 4, "bytes_written": a.numel() * 4, "repeats": 3}))
+        return
 
     t0 = time.time()
     X, _, k = gen.make(args.workload, n=args.rows)
