@@ -39,7 +39,7 @@ constexpr unsigned long long LIST_SENTINEL = 0x7f8000007fffffffull;   // (+inf, 
 
 __host__ __device__ inline size_t sweep_lds_bytes(int KL)
 {
-    return (size_t)(BM * LDK + BN * LDK + BN /*hc*/ + BN /*ccol*/ + BM /*negg*/ + BM /*qid*/ +
+    return (size_t)(BM * LDK + BN * LDK + 2 * BN /*hc*/ + 2 * BN /*ccol*/ + BM /*bounds*/ + BM /*qid*/ +
                     BM /*hq*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
 }
 
@@ -150,9 +150,9 @@ struct SweepLds {
     {
         Qs = reinterpret_cast<float*>(base);
         Cs = Qs + BM * LDK;
-        hcs = Cs + BN * LDK;
-        ccol = reinterpret_cast<int*>(hcs + BN);
-        bounds = reinterpret_cast<float*>(ccol + BN);
+        hcs = Cs + BN * LDK;                                  // two buffers of BN (tile parity)
+        ccol = reinterpret_cast<int*>(hcs + 2 * BN);          // two buffers of BN
+        bounds = reinterpret_cast<float*>(ccol + 2 * BN);
         qid = reinterpret_cast<int*>(bounds + BM);
         hqs = reinterpret_cast<float*>(qid + BM);
         lists = reinterpret_cast<unsigned long long*>(hqs + BM);
@@ -170,10 +170,12 @@ extern __shared__ __align__(16) unsigned char sweep_smem[];
 // pairs compacted (lane 0 only, 0 elsewhere).
 template <int KL, bool MASKED, bool VEC4>
 __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
-                                                               int col0, const float* __restrict__ X,
+                                                               int col0, int colbuf,
+                                                               const float* __restrict__ X,
                                                                int N, int d, int k)
 {
     const SweepLds<KL> L(sweep_smem);
+    const int* ccol = L.ccol + colbuf * BN;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int l32 = lane & 31;
@@ -187,7 +189,7 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
         const int cg = col0 + cl;
         bool pred = real_query && (t[r] >= bound) && (cg < N);
-        if (MASKED) pred = pred && (L.ccol[cl] != tag);
+        if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
         const unsigned long long mask = __ballot(pred);
         if (mask) {
@@ -402,10 +404,204 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
             }
             if (__builtin_expect(flagged != 0, 0)) {
                 const int my_tag = MASKED ? my_qcol : my_qrow;
-                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, X, N, d, k);
-                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, X, N, d, k);
-                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, X, N, d, k);
-                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, X, N, d, k);
+                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, 0, X, N, d, k);
+                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, 0, X, N, d, k);
+                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, 0, X, N, d, k);
+                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, 0, X, N, d, k);
+                bound = bounds[my_q_local];
+            }
+        }
+
+        // ---- panel epilogue: lists are already ascending; write them out ----
+        __builtin_amdgcn_wave_barrier();
+        for (int ql = 0; ql < 32; ++ql) {
+            const int row = qid[wave * 32 + ql];
+            if (row < 0) continue;
+            if (lane < k) {
+                const unsigned long long key = mylists[(size_t)ql * KL + lane];
+                const float dist = __uint_as_float((unsigned int)(key >> 32));
+                int idx = (int)(unsigned int)(key & 0xffffffffull);
+                if (key == LIST_SENTINEL) idx = -1;
+                const size_t o = MASKED ? (size_t)(panel * BM + wave * 32 + ql)
+                                        : (size_t)row * k + lane;
+                p.out_idx[o] = idx;
+                p.out_dist[o] = dist;
+            }
+        }
+    }
+    if (p.survivors && lane == 0 && survivors) atomicAdd(p.survivors, survivors);
+}
+
+// Variant for d <= 128 (d a multiple of 4): the query fragments of the MFMA B operand stay in
+// registers for the whole sweep (DCH chunks of 32 columns -> 16*DCH registers per lane), so the
+// query panel is read from memory once per panel instead of once per candidate tile, and LDS only
+// stages candidates.  Candidate chunks are double-buffered in LDS (the buffer the streaming
+// variant uses for queries is the second candidate buffer), which leaves ONE barrier per chunk:
+// a wavefront can only overwrite buffer s&1 at step s+2 after every wavefront has passed the
+// barrier of step s+1, i.e. has finished multiplying step s.  The per-tile candidate half norms
+// and colours are double-buffered by tile parity for the same reason.
+template <int KL, bool MASKED, int DCH>
+__global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
+{
+    const SweepLds<KL> L(sweep_smem);
+    float* bounds = L.bounds; int* qid = L.qid; float* hqs = L.hqs;
+    unsigned long long* lists = L.lists;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int lhalf = lane >> 5;
+    const int N = p.N, d = p.d, k = p.k;
+    const float* __restrict__ X = p.X;
+    const float* __restrict__ hn = p.hn;
+    const int nq = MASKED ? p.m : N;
+    const int npanels = (nq + BM - 1) / BM;
+    const int ntiles = (N + BN - 1) / BN;
+    const int ld_row = tid >> 3;          // 0..31 (+32 i)
+    const int ld_col = (tid & 7) * 4;     // 0..28
+    unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
+    unsigned long long survivors = 0;
+
+    for (int panel = blockIdx.x; panel < npanels; panel += gridDim.x) {
+        __syncthreads();          // previous panel fully written out before its state is reused
+        if (tid < BM) {
+            const int qi = panel * BM + tid;
+            int row = -1;
+            if (qi < nq) row = (MASKED && p.rows) ? p.rows[qi] : qi;
+            if ((unsigned int)row >= (unsigned int)N) row = -1;      // never index X with a bad row
+            qid[tid] = row;
+            hqs[tid] = row >= 0 ? hn[row] : 0.f;
+            bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
+        }
+        for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
+        __syncthreads();
+
+        const int my_q_local = wave * 32 + l32;
+        const int my_qrow = qid[my_q_local];
+        int my_qcol = -1;
+        if (MASKED) my_qcol = my_qrow >= 0 ? p.colour[my_qrow] : -1;
+        float bound = bounds[my_q_local];
+
+        // query fragments: lane (l32, lhalf) holds columns kk*8 + 4*lhalf .. +3 of its query row
+        v4f qf[DCH * 4];
+        {
+            const unsigned int qo = (unsigned int)(my_qrow >= 0 ? my_qrow : 0) * (unsigned int)d;
+#pragma unroll
+            for (int kk = 0; kk < DCH * 4; ++kk) {
+                const int col = kk * 8 + 4 * lhalf;
+                const bool live = col < d;
+                const v4f v = *reinterpret_cast<const v4f*>(X + (qo + (live ? (unsigned int)col : 0u)));
+                qf[kk] = live ? v : v4f{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+
+        v4f creg[4];
+        float hreg = 0.f;
+        int colreg = 0;
+        auto gload = [&](int tile, int chunk) {
+            const int col = chunk * KC + ld_col;
+            const unsigned int c0 = col < d ? (unsigned int)col : 0u;
+            const int crow0 = tile * BN + ld_row;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int crow = crow0 + 32 * i;
+                crow = crow < N ? crow : N - 1;
+                creg[i] = *reinterpret_cast<const v4f*>(X + ((unsigned int)crow * (unsigned int)d + c0));
+            }
+            if (chunk == 0 && tid < BN) {
+                const int crow = tile * BN + tid;
+                const int cr = crow < N ? crow : N - 1;
+                hreg = hn[cr];
+                if (MASKED) colreg = p.colour[cr];
+            }
+        };
+
+        v16f acc[4];
+        gload(0, 0);
+        for (int tile = 0; tile < ntiles; ++tile) {
+            const int col0 = tile * BN;
+            const int tpar = tile & 1;
+            float* hcs = L.hcs + tpar * BN;
+            int* ccol = L.ccol + tpar * BN;
+#pragma unroll
+            for (int chunk = 0; chunk < DCH; ++chunk) {
+                // candidate buffer of this step: steps alternate between the two LDS buffers
+                float* Cb = (((DCH & 1) ? (tile + chunk) : chunk) & 1) ? L.Qs : L.Cs;
+                {
+                    const bool live = chunk * KC + ld_col < d;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const v4f c = live ? creg[i] : v4f{0.f, 0.f, 0.f, 0.f};
+                        *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDK + ld_col) = c;
+                    }
+                }
+                if (chunk == 0 && tid < BN) {
+                    const bool in_range = col0 + tid < N;
+                    hcs[tid] = in_range ? hreg : __builtin_inff();
+                    if (MASKED) ccol[tid] = in_range ? colreg : -1;
+                }
+                __syncthreads();
+                {
+                    int nt = tile, nc = chunk + 1;
+                    if (nc == DCH) { nc = 0; nt = tile + 1; }
+                    if (nt < ntiles) gload(nt, nc);
+                }
+                if (chunk == 0) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const v4f h = *reinterpret_cast<const v4f*>(hcs + b * 32 + 8 * g + 4 * lhalf);
+                            acc[b][4 * g + 0] = -h[0];
+                            acc[b][4 * g + 1] = -h[1];
+                            acc[b][4 * g + 2] = -h[2];
+                            acc[b][4 * g + 3] = -h[3];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int kk = 0; kk < KC / 8; ++kk) {
+                    v4f cf[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        cf[b] = *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + kk * 8 + 4 * lhalf);
+                    const v4f q = qf[chunk * 4 + kk];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(cf[b][e], q[e], acc[b], 0, 0, 0);
+                    }
+                }
+            }
+
+            // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
+            unsigned int flagged = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                bool any = false;
+                if (MASKED) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int4 cc = *reinterpret_cast<const int4*>(ccol + b * 32 + 8 * g + 4 * lhalf);
+                        any |= (acc[b][4 * g + 0] >= bound) & (cc.x != my_qcol);
+                        any |= (acc[b][4 * g + 1] >= bound) & (cc.y != my_qcol);
+                        any |= (acc[b][4 * g + 2] >= bound) & (cc.z != my_qcol);
+                        any |= (acc[b][4 * g + 3] >= bound) & (cc.w != my_qcol);
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) any |= (acc[b][r] >= bound);
+                }
+                if (__any(any)) flagged |= 1u << b;
+            }
+            if (__builtin_expect(flagged != 0, 0)) {
+                const int my_tag = MASKED ? my_qcol : my_qrow;
+                if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, X, N, d, k);
+                if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, X, N, d, k);
+                if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, X, N, d, k);
+                if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, X, N, d, k);
                 bound = bounds[my_q_local];
             }
         }
@@ -468,6 +664,16 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
     return hipGetLastError();
 }
 
+template <typename K>
+static hipError_t launch_with_lds(K kernel, int grid, size_t lds, const SweepParams& p, hipStream_t stream)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(WG_THREADS), lds, stream, p);
+    return hipGetLastError();
+}
+
 template <int KL, bool MASKED>
 static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
 {
@@ -481,18 +687,16 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     int grid = cus * per_cu;
     if (grid > npanels) grid = npanels;
     const bool vec4 = (p.d % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
-    if (vec4) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_kernel<KL, MASKED, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((sweep_kernel<KL, MASKED, true>), dim3(grid), dim3(WG_THREADS), lds, stream, p);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sweep_kernel<KL, MASKED, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((sweep_kernel<KL, MASKED, false>), dim3(grid), dim3(WG_THREADS), lds, stream, p);
+    if (vec4 && p.d <= 4 * KC) {
+        // up to 128 features: query fragments live in registers
+        const int dch = (p.d + KC - 1) / KC;
+        if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1>, grid, lds, p, stream);
+        if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2>, grid, lds, p, stream);
+        if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3>, grid, lds, p, stream);
+        return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4>, grid, lds, p, stream);
     }
-    return hipGetLastError();
+    if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
+    return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
 }
 
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream)
