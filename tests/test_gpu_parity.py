@@ -342,3 +342,79 @@ def test_slhc_tiny(lib):
         X = np.random.default_rng(N).standard_normal((N, 2)).astype(np.float32)
         out = lib.slhc(torch.from_numpy(X).cuda(), k)
         check_slhc(X, out, tie_free=True)
+
+
+# ----------------------------------------------------------------------------- full size (headline)
+def test_headline_full_size_properties(lib):
+    """c3 at its full size (1M x 128, k=32), in the launch configuration bench.py times.  The
+    oracle cannot run the whole problem, so: sampled rows of the k-NN graph are checked one by one
+    against it, sampled reported pairs are recomputed in float64, and the tree is checked through
+    properties that hold at any size (spanning, weights of the returned pairs, the nearest
+    neighbour of every sampled vertex is a tree edge, no sampled pair is closer than the largest
+    edge on its tree path)."""
+    X, _, k = gen.make("c3")
+    N = X.shape[0]
+    Xd = torch.from_numpy(X).cuda()
+    print("headline: knn", flush=True)
+    idx, dist = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    gi, gd = idx.cpu().numpy(), dist.cpu().numpy()
+    rng = np.random.default_rng(99)
+    rows = rng.choice(N, size=192, replace=False)
+    check_knn(X, k, gi[rows], gd[rows], rows=rows, min_exact=0.999)
+    pr = rng.integers(0, N, size=400_000)
+    pc = rng.integers(0, k, size=400_000)
+    assert close(gd[pr, pc], pair_dist64(X, pr, gi[pr, pc]), RTOL_DIST).all()
+    assert (np.diff(gd.astype(np.float64), axis=1) >= 0).all()
+    assert not (gi == np.arange(N)[:, None]).any()
+
+    print("headline: slhc", flush=True)
+    out = lib.slhc(Xd, k)
+    print("stats", out["stats"], flush=True)
+    src, dst, w = (out[n].cpu().numpy() for n in ("mst_src", "mst_dst", "mst_w"))
+    children, heights, sizes = (out[n].cpu().numpy() for n in ("children", "heights", "sizes"))
+    assert (src < dst).all() and (np.diff(w.astype(np.float64)) >= 0).all()
+    es = rng.choice(N - 1, size=300_000, replace=False)
+    assert close(w[es], pair_dist64(X, src[es], dst[es]), RTOL_DIST).all()
+    assert np.array_equal(heights, w)
+    # spanning + linkage invariants through the returned dendrogram
+    assert sizes[-1] == N
+    counts = np.bincount(children.ravel(), minlength=2 * N - 1)
+    assert (counts[:2 * N - 2] == 1).all() and counts[2 * N - 2] == 0
+    assert (children[:, 0] < children[:, 1]).all()
+    assert (children < (N + np.arange(N - 1))[:, None]).all()
+    # the sizes must be those of the union-find over the returned edges (=> acyclic, spanning)
+    parent = np.arange(2 * N - 1)
+    sz = np.ones(2 * N - 1, dtype=np.int64)
+    parent[children[:, 0]] = N + np.arange(N - 1)
+    parent[children[:, 1]] = N + np.arange(N - 1)
+    for i in range(N - 1):
+        sz[N + i] = sz[children[i, 0]] + sz[children[i, 1]]
+    assert np.array_equal(sz[N:], sizes.astype(np.int64))
+    # every vertex's nearest neighbour is a tree edge (first Boruvka round is exact)
+    edge_keys = set((src.astype(np.int64) * N + dst).tolist())
+    vs = rng.choice(N, size=20_000, replace=False)
+    nn = gi[vs, 0].astype(np.int64)
+    lo, hi = np.minimum(vs, nn), np.maximum(vs, nn)
+    assert all(int(a) * N + int(b) in edge_keys for a, b in zip(lo, hi))
+    # cycle property on sampled pairs: d(a,b) >= height of the lowest common ancestor
+    up = parent
+
+    def lca_height(a, b):
+        seen = set()
+        x = int(a)
+        while True:
+            seen.add(x)
+            if up[x] == x:
+                break
+            x = int(up[x])
+        y = int(b)
+        while y not in seen:
+            y = int(up[y])
+        return float(heights[y - N])
+
+    pa = rng.integers(0, N, size=300)
+    pb = gi[pa, rng.integers(0, k, size=300)]          # near pairs are the ones that could violate it
+    d_ab = pair_dist64(X, pa, pb)
+    for a, b, dab in zip(pa, pb, d_ab):
+        assert lca_height(a, b) <= dab * (1 + 1e-5)
