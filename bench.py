@@ -35,6 +35,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--rows", type=int, default=None, help="scale the workload to this many rows")
+    ap.add_argument("--k", type=int, default=None, help="override the workload's k (kernel studies)")
     ap.add_argument("--knn-only", action="store_true", help="time slhc_knn_graph alone (kernel study)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -71,6 +72,8 @@ def main():
     t0 = time.time()
     X, _, k = gen.make(args.workload, n=args.rows)
     N, d = X.shape
+    if args.k is not None:
+        k = args.k
     gen_s = time.time() - t0
     Xd = torch.from_numpy(X).to(dev)
     torch.cuda.synchronize()
