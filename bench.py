@@ -151,6 +151,16 @@ def main():
         },
         "input_generation_s": gen_s,
     }
+    # HBM traffic of the sweep launch is not measurable from here; it comes from the committed
+    # rocprofv3 counter runs of this same workload (profiles/traffic.json), when there is one
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            t = json.load(f).get(args.workload)
+        if t and t["N"] == N and t["d"] == d and t["k"] == k:
+            line["roofline"]["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
+            line["roofline"]["traffic_unit"] = "bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated)"
+    except (OSError, ValueError, KeyError):
+        pass
     if not args.knn_only:
         line["stages_ms"] = {n: mean(n) for n in ("ms_knn", "ms_norm_kernel", "ms_knn_kernel", "ms_boruvka",
                                                   "ms_connect", "ms_connect_kernels", "ms_sort",
