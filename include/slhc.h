@@ -53,7 +53,7 @@ typedef struct slhc_stats {
     int32_t boruvka_rounds;          /* rounds of min-edge + relabel                              */
     int32_t connect_rounds;          /* rounds in which the cross-component 1-NN kernel ran        */
     int32_t components_after_knn;    /* components when the k-NN lists alone could add no edge     */
-    int32_t reserved0;
+    int32_t order_pivots;            /* pivots of the row order (0 when not pruned)                */
     int64_t knn_filter_survivors;    /* pairs that passed the MFMA filter in the k-NN sweep        */
     int64_t connect_query_rows;      /* sum over connection rounds of queried rows                 */
     int64_t connect_filter_survivors;
@@ -66,8 +66,19 @@ typedef struct slhc_stats {
     float ms_norm_kernel;            /* HIP-event time of the half-norm kernel                     */
     float ms_knn_kernel;             /* HIP-event time of the fused k-NN sweep kernel alone        */
     float ms_connect_kernels;        /* HIP-event time summed over the cross-component 1-NN sweeps */
-    float reserved1;
+    float ms_order;                  /* HIP-event time of building the row order + tile balls     */
+    int64_t knn_tile_steps;          /* (query panel, candidate tile) pairs the k-NN sweep multiplied;
+                                        ceil(N/128)^2 when nothing is pruned                        */
+    int64_t connect_tile_steps;      /* same, summed over the connection sweeps                    */
+    int32_t pruned;                  /* 1 when tile pruning was active in this call                */
+    int32_t order_padded_rows;       /* rows of the reordered copy incl. padding (0 when not pruned) */
 } slhc_stats;
+
+/* Option flags of the *_opt entry points. */
+#define SLHC_PRUNE 1u   /* reorder rows spatially and skip (query panel, candidate tile) pairs whose
+                           bounding balls prove that no pair can enter a list.  Results are identical
+                           to the unpruned sweep; only available for d <= 128 with d % 4 == 0 and
+                           N >= 512 (ignored otherwise).  Not in the paper, whose k-NN multiplies every tile.          */
 
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */
@@ -92,6 +103,10 @@ int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes /* H
 int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k,
                    int32_t* nbr_idx, float* nbr_dist,
                    void* workspace, size_t workspace_bytes, void* stream);
+/* Same result; flags = 0 is slhc_knn_graph (every tile multiplied, as in the paper). */
+int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k,
+                       int32_t* nbr_idx, float* nbr_dist,
+                       void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
 /*
  * Cross-component 1-NN (paper Sec. 3.1.2, Alg. "Fused 1-NN", used by Alg. "connect_graph").
@@ -139,6 +154,13 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k,
               int32_t* mst_src, int32_t* mst_dst, float* mst_w,
               int32_t* children, float* heights, int32_t* sizes,
               slhc_stats* stats, void* workspace, size_t workspace_bytes, void* stream);
+/* slhc_slhc is slhc_slhc_opt with flags = SLHC_PRUNE; flags = 0 multiplies every tile in the k-NN
+ * and connection sweeps (the paper's brute-force method).  Same outputs either way. */
+int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k,
+                  int32_t* mst_src, int32_t* mst_dst, float* mst_w,
+                  int32_t* children, float* heights, int32_t* sizes,
+                  slhc_stats* stats, void* workspace, size_t workspace_bytes, void* stream,
+                  uint32_t flags);
 
 #ifdef __cplusplus
 }

@@ -20,14 +20,18 @@ class SlhcError(RuntimeError):
 class _Stats(ctypes.Structure):
     _fields_ = [
         ("boruvka_rounds", ctypes.c_int32), ("connect_rounds", ctypes.c_int32),
-        ("components_after_knn", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("components_after_knn", ctypes.c_int32), ("order_pivots", ctypes.c_int32),
         ("knn_filter_survivors", ctypes.c_int64), ("connect_query_rows", ctypes.c_int64),
         ("connect_filter_survivors", ctypes.c_int64),
         ("ms_knn", ctypes.c_float), ("ms_boruvka", ctypes.c_float), ("ms_connect", ctypes.c_float),
         ("ms_sort", ctypes.c_float), ("ms_dendrogram", ctypes.c_float), ("ms_total", ctypes.c_float),
         ("ms_norm_kernel", ctypes.c_float), ("ms_knn_kernel", ctypes.c_float),
-        ("ms_connect_kernels", ctypes.c_float), ("reserved1", ctypes.c_float),
+        ("ms_connect_kernels", ctypes.c_float), ("ms_order", ctypes.c_float),
+        ("knn_tile_steps", ctypes.c_int64), ("connect_tile_steps", ctypes.c_int64),
+        ("pruned", ctypes.c_int32), ("order_padded_rows", ctypes.c_int32),
     ]
+
+SLHC_PRUNE = 1
 
 
 def library_path():
@@ -49,12 +53,15 @@ def load_library():
     lib.slhc_last_error.restype = ctypes.c_char_p
     lib.slhc_knn_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
     lib.slhc_knn_graph.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.slhc_knn_graph_opt.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp, ctypes.c_uint32]
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
     lib.slhc_cross_1nn.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
     lib.slhc_slhc.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats), vp, sz, vp]
-    for name in ("slhc_knn_workspace_bytes", "slhc_knn_graph", "slhc_cross_1nn_workspace_bytes",
-                 "slhc_cross_1nn", "slhc_workspace_bytes", "slhc_slhc"):
+    lib.slhc_slhc_opt.argtypes = lib.slhc_slhc.argtypes + [ctypes.c_uint32]
+    for name in ("slhc_knn_workspace_bytes", "slhc_knn_graph", "slhc_knn_graph_opt",
+                 "slhc_cross_1nn_workspace_bytes", "slhc_cross_1nn", "slhc_workspace_bytes", "slhc_slhc",
+                 "slhc_slhc_opt"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -97,9 +104,9 @@ def slhc_workspace_bytes(N, d, k):
     return out.value
 
 
-def knn_graph(X, k, out=None, workspace=None):
-    """slhc_knn_graph: returns (idx int32 [N,k], dist float32 [N,k]) device tensors.  Asynchronous
-    on the current stream."""
+def knn_graph(X, k, out=None, workspace=None, prune=False):
+    """slhc_knn_graph (prune=False) / slhc_knn_graph_opt with SLHC_PRUNE: returns (idx int32 [N,k],
+    dist float32 [N,k]) device tensors.  Asynchronous on the current stream."""
     X = _device_matrix(X)
     N, d = X.shape
     lib = load_library()
@@ -110,8 +117,9 @@ def knn_graph(X, k, out=None, workspace=None):
         dist = torch.empty((N, k), dtype=torch.float32, device=X.device)
     else:
         idx, dist = out
-    _check(lib.slhc_knn_graph(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
-                              workspace.data_ptr(), workspace.numel(), _stream()))
+    _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream(),
+                                  SLHC_PRUNE if prune else 0))
     return idx, dist
 
 
@@ -139,10 +147,11 @@ def cross_1nn(X, colour, rows=None, m=None):
     return idx, dist
 
 
-def slhc(X, k, workspace=None, out=None):
+def slhc(X, k, workspace=None, out=None, prune=True):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
-    ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory."""
+    ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
+    prune=True is slhc_slhc; prune=False multiplies every tile (slhc_slhc_opt with flags 0)."""
     X = _device_matrix(X)
     N, d = X.shape
     lib = load_library()
@@ -158,9 +167,9 @@ def slhc(X, k, workspace=None, out=None):
         sizes=torch.empty(N - 1, dtype=torch.int32, device=dev),
     )
     st = _Stats()
-    _check(lib.slhc_slhc(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
-                         out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
-                         out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
-                         workspace.numel(), _stream()))
+    _check(lib.slhc_slhc_opt(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
+                             out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
+                             out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
+                             workspace.numel(), _stream(), SLHC_PRUNE if prune else 0))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out

@@ -34,8 +34,9 @@ hipError_t forest_init(const ForestState& f, hipStream_t s);
 hipError_t forest_round_reset(const ForestState& f, hipStream_t s);
 hipError_t forest_scan_lists(const ForestState& f, hipStream_t s);
 hipError_t forest_classify(const ForestState& f, hipStream_t s);
-hipError_t forest_apply_queries(const ForestState& f, const int32_t* q_idx, const float* q_dist,
-                                int nq, hipStream_t s);
+// qrows[q] is the vertex query q was made for (f.qlist, or a reordered copy of it)
+hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
+                                const float* q_dist, int nq, hipStream_t s);
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
 hipError_t forest_commit(const ForestState& f, hipStream_t s);
 hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step
@@ -48,5 +49,11 @@ hipError_t edge_sort(const int32_t* lo, const int32_t* hi, const float* w, int E
                      unsigned long long* keys_a, unsigned long long* keys_b,
                      uint32_t* vals_a, uint32_t* vals_b, void* temp, size_t temp_bytes,
                      int32_t* out_lo, int32_t* out_hi, float* out_w, hipStream_t s);
+
+// Stable sort of n (key, value) pairs of 32-bit words by key (keys below 2^key_bits).
+size_t pair_sort_temp_bytes(int n);
+hipError_t pair_sort_u32(const uint32_t* keys_in, uint32_t* keys_out, const uint32_t* vals_in,
+                         uint32_t* vals_out, int n, int key_bits, void* temp, size_t temp_bytes,
+                         hipStream_t s);
 
 }  // namespace slhc

@@ -130,12 +130,13 @@ __global__ void __launch_bounds__(TB) k_classify(ForestState f)
     }
 }
 
-__global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32_t* __restrict__ q_idx,
+__global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32_t* __restrict__ qrows,
+                                                      const int32_t* __restrict__ q_idx,
                                                       const float* __restrict__ q_dist, int nq)
 {
     const int q = blockIdx.x * TB + threadIdx.x;
     if (q >= nq) return;
-    const int v = f.qlist[q];
+    const int v = qrows[q];
     const int u = q_idx[q];
     const float w = q_dist[q];
     if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) { report(f, 6); return; }
@@ -230,10 +231,10 @@ hipError_t forest_scan_lists(const ForestState& f, hipStream_t s)
 
 hipError_t forest_classify(const ForestState& f, hipStream_t s) { LAUNCH1(k_classify, f.N, s, f); }
 
-hipError_t forest_apply_queries(const ForestState& f, const int32_t* q_idx, const float* q_dist,
-                                int nq, hipStream_t s)
+hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
+                                const float* q_dist, int nq, hipStream_t s)
 {
-    LAUNCH1(k_apply_queries, nq, s, f, q_idx, q_dist, nq);
+    LAUNCH1(k_apply_queries, nq, s, f, qrows, q_idx, q_dist, nq);
 }
 
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }
@@ -294,6 +295,25 @@ hipError_t edge_sort(const int32_t* lo, const int32_t* hi, const float* w, int E
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_unpack_edges, dim3(blocks_for(E)), dim3(TB), 0, s, keys_a, vals_a, E, out_lo, out_hi, out_w);
     return hipGetLastError();
+}
+
+size_t pair_sort_temp_bytes(int n)
+{
+    size_t a = 0;
+    uint32_t* k32 = nullptr;
+    (void)rocprim::radix_sort_pairs(nullptr, a, k32, k32, k32, k32, (size_t)n, 0, 32, (hipStream_t)0);
+    return (a + 255) & ~(size_t)255;
+}
+
+hipError_t pair_sort_u32(const uint32_t* keys_in, uint32_t* keys_out, const uint32_t* vals_in,
+                         uint32_t* vals_out, int n, int key_bits, void* temp, size_t temp_bytes,
+                         hipStream_t s)
+{
+    size_t tb = temp_bytes;
+    if (key_bits < 1) key_bits = 1;
+    if (key_bits > 32) key_bits = 32;
+    return rocprim::radix_sort_pairs(temp, tb, keys_in, keys_out, vals_in, vals_out, (size_t)n, 0,
+                                     (unsigned int)key_bits, s);
 }
 
 }  // namespace slhc

@@ -3,6 +3,7 @@
 // Alg. "MST Algorithm" of the paper, restructured as one certified Boruvka loop (see
 // forest_kernels.hip for what "certified" means).
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -12,6 +13,7 @@
 
 #include "../../include/slhc.h"
 #include "forest_kernels.h"
+#include "order_kernels.h"
 #include "sweep_kernels.h"
 
 namespace {
@@ -88,15 +90,76 @@ struct EventPair {
     float ms() const { float t = 0.f; return hipEventElapsedTime(&t, a, b) == hipSuccess ? t : -1.f; }
 };
 
+// Tile pruning is implemented by the register-resident-query sweep only (d <= 128, d % 4 == 0), and
+// pays off only when there are enough rows to form several tiles per cluster.
+#ifndef SLHC_PRUNE_MIN_ROWS
+#define SLHC_PRUNE_MIN_ROWS 512      // compile-time knob so that small harnesses can exercise the reordered path
+#endif
+constexpr int64_t PRUNE_MIN_ROWS = SLHC_PRUNE_MIN_ROWS;
+constexpr int NESTED_K = 8;
+bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
+int first_level_pivots(int64_t N) { return (int)((N + 63) / 64); }
+// The reordered copy inserts padding rows so that well separated clusters start on a tile
+// boundary; padding is limited to N/2 rows.
+int64_t padded_rows_limit(int64_t N) { return N + N / 2 + 256; }
+
+size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
+
+// Buffers of the spatially coherent row order (see build_order).
+struct OrderWs {
+    float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *n_w, *n_heights;
+    int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *counts, *rank, *shift, *far_count;
+    int32_t *n_src, *n_dst, *n_children, *n_sizes;
+    uint32_t *tmp_a, *tmp_b, *tmp_c;
+    void* sort_temp; size_t sort_temp_bytes;
+    void* nested_ws; size_t nested_bytes;
+    int P1, Pmax, Tmax;
+    int64_t Nmax;
+    int P = 0;        // pivots in use          (set by build_order)
+    int Ns = 0;       // rows of the padded copy (set by build_order)
+    static constexpr int SAMPLE = 4096;
+    void carve(Carver& c, int64_t N, int32_t d)
+    {
+        const size_t n = (size_t)N;
+        P1 = first_level_pivots(N);
+        Pmax = 2 * P1;
+        Nmax = padded_rows_limit(N);
+        Tmax = (int)((Nmax + 127) / 128);
+        const size_t nm = (size_t)Nmax, pm = (size_t)Pmax;
+        Xp = c.take<float>(pm * d); hp = c.take<float>(pm);
+        pdist = c.take<float>(n); sample = c.take<float>(SAMPLE);
+        Xs = c.take<float>(nm * d); hs = c.take<float>(nm);
+        tile_c = c.take<float>((size_t)Tmax * d); tile_r = c.take<float>((size_t)Tmax);
+        int grid = slhc::sweep_grid_limit();
+        if (grid < 1) grid = 512;
+        gap_ws = c.take<float>((size_t)grid * Tmax);
+        pid = c.take<int32_t>(n); perm = c.take<int32_t>(nm); inv = c.take<int32_t>(n); colour_s = c.take<int32_t>(nm);
+        qslot = c.take<int32_t>(nm); tile_colour = c.take<int32_t>((size_t)Tmax);
+        counts = c.take<int32_t>(pm); rank = c.take<int32_t>(pm); shift = c.take<int32_t>(pm); far_count = c.take<int32_t>(64);
+        tmp_a = c.take<uint32_t>(n); tmp_b = c.take<uint32_t>(n); tmp_c = c.take<uint32_t>(n);
+        sort_temp_bytes = slhc::pair_sort_temp_bytes((int)N);
+        sort_temp = c.take<unsigned char>(sort_temp_bytes);
+        n_src = c.take<int32_t>(pm); n_dst = c.take<int32_t>(pm); n_w = c.take<float>(pm);
+        n_children = c.take<int32_t>(2 * pm); n_heights = c.take<float>(pm); n_sizes = c.take<int32_t>(pm);
+        const int32_t kp = Pmax - 1 < NESTED_K ? Pmax - 1 : NESTED_K;
+        nested_bytes = slhc_ws_bytes(Pmax, d, kp, false);
+        nested_ws = c.take<unsigned char>(nested_bytes);
+    }
+};
+
 struct KnnWs {
-    unsigned long long* survivors;
+    unsigned long long* counters;    // [0] k-NN survivors [1] connect survivors [2] k-NN tile steps [3] connect tile steps
     float* hn;
+    bool has_order;
+    OrderWs order;
     size_t bytes;
-    KnnWs(void* ws, int64_t N)
+    KnnWs(void* ws, int64_t N, int32_t d, bool with_order)
     {
         Carver c(ws);
-        survivors = c.take<unsigned long long>(32);
+        counters = c.take<unsigned long long>(32);
         hn = c.take<float>((size_t)N);
+        has_order = with_order && prunable(N, d);
+        if (has_order) order.carve(c, N, d);
         bytes = c.off;
     }
 };
@@ -110,11 +173,11 @@ struct SlhcWs {
     unsigned long long *best_e, *keys_a, *keys_b;
     void* sort_temp; size_t sort_temp_bytes;
     size_t bytes;
-    SlhcWs(void* ws, int64_t N, int32_t k)
+    SlhcWs(void* ws, int64_t N, int32_t d, int32_t k, bool with_order)
     {
         Carver c(ws);
         const size_t n = (size_t)N;
-        knn_ws = c.take<unsigned char>(KnnWs(nullptr, N).bytes);
+        knn_ws = c.take<unsigned char>(KnnWs(nullptr, N, d, with_order).bytes);
         nbr_idx = c.take<int32_t>(n * k);
         nbr_dist = c.take<float>(n * k);
         colour = c.take<int32_t>(n); ptr = c.take<int32_t>(n); ext_idx = c.take<int32_t>(n);
@@ -131,25 +194,216 @@ struct SlhcWs {
     }
 };
 
-int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
-            void* workspace, hipStream_t stream, unsigned long long** survivors_out,
-            EventPair* ev_norm = nullptr, EventPair* ev_sweep = nullptr)
+size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order) { return SlhcWs(nullptr, N, d, k, with_order).bytes; }
+
+int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, int32_t* mst_dst, float* mst_w,
+             int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats, void* workspace,
+             hipStream_t s, uint32_t flags, bool with_order);
+
+int bits_for(long long n) { int b = 1; while (b < 32 && (1LL << b) < n) ++b; return b; }
+
+// Nearest pivot of every row by the fused sweep (k = 1 against the P pivot rows).
+int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, int P, hipStream_t s)
 {
-    KnnWs ws(workspace, N);
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(ws.survivors), 64);
+    slhc::SweepParams p{};
+    p.Xq = X; p.hq = hn; p.NQ = (int)N;
+    p.Xc = o.Xp; p.hc = o.hp; p.NC = P;
+    p.d = d; p.k = 1;
+    p.out_idx = o.pid; p.out_dist = o.pdist;
+    HIP_TRY(slhc::launch_knn_sweep(p, s));
+    return SLHC_OK;
+}
+
+// Spatially coherent order of the rows (not in the paper, whose sweeps multiply every tile).
+//   1. Every 64th row is a pivot; each row is assigned to its nearest pivot by the fused 1-NN sweep.
+//      Rows much farther from their pivot than the typical row belong to clusters that received no
+//      pivot; a sample of those rows becomes a second set of pivots and the assignment is repeated.
+//   2. The pivots are clustered by this library's own single-linkage path (without reordering); the
+//      leaf order of their dendrogram puts pivots of one cluster next to each other at every scale.
+//   3. Rows are sorted by the position of their pivot in that order.  Where consecutive pivots are
+//      joined only far above the typical cell scale, the next row starts a new tile of 128 (padding
+//      rows: perm = -1, zero features, +inf half norm), so tiles do not straddle distant clusters.
+//   4. One bounding ball per tile of the reordered copy.
+// The order only affects which tiles the sweeps can skip, never a result.
+int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, hipStream_t s)
+{
+    const int n = (int)N;
+    const int P1 = o.P1;
+    PinnedHost pin;
+    HIP_TRY(pin.alloc(((size_t)OrderWs::SAMPLE + 16 + 6 * (size_t)o.Pmax) * 4));
+    float* h_sample = static_cast<float*>(pin.p);
+    int32_t* h_count = reinterpret_cast<int32_t*>(h_sample + OrderWs::SAMPLE);
+    int32_t* h_src = h_count + 16;
+    int32_t* h_dst = h_src + o.Pmax;
+    float* h_w = reinterpret_cast<float*>(h_dst + o.Pmax);
+    int32_t* h_cells = reinterpret_cast<int32_t*>(h_w + o.Pmax);
+    int32_t* h_rank = h_cells + o.Pmax;
+    int32_t* h_shift = h_rank + o.Pmax;
+
+    // ---- 1. pivots and assignment
+    HIP_TRY(slhc::order_pick_rows(X, hn, n, d, P1, o.Xp, o.hp, s));
+    int rc = assign_to_pivots(X, N, d, hn, o, P1, s);
+    if (rc != SLHC_OK) return rc;
+    const int S = n < OrderWs::SAMPLE ? n : OrderWs::SAMPLE;
+    HIP_TRY(slhc::order_pick_f32(o.pdist, n, S, o.sample, s));
+    HIP_TRY(hipMemcpyAsync(h_sample, o.sample, (size_t)S * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    float tau = __builtin_inff();          // 4 x median positive squared distance to the pivot
+    {
+        std::vector<float> v;
+        for (int i = 0; i < S; ++i) if (h_sample[i] > 0.f && std::isfinite(h_sample[i])) v.push_back(h_sample[i]);
+        if (!v.empty()) {
+            std::nth_element(v.begin(), v.begin() + v.size() / 2, v.end());
+            tau = 4.f * v[v.size() / 2];
+        }
+    }
+    int P = P1;
+    if (std::isfinite(tau)) {
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(o.far_count), 64);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(slhc::order_mark_far(o.pdist, n, tau, o.tmp_a, o.far_count, s));
+        HIP_TRY(hipMemcpyAsync(h_count, o.far_count, 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const int far = h_count[0];
+        if (far < 0 || far > n) { set_err("row order: bad far-row count %d", far); return SLHC_INTERNAL; }
+        if (far > 0) {
+            // far rows first, in row order (stable 1-bit sort); every 16th becomes a pivot
+            HIP_TRY(slhc::order_iota(reinterpret_cast<int32_t*>(o.tmp_b), n, s));
+            HIP_TRY(slhc::pair_sort_u32(o.tmp_a, o.tmp_c, o.tmp_b, reinterpret_cast<uint32_t*>(o.perm), n, 1,
+                                        o.sort_temp, o.sort_temp_bytes, s));
+            int P2 = (far + 15) / 16;
+            if (P2 > P1) P2 = P1;
+            HIP_TRY(slhc::order_pick_listed_rows(X, hn, reinterpret_cast<const uint32_t*>(o.perm), far, n, d, P2,
+                                                 o.Xp + (size_t)P1 * d, o.hp + P1, s));
+            P = P1 + P2;
+            rc = assign_to_pivots(X, N, d, hn, o, P, s);
+            if (rc != SLHC_OK) return rc;
+        }
+    }
+    o.P = P;
+
+    // ---- 2. hierarchy of the pivots: concatenating the two sides of every merge, in merge order,
+    // yields a leaf order of the dendrogram; `joined[i]` is the height at which pivot i's successor
+    // in that order was attached.
+    std::vector<int32_t> order((size_t)P), head((size_t)P), tail((size_t)P), nxt((size_t)P, -1), up_set((size_t)P);
+    std::vector<float> joined((size_t)P, 0.f);
+    for (int i = 0; i < P; ++i) head[(size_t)i] = tail[(size_t)i] = up_set[(size_t)i] = i;
+    if (P >= 2) {
+        const int32_t kp = P - 1 < NESTED_K ? P - 1 : NESTED_K;
+        rc = run_slhc(o.Xp, P, d, kp, o.n_src, o.n_dst, o.n_w, o.n_children, o.n_heights, o.n_sizes, nullptr,
+                      o.nested_ws, s, 0u, false);
+        if (rc != SLHC_OK) return rc;
+        const size_t E = (size_t)(P - 1);
+        HIP_TRY(hipMemcpyAsync(h_src, o.n_src, E * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_dst, o.n_dst, E * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_w, o.n_w, E * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        auto top = [&](int32_t a) {
+            while (up_set[(size_t)a] != a) {
+                up_set[(size_t)a] = up_set[(size_t)up_set[(size_t)a]];
+                a = up_set[(size_t)a];
+            }
+            return a;
+        };
+        for (size_t e = 0; e < E; ++e) {
+            if ((uint32_t)h_src[e] >= (uint32_t)P || (uint32_t)h_dst[e] >= (uint32_t)P) { set_err("row order: bad pivot edge"); return SLHC_INTERNAL; }
+            const int32_t a = top(h_src[e]), b = top(h_dst[e]);
+            if (a == b) { set_err("row order: pivot tree has a cycle"); return SLHC_INTERNAL; }
+            nxt[(size_t)tail[(size_t)a]] = head[(size_t)b];
+            joined[(size_t)tail[(size_t)a]] = h_w[e];
+            tail[(size_t)a] = tail[(size_t)b];
+            up_set[(size_t)b] = a;
+        }
+        int32_t at = head[(size_t)top(0)];
+        for (int r = 0; r < P; ++r) {
+            if (at < 0) { set_err("row order: pivot chain ends early"); return SLHC_INTERNAL; }
+            order[(size_t)r] = at;
+            at = nxt[(size_t)at];
+        }
+    } else {
+        order[0] = 0;
+    }
+    for (int r = 0; r < P; ++r) h_rank[order[(size_t)r]] = r;
+
+    // ---- 3. cell sizes and the padded layout
+    HIP_TRY(slhc::order_fill_i32(o.counts, P, 0, s));
+    HIP_TRY(slhc::order_histogram(o.pid, n, P, o.counts, s));
+    HIP_TRY(hipMemcpyAsync(h_cells, o.counts, (size_t)P * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    {
+        long long total = 0;
+        for (int i = 0; i < P; ++i) { if (h_cells[i] < 0) { total = -1; break; } total += h_cells[i]; }
+        if (total != (long long)N) { set_err("row order: cells hold %lld of %lld rows", total, (long long)N); return SLHC_INTERNAL; }
+    }
+    const long long budget = (long long)(N / 2);
+    float tau_pad = tau;
+    long long Ns = 0;
+    for (int attempt = 0; attempt < 200; ++attempt) {
+        long long pos = 0, plain = 0;
+        for (int r = 0; r < P; ++r) {
+            const int pv = order[(size_t)r];
+            h_shift[r] = (int32_t)(pos - plain);
+            pos += h_cells[pv];
+            plain += h_cells[pv];
+            if (r + 1 < P && joined[(size_t)pv] > tau_pad) pos = (pos + 127) / 128 * 128;
+        }
+        Ns = pos;
+        if (Ns - (long long)N <= budget) break;
+        tau_pad = attempt < 190 ? tau_pad * 2.f : __builtin_inff();
+    }
+    if (Ns < (long long)N || Ns > (long long)o.Nmax) { set_err("row order: padded size %lld out of range", Ns); return SLHC_INTERNAL; }
+    o.Ns = (int)Ns;
+
+    // ---- 4. place the rows, gather the copy, bound the tiles
+    HIP_TRY(hipMemcpyAsync(o.rank, h_rank, (size_t)P * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(o.shift, h_shift, (size_t)P * 4, hipMemcpyHostToDevice, s));
+    uint32_t* keys = reinterpret_cast<uint32_t*>(o.colour_s);        // free until the connection rounds
+    HIP_TRY(slhc::order_keys(o.pid, o.rank, n, P, keys, s));
+    HIP_TRY(slhc::order_iota(reinterpret_cast<int32_t*>(o.tmp_a), n, s));
+    HIP_TRY(slhc::pair_sort_u32(keys, o.tmp_b, o.tmp_a, o.tmp_c, n, bits_for(P), o.sort_temp, o.sort_temp_bytes, s));
+    HIP_TRY(slhc::order_fill_i32(o.perm, o.Ns, -1, s));
+    HIP_TRY(slhc::order_scatter(o.tmp_b, o.tmp_c, o.shift, n, P, o.Ns, o.perm, o.inv, s));
+    HIP_TRY(slhc::order_gather_padded(X, hn, o.perm, o.Ns, n, d, o.Xs, o.hs, s));
+    HIP_TRY(slhc::order_tile_balls(o.Xs, o.perm, o.Ns, d, o.tile_c, o.tile_r, s));
+    HIP_TRY(hipStreamSynchronize(s));        // the pinned staging buffer is released on return
+    return SLHC_OK;
+}
+
+int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
+            KnnWs& ws, hipStream_t stream, uint32_t flags, bool* pruned_out = nullptr,
+            EventPair* ev_norm = nullptr, EventPair* ev_order = nullptr, EventPair* ev_sweep = nullptr)
+{
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(ws.counters), 64);
     HIP_TRY(hipGetLastError());
     if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->a, stream));
     HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn, stream));
     if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->b, stream));
+    const bool prune = (flags & SLHC_PRUNE) && ws.has_order;
+    if (pruned_out) *pruned_out = prune;
+    if (ev_order) HIP_TRY(hipEventRecord(ev_order->a, stream));
+    if (prune) {
+        const int rc = build_order(X, N, d, ws.hn, ws.order, stream);
+        if (rc != SLHC_OK) return rc;
+    }
+    if (ev_order) HIP_TRY(hipEventRecord(ev_order->b, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->a, stream));
     slhc::SweepParams p{};
-    p.X = X; p.hn = ws.hn; p.N = (int)N; p.d = d; p.k = k;
+    p.d = d; p.k = k;
     p.out_idx = nbr_idx; p.out_dist = nbr_dist;
-    p.colour = nullptr; p.rows = nullptr; p.m = 0;
-    p.survivors = ws.survivors;
+    p.exclude_self = 1;
+    p.survivors = ws.counters;
+    p.tiles_done = ws.counters + 2;
+    if (prune) {
+        const OrderWs& o = ws.order;
+        p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
+        p.q_out_row = o.perm; p.c_id = o.perm;
+        p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
+        p.own_tile_first = 1;
+    } else {
+        p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
+    }
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));
-    if (survivors_out) *survivors_out = ws.survivors;
     return SLHC_OK;
 }
 
@@ -213,19 +467,25 @@ int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
     if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
     const int rc = check_shape(N, d, k, true);
     if (rc != SLHC_OK) return rc;
-    *bytes = KnnWs(nullptr, N).bytes;
+    *bytes = KnnWs(nullptr, N, d, true).bytes;
     return SLHC_OK;
+}
+
+int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
+                       void* workspace, size_t workspace_bytes, void* stream, uint32_t flags)
+{
+    if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+    const int rc = check_shape(N, d, k, true);
+    if (rc != SLHC_OK) return rc;
+    KnnWs ws(workspace, N, d, true);
+    if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+    return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
 }
 
 int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
                    void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, k, true);
-    if (rc != SLHC_OK) return rc;
-    const size_t need = KnnWs(nullptr, N).bytes;
-    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
-    return run_knn(X, N, d, k, nbr_idx, nbr_dist, workspace, static_cast<hipStream_t>(stream), nullptr);
+    return slhc_knn_graph_opt(X, N, d, k, nbr_idx, nbr_dist, workspace, workspace_bytes, stream, 0u);
 }
 
 int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes)
@@ -234,7 +494,7 @@ int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* byte
     const int rc = check_shape(N, d, 1, false);
     if (rc != SLHC_OK) return rc;
     if (m < 0 || m > 2147483647LL) { set_err("bad m"); return SLHC_INVALID_ARG; }
-    *bytes = KnnWs(nullptr, N).bytes;
+    *bytes = up(32 * sizeof(unsigned long long)) + up((size_t)N * sizeof(float));
     return SLHC_OK;
 }
 
@@ -246,19 +506,20 @@ int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour, 
     const int rc = check_shape(N, d, 1, false);
     if (rc != SLHC_OK) return rc;
     if (m < 0 || m > 2147483647LL || (!rows && m > N)) { set_err("bad m=%lld", (long long)m); return SLHC_INVALID_ARG; }
-    const size_t need = KnnWs(nullptr, N).bytes;
-    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
+    Carver c(workspace);
+    unsigned long long* counters = c.take<unsigned long long>(32);
+    float* hn = c.take<float>((size_t)N);
+    if (workspace_bytes < c.off) { set_err("workspace %zu < %zu bytes", workspace_bytes, c.off); return SLHC_WORKSPACE_TOO_SMALL; }
     if (m == 0) return SLHC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    KnnWs ws(workspace, N);
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.survivors), 64);
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(counters), 64);
     HIP_TRY(hipGetLastError());
-    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn, s));
+    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, hn, s));
     slhc::SweepParams p{};
-    p.X = X; p.hn = ws.hn; p.N = (int)N; p.d = d; p.k = 1;
+    p.Xq = p.Xc = X; p.hq = p.hc = hn; p.NQ = p.NC = (int)N; p.d = d; p.k = 1;
     p.out_idx = out_idx; p.out_dist = out_dist;
-    p.colour = colour; p.rows = rows; p.m = (int)m;
-    p.survivors = ws.survivors;
+    p.qcolour = p.ccolour = colour; p.rows = rows; p.m = (int)m;
+    p.survivors = counters;
     HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
     return SLHC_OK;
 }
@@ -268,7 +529,7 @@ int slhc_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
     if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
     const int rc = check_shape(N, d, k, true);
     if (rc != SLHC_OK) return rc;
-    *bytes = SlhcWs(nullptr, N, k).bytes;
+    *bytes = SlhcWs(nullptr, N, d, k, true).bytes;
     return SLHC_OK;
 }
 
@@ -276,34 +537,61 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
               float* mst_w, int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats,
               void* workspace, size_t workspace_bytes, void* stream)
 {
+    return slhc_slhc_opt(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
+                         workspace_bytes, stream, SLHC_PRUNE);
+}
+
+int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, int32_t* mst_dst,
+                  float* mst_w, int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats,
+                  void* workspace, size_t workspace_bytes, void* stream, uint32_t flags)
+{
     if (!X || !mst_src || !mst_dst || !mst_w || !children || !heights || !sizes || !workspace) {
         set_err("NULL pointer argument");
         return SLHC_INVALID_ARG;
     }
-    int rc = check_shape(N, d, k, true);
+    const int rc = check_shape(N, d, k, true);
     if (rc != SLHC_OK) return rc;
-    SlhcWs ws(workspace, N, k);
-    if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t need = slhc_ws_bytes(N, d, k, true);
+    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
+    return run_slhc(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
+                    static_cast<hipStream_t>(stream), flags, true);
+}
+
+}  // extern "C"
+
+namespace {
+
+// The whole pipeline on validated arguments.  `with_order` selects the workspace layout (the
+// nested call that clusters the pivots of the row order runs without one).
+int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, int32_t* mst_dst, float* mst_w,
+             int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats, void* workspace,
+             hipStream_t s, uint32_t flags, bool with_order)
+{
+    int rc = SLHC_OK;
+    SlhcWs ws(workspace, N, d, k, with_order);
     slhc_stats st;
     std::memset(&st, 0, sizeof(st));
     const double t_begin = now_ms();
 
     // ---- k-NN graph (Alg. "cuSLINK Algorithm", first step)
-    unsigned long long* d_surv = nullptr;
-    EventPair ev_norm, ev_knn, ev_conn;
+    EventPair ev_norm, ev_order, ev_knn, ev_conn;
     HIP_TRY(ev_norm.create());
+    HIP_TRY(ev_order.create());
     HIP_TRY(ev_knn.create());
     HIP_TRY(ev_conn.create());
-    rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, ws.knn_ws, s, &d_surv, &ev_norm, &ev_knn);
+    bool pruned = false;
+    KnnWs kws(ws.knn_ws, N, d, with_order);      // half norms and row order are reused by the connection sweeps
+    rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, kws, s, flags, &pruned, &ev_norm, &ev_order, &ev_knn);
     if (rc != SLHC_OK) return rc;
     PinnedHost pin_surv;
     HIP_TRY(pin_surv.alloc(64));
     unsigned long long* h_surv = static_cast<unsigned long long*>(pin_surv.p);
-    HIP_TRY(hipMemcpyAsync(h_surv, d_surv, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     st.knn_filter_survivors = (int64_t)h_surv[0];
+    st.knn_tile_steps = (int64_t)h_surv[2];
     st.ms_norm_kernel = ev_norm.ms();
+    st.ms_order = ev_order.ms();
     st.ms_knn_kernel = ev_knn.ms();
     const double t_knn = now_ms();
     st.ms_knn = (float)(t_knn - t_begin);
@@ -317,7 +605,6 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
     f.min_lb = ws.min_lb; f.hook = ws.hook; f.qlist = ws.qlist; f.counters = ws.counters;
     f.e_lo = ws.e_lo; f.e_hi = ws.e_hi; f.e_w = ws.e_w;
     HIP_TRY(slhc::forest_init(f, s));
-    KnnWs kws(ws.knn_ws, N);       // the half norms computed for the k-NN sweep are reused
     PinnedHost pin_cnt;
     HIP_TRY(pin_cnt.alloc(64));
     int32_t* h_cnt = static_cast<int32_t*>(pin_cnt.p);
@@ -344,14 +631,35 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
             ++st.connect_rounds;
             st.connect_query_rows += nq;
             slhc::SweepParams p{};
-            p.X = X; p.hn = kws.hn; p.N = (int)N; p.d = d; p.k = 1;
+            p.d = d; p.k = 1;
             p.out_idx = ws.q_idx; p.out_dist = ws.q_dist;
-            p.colour = ws.colour; p.rows = ws.qlist; p.m = nq;
-            p.survivors = kws.survivors + 1;
+            p.m = nq;
+            p.survivors = kws.counters + 1;
+            p.tiles_done = kws.counters + 3;
+            const int32_t* qrows = ws.qlist;
+            if (pruned) {
+                // colours in the reordered copy, one colour summary per tile, and the queried rows
+                // marked in place so that query panels coincide with candidate tiles
+                const OrderWs& o = kws.order;
+                HIP_TRY(slhc::order_gather_i32(ws.colour, o.perm, o.Ns, (int)N, -1, o.colour_s, s));
+                HIP_TRY(slhc::order_tile_colours(o.colour_s, o.Ns, o.tile_colour, s));
+                HIP_TRY(slhc::order_fill_i32(o.qslot, o.Ns, -1, s));
+                HIP_TRY(slhc::order_scatter_slots(o.inv, ws.qlist, nq, (int)N, o.Ns, o.qslot, s));
+                p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
+                p.qcolour = p.ccolour = o.colour_s;
+                p.qslot = o.qslot;
+                p.c_id = o.perm;
+                p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
+                p.tile_colour = o.tile_colour;
+            } else {
+                p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
+                p.qcolour = p.ccolour = ws.colour;
+                p.rows = ws.qlist;
+            }
             HIP_TRY(hipEventRecord(ev_conn.a, s));
             HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
             HIP_TRY(hipEventRecord(ev_conn.b, s));
-            HIP_TRY(slhc::forest_apply_queries(f, ws.q_idx, ws.q_dist, nq, s));
+            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, s));
             HIP_TRY(hipStreamSynchronize(s));
             st.ms_connect_kernels += ev_conn.ms();
             ms_connect += now_ms() - tc0;
@@ -372,9 +680,12 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
         if (h_cnt[1] <= edges || h_cnt[1] > N - 1) { set_err("round added %d edges (total %d)", h_cnt[1] - edges, h_cnt[1]); return SLHC_INTERNAL; }
         edges = h_cnt[1];
     }
-    HIP_TRY(hipMemcpyAsync(h_surv, kws.survivors + 1, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    st.connect_filter_survivors = (int64_t)h_surv[0];
+    st.connect_filter_survivors = (int64_t)h_surv[1];
+    st.connect_tile_steps = (int64_t)h_surv[3];
+    st.pruned = pruned ? 1 : 0;
+    if (pruned) { st.order_pivots = kws.order.P; st.order_padded_rows = kws.order.Ns; }
     const double t_forest = now_ms();
     st.ms_connect = (float)ms_connect;
     st.ms_boruvka = (float)(t_forest - t_knn - ms_connect);
@@ -408,4 +719,4 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src,
     return SLHC_OK;
 }
 
-}  // extern "C"
+}  // namespace

@@ -5,20 +5,44 @@
 
 namespace slhc {
 
+// Queries and candidates are rows of two row-major matrices (the same one for a self-join).
+// Row indices inside a sweep are positions in those matrices; `c_id` / `q_out_row` translate
+// them back when the matrices are a reordered copy of the caller's data.
 struct SweepParams {
-    const float* X;        // [N, d]
-    const float* hn;       // [N]  (1-c)/2 * ||x||^2, from launch_half_norms
-    int N, d, k;
-    int32_t* out_idx;      // k-NN: [N, k]; cross 1-NN: [m]
+    const float* Xq;       // [NQ, d] query rows
+    const float* hq;       // [NQ]  (1-c)/2 * ||x||^2 of the query rows (launch_half_norms)
+    const float* Xc;       // [NC, d] candidate rows
+    const float* hc;       // [NC]
+    int NQ, NC, d, k;
+    int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
-    const int32_t* colour; // cross 1-NN only: [N]
+    const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)
+    const int32_t* c_id;        // id reported for candidate row c and used to order ties (nullptr: c)
+    int exclude_self;      // k-NN only: candidate row == query row is skipped (self-join)
+    const int32_t* qcolour;     // cross 1-NN only: [NQ] colour of query rows
+    const int32_t* ccolour;     // cross 1-NN only: [NC] colour of candidate rows
     const int32_t* rows;   // cross 1-NN only: [m] query rows, or nullptr for rows 0..m-1
     int m;                 // cross 1-NN only
+    // cross 1-NN, alternative to rows/m: qslot[NQ] holds the output slot of every query row and -1
+    // for rows that are not queried; panel p then serves the queried rows among rows 128p..128p+127
+    // (queries stay aligned with the candidate tiles of a reordered copy)
+    const int32_t* qslot;
+    // Tile pruning (all nullptr / 0: every candidate tile is multiplied).  tile_c [T, d] and
+    // tile_r [T] are bounding balls of the candidate tiles of 128 rows (tile_r already inflated
+    // for rounding); gap_ws is scratch of gridDim.x * T floats.
+    const float* tile_c;
+    const float* tile_r;
+    float* gap_ws;
+    const int32_t* tile_colour;   // cross 1-NN only, optional [T]: the colour all valid rows of a tile
+                                  // share, or -1; a tile in the colour of all the panel's queries is skipped
+    int own_tile_first;    // self-join in the same row order: start each panel at its own tile
     unsigned long long* survivors;   // optional device counter: pairs that passed the filter
+    unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
 };
 
 float filter_slack_coefficient(int d);
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream);
+int sweep_grid_limit();   // upper bound of gridDim.x of a sweep launch (for sizing gap_ws); 0 on error
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream);
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);
 

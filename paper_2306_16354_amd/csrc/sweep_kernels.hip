@@ -40,7 +40,7 @@ constexpr unsigned long long LIST_SENTINEL = 0x7f8000007fffffffull;   // (+inf, 
 __host__ __device__ inline size_t sweep_lds_bytes(int KL)
 {
     return (size_t)(BM * LDK + BN * LDK + 2 * BN /*hc*/ + 2 * BN /*ccol*/ + BM /*bounds*/ + BM /*qid*/ +
-                    BM /*hq*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
+                    BM /*hq*/ + 8 /*wmax*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
 }
 
 // sum_t (a_t - b_t)^2 over d features by a group of 16 adjacent lanes; every lane of the group
@@ -144,7 +144,7 @@ __device__ inline void wave_list_insert(unsigned long long* list, int k, unsigne
 // LDS layout of a sweep workgroup (dynamic shared memory).
 template <int KL>
 struct SweepLds {
-    float* Qs; float* Cs; float* hcs; int* ccol; float* bounds; int* qid; float* hqs;
+    float* Qs; float* Cs; float* hcs; int* ccol; float* bounds; int* qid; float* hqs; float* wmax;
     unsigned long long* lists; unsigned short* queues;
     __device__ explicit SweepLds(unsigned char* base)
     {
@@ -155,7 +155,8 @@ struct SweepLds {
         bounds = reinterpret_cast<float*>(ccol + 2 * BN);
         qid = reinterpret_cast<int*>(bounds + BM);
         hqs = reinterpret_cast<float*>(qid + BM);
-        lists = reinterpret_cast<unsigned long long*>(hqs + BM);
+        wmax = hqs + BM;                                      // [2 parities][4 wavefronts]
+        lists = reinterpret_cast<unsigned long long*>(wmax + 8);
         queues = reinterpret_cast<unsigned short*>(lists + BM * KL);
     }
 };
@@ -165,13 +166,16 @@ extern __shared__ __align__(16) unsigned char sweep_smem[];
 // Rare path of the tile epilogue for one 32x32 block of a wavefront (a real call, so that its
 // registers do not weigh on the multiply loop): compact the pairs that pass the filter into the
 // wavefront's queue, re-evaluate each exactly, insert into the query lists, refresh the bounds.
-// `t` holds the block's accumulators, `tag` the lane's query row (k-NN: to skip itself) or the
-// lane's query colour (cross-colour 1-NN: to skip its own component).  Returns the number of
+// `t` holds the block's accumulators, `tag` the lane's query row (k-NN self-join: to skip itself;
+// -1 when nothing is to be skipped) or the lane's query colour (cross-colour 1-NN: to skip its
+// own component).  Returns the number of
 // pairs compacted (lane 0 only, 0 elsewhere).
 template <int KL, bool MASKED, bool VEC4>
 __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
                                                                int col0, int colbuf,
-                                                               const float* __restrict__ X,
+                                                               const float* __restrict__ Xq,
+                                                               const float* __restrict__ Xc,
+                                                               const int32_t* __restrict__ c_id,
                                                                int N, int d, int k)
 {
     const SweepLds<KL> L(sweep_smem);
@@ -188,7 +192,8 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
     for (int r = 0; r < 16; ++r) {
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
         const int cg = col0 + cl;
-        bool pred = real_query && (t[r] >= bound) && (cg < N);
+        // candidates past the end or padding rows carry h = +inf, i.e. an accumulator of -inf
+        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
         if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
         const unsigned long long mask = __ballot(pred);
@@ -210,14 +215,15 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
         const int ql = (int)(ent >> 8);
         const int cg = col0 + (int)(ent & 255u);
         const int qrow = L.qid[wave * 32 + ql];
-        const float* xa = X + (size_t)(valid ? qrow : 0) * d;
-        const float* xb = X + (size_t)(valid ? cg : 0) * d;
+        const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
+        const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
         const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
+        const int cid = (c_id && valid) ? c_id[cg] : cg;      // id that orders ties and is reported
         const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
         for (int g = 0; g < npass; ++g) {
             const float dg = __shfl(dist, g * 16);
             const int qlg = __shfl(ql, g * 16);
-            const int cgg = __shfl(cg, g * 16);
+            const int cgg = __shfl(cid, g * 16);
             wave_list_insert(mylists + (size_t)qlg * KL, k, make_key(dg, cgg),
                              L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
         }
@@ -239,10 +245,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     const int wave = tid >> 6;
     const int l32 = lane & 31;
     const int lhalf = lane >> 5;
-    const int N = p.N, d = p.d, k = p.k;
-    const float* __restrict__ X = p.X;
-    const float* __restrict__ hn = p.hn;
-    const int nq = MASKED ? p.m : N;
+    const int N = p.NC, d = p.d, k = p.k;          // N: candidate rows
+    const float* __restrict__ Xq = p.Xq;
+    const float* __restrict__ Xc = p.Xc;
+    const float* __restrict__ hq = p.hq;
+    const float* __restrict__ hc = p.hc;
+    const int nq = MASKED ? p.m : p.NQ;
     const int npanels = (nq + BM - 1) / BM;
     const int ntiles = (N + BN - 1) / BN;
     const int nchunks = (d + KC - 1) / KC;
@@ -257,9 +265,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
             const int qi = panel * BM + tid;
             int row = -1;
             if (qi < nq) row = (MASKED && p.rows) ? p.rows[qi] : qi;
-            if ((unsigned int)row >= (unsigned int)N) row = -1;      // never index X with a bad row
+            if ((unsigned int)row >= (unsigned int)p.NQ) row = -1;   // never index Xq with a bad row
+            if (!MASKED && p.q_out_row && row >= 0 && p.q_out_row[row] < 0) row = -1;   // padding row
             qid[tid] = row;
-            hqs[tid] = row >= 0 ? hn[row] : 0.f;
+            hqs[tid] = row >= 0 ? hq[row] : 0.f;
             bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
         }
         for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
@@ -277,7 +286,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         const int my_q_local = wave * 32 + l32;
         const int my_qrow = qid[my_q_local];
         int my_qcol = -1;
-        if (MASKED) my_qcol = my_qrow >= 0 ? p.colour[my_qrow] : -1;
+        if (MASKED) my_qcol = my_qrow >= 0 ? p.qcolour[my_qrow] : -1;
         float bound = bounds[my_q_local];
 
         v4f qreg[4], creg[4];
@@ -293,8 +302,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 for (int i = 0; i < 4; ++i) {
                     int crow = crow0 + 32 * i;
                     crow = crow < N ? crow : N - 1;
-                    qreg[i] = *reinterpret_cast<const v4f*>(X + (qoff[i] + c0));
-                    creg[i] = *reinterpret_cast<const v4f*>(X + ((unsigned int)crow * (unsigned int)d + c0));
+                    qreg[i] = *reinterpret_cast<const v4f*>(Xq + (qoff[i] + c0));
+                    creg[i] = *reinterpret_cast<const v4f*>(Xc + ((unsigned int)crow * (unsigned int)d + c0));
                 }
             } else {
 #pragma unroll
@@ -306,8 +315,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                     for (int e = 0; e < 4; ++e) {
                         const bool live = col + e < d;
                         const unsigned int ce = live ? (unsigned int)(col + e) : 0u;
-                        q[e] = X[qoff[i] + ce];
-                        c[e] = X[(unsigned int)crow * (unsigned int)d + ce];
+                        q[e] = Xq[qoff[i] + ce];
+                        c[e] = Xc[(unsigned int)crow * (unsigned int)d + ce];
                     }
                     qreg[i] = q;
                     creg[i] = c;
@@ -316,8 +325,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
             if (chunk == 0 && tid < BN) {
                 const int crow = tile * BN + tid;
                 const int cr = crow < N ? crow : N - 1;
-                hreg = hn[cr];
-                if (MASKED) colreg = p.colour[cr];
+                hreg = hc[cr];
+                if (MASKED) colreg = p.ccolour[cr];
             }
         };
 
@@ -403,11 +412,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 if (__any(any)) flagged |= 1u << b;
             }
             if (__builtin_expect(flagged != 0, 0)) {
-                const int my_tag = MASKED ? my_qcol : my_qrow;
-                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, 0, X, N, d, k);
-                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, 0, X, N, d, k);
-                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, 0, X, N, d, k);
-                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, 0, X, N, d, k);
+                const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
+                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
                 bound = bounds[my_q_local];
             }
         }
@@ -423,7 +432,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 int idx = (int)(unsigned int)(key & 0xffffffffull);
                 if (key == LIST_SENTINEL) idx = -1;
                 const size_t o = MASKED ? (size_t)(panel * BM + wave * 32 + ql)
-                                        : (size_t)row * k + lane;
+                                        : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + lane;
                 p.out_idx[o] = idx;
                 p.out_dist[o] = dist;
             }
@@ -439,7 +448,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 // variant uses for queries is the second candidate buffer), which leaves ONE barrier per chunk:
 // a wavefront can only overwrite buffer s&1 at step s+2 after every wavefront has passed the
 // barrier of step s+1, i.e. has finished multiplying step s.  The per-tile candidate half norms
-// and colours are double-buffered by tile parity for the same reason.
+// and colours are double-buffered by step parity for the same reason.
+//
+// Tile pruning (when p.tile_c is given; not in the paper, which multiplies every tile): at the
+// start of a panel the workgroup computes the bounding ball of its query rows and, for every
+// candidate tile, a lower bound on any query-candidate distance of the pair of balls,
+//     lb = max(0, |c_Q - c_T| - r_Q - r_T)^2     (rounded towards zero),
+// into its slice of gap_ws.  A tile whose bound exceeds the largest current threshold of the
+// panel's queries cannot change any list and is neither loaded nor multiplied.  Thresholds only
+// shrink, so testing against an older maximum is safe; the maximum is exchanged between the four
+// wavefronts through LDS slots that alternate with the step parity, which makes the skip decision
+// identical in all wavefronts (they have to agree on the barrier sequence).
 template <int KL, bool MASKED, int DCH>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
 {
@@ -452,36 +471,107 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     const int wave = tid >> 6;
     const int l32 = lane & 31;
     const int lhalf = lane >> 5;
-    const int N = p.N, d = p.d, k = p.k;
-    const float* __restrict__ X = p.X;
-    const float* __restrict__ hn = p.hn;
-    const int nq = MASKED ? p.m : N;
+    const int N = p.NC, d = p.d, k = p.k;          // N: candidate rows
+    const float* __restrict__ Xq = p.Xq;
+    const float* __restrict__ Xc = p.Xc;
+    const float* __restrict__ hq = p.hq;
+    const float* __restrict__ hc = p.hc;
+    // cross 1-NN with a slot map: panel p holds the query rows among rows 128p .. 128p+127
+    const bool aligned = MASKED && p.qslot != nullptr;
+    const int nq = (MASKED && !aligned) ? p.m : p.NQ;
     const int npanels = (nq + BM - 1) / BM;
     const int ntiles = (N + BN - 1) / BN;
     const int ld_row = tid >> 3;          // 0..31 (+32 i)
     const int ld_col = (tid & 7) * 4;     // 0..28
+    const bool prune = p.tile_c != nullptr;
+    float* __restrict__ gap = prune ? p.gap_ws + (size_t)blockIdx.x * ntiles : nullptr;
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
+    unsigned long long tiles_done = 0;
 
     for (int panel = blockIdx.x; panel < npanels; panel += gridDim.x) {
         __syncthreads();          // previous panel fully written out before its state is reused
         if (tid < BM) {
             const int qi = panel * BM + tid;
             int row = -1;
-            if (qi < nq) row = (MASKED && p.rows) ? p.rows[qi] : qi;
-            if ((unsigned int)row >= (unsigned int)N) row = -1;      // never index X with a bad row
+            if (qi < nq) row = (MASKED && !aligned && p.rows) ? p.rows[qi] : qi;
+            if ((unsigned int)row >= (unsigned int)p.NQ) row = -1;   // never index Xq with a bad row
+            if (!MASKED && p.q_out_row && row >= 0 && p.q_out_row[row] < 0) row = -1;   // padding row
+            if (aligned && row >= 0 && p.qslot[row] < 0) row = -1;                      // not queried
             qid[tid] = row;
-            hqs[tid] = row >= 0 ? hn[row] : 0.f;
+            hqs[tid] = row >= 0 ? hq[row] : 0.f;
             bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
         }
         for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
+        if (tid < 8) L.wmax[tid] = __builtin_inff();
         __syncthreads();
+        // a panel without a single query has nothing to do (every wavefront reads the same qid)
+        if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
+
+        if (prune) {
+            // ---- bounding ball of the panel's query rows (L.Cs is free here: d <= 128 floats)
+            float* qc = L.Cs;                       // centre
+            unsigned int* rq_bits = reinterpret_cast<unsigned int*>(L.Cs + 256);
+            int* col_lo = reinterpret_cast<int*>(L.Cs + 257);
+            int* col_hi = reinterpret_cast<int*>(L.Cs + 258);
+            if (tid == 0) { *rq_bits = 0u; *col_lo = 0x7fffffff; *col_hi = -0x7fffffff - 1; }
+            if (tid < d) {
+                float sum = 0.f;
+                int cnt = 0;
+                for (int r = 0; r < BM; ++r) {
+                    const int row = qid[r];
+                    if (row >= 0) { sum += Xq[(size_t)row * d + tid]; ++cnt; }
+                }
+                qc[tid] = cnt > 0 ? sum / (float)cnt : 0.f;
+            }
+            __syncthreads();
+            if (tid < BM && qid[tid] >= 0) {
+                const float* x = Xq + (size_t)qid[tid] * d;
+                float s2 = 0.f;
+                for (int t = 0; t < d; ++t) { const float e = x[t] - qc[t]; s2 = __builtin_fmaf(e, e, s2); }
+                atomicMax(rq_bits, __float_as_uint(__builtin_sqrtf(s2)));
+                if (MASKED && p.tile_colour) {
+                    const int c = p.qcolour[qid[tid]];
+                    atomicMin(col_lo, c);
+                    atomicMax(col_hi, c);
+                }
+            }
+            __syncthreads();
+            const float rq = __uint_as_float(*rq_bits);
+            // the colour all queries of the panel share (-2: they differ, or no colour summary)
+            const int panel_colour = (MASKED && p.tile_colour && *col_lo == *col_hi) ? *col_lo : -2;
+            for (int t = tid; t < ntiles; t += WG_THREADS) {
+                const float* c = p.tile_c + (size_t)t * d;
+                float s2 = 0.f;
+                for (int j = 0; j < d; j += 4) {
+                    const v4f cv = *reinterpret_cast<const v4f*>(c + j);
+                    const v4f qv = *reinterpret_cast<const v4f*>(qc + j);
+                    float e;
+                    e = cv[0] - qv[0]; s2 = __builtin_fmaf(e, e, s2);
+                    e = cv[1] - qv[1]; s2 = __builtin_fmaf(e, e, s2);
+                    e = cv[2] - qv[2]; s2 = __builtin_fmaf(e, e, s2);
+                    e = cv[3] - qv[3]; s2 = __builtin_fmaf(e, e, s2);
+                }
+                // rounding: the centre distance may be 2e-5 too large, the radii 2e-5 too small
+                const float rt = p.tile_r[t];
+                const float g = __builtin_sqrtf(s2) * (1.f - 2e-5f) - (rq + rt) * (1.f + 2e-5f);
+                float lb = g > 0.f ? g * g * (1.f - 1e-5f) : 0.f;
+                // NaN marks a tile that is never needed: no valid row, or (cross 1-NN) every row of
+                // it has the colour all queries of this panel have
+                if (rt < 0.f) lb = __builtin_nanf("");
+                if (MASKED && p.tile_colour && p.tile_colour[t] == panel_colour) lb = __builtin_nanf("");
+                gap[t] = lb;
+            }
+            __syncthreads();
+        }
 
         const int my_q_local = wave * 32 + l32;
         const int my_qrow = qid[my_q_local];
         int my_qcol = -1;
-        if (MASKED) my_qcol = my_qrow >= 0 ? p.colour[my_qrow] : -1;
+        if (MASKED) my_qcol = my_qrow >= 0 ? p.qcolour[my_qrow] : -1;
         float bound = bounds[my_q_local];
+        // largest threshold among this wavefront's queries (no query: nothing can enter a list)
+        float wave_thr_max = __any(my_qrow >= 0) ? __builtin_inff() : 0.f;
 
         // query fragments: lane (l32, lhalf) holds columns kk*8 + 4*lhalf .. +3 of its query row
         v4f qf[DCH * 4];
@@ -491,10 +581,43 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             for (int kk = 0; kk < DCH * 4; ++kk) {
                 const int col = kk * 8 + 4 * lhalf;
                 const bool live = col < d;
-                const v4f v = *reinterpret_cast<const v4f*>(X + (qo + (live ? (unsigned int)col : 0u)));
+                const v4f v = *reinterpret_cast<const v4f*>(Xq + (qo + (live ? (unsigned int)col : 0u)));
                 qf[kk] = live ? v : v4f{0.f, 0.f, 0.f, 0.f};
             }
         }
+
+        // Order in which the candidate tiles are visited: the panel's own tile first (self-join in
+        // the same row order), then the tiles after it, wrapping around.  In a spatially coherent
+        // order the nearest rows sit in the neighbouring tiles, so the thresholds tighten early.
+        // `scan` indices count from `base`; every lane of every wavefront evaluates next_scan on
+        // the same data, so its result is workgroup-uniform.
+        const int own_tile = (!MASKED && p.own_tile_first && panel < ntiles) ? panel : -1;
+        int base = 0;
+        if (own_tile >= 0) base = own_tile + 1;
+        else if (aligned) base = panel < ntiles ? panel : 0;
+        else if (prune && MASKED && qid[0] >= 0) base = qid[0] / BN;
+        const int nscan = own_tile >= 0 ? ntiles - 1 : ntiles;
+        auto tile_of = [&](int i) -> int {
+            if (i >= nscan) return ntiles;
+            const int t = base + i;
+            return t >= ntiles ? t - ntiles : t;
+        };
+        auto next_scan = [&](int i, float thr_max) -> int {
+            if (!prune) return i;
+            while (i < nscan) {
+                const int ii = i + lane;
+                bool need = false;
+                if (ii < nscan) {
+                    int t = base + ii;
+                    t = t >= ntiles ? t - ntiles : t;
+                    need = gap[t] <= thr_max;          // false for NaN
+                }
+                const unsigned long long mask = __ballot(need);
+                if (mask) return i + __builtin_ctzll(mask);
+                i += 64;
+            }
+            return nscan;
+        };
 
         v4f creg[4];
         float hreg = 0.f;
@@ -507,27 +630,36 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             for (int i = 0; i < 4; ++i) {
                 int crow = crow0 + 32 * i;
                 crow = crow < N ? crow : N - 1;
-                creg[i] = *reinterpret_cast<const v4f*>(X + ((unsigned int)crow * (unsigned int)d + c0));
+                creg[i] = *reinterpret_cast<const v4f*>(Xc + ((unsigned int)crow * (unsigned int)d + c0));
             }
             if (chunk == 0 && tid < BN) {
                 const int crow = tile * BN + tid;
                 const int cr = crow < N ? crow : N - 1;
-                hreg = hn[cr];
-                if (MASKED) colreg = p.colour[cr];
+                hreg = hc[cr];
+                if (MASKED) colreg = p.ccolour[cr];
             }
         };
 
         v16f acc[4];
-        gload(0, 0);
-        for (int tile = 0; tile < ntiles; ++tile) {
+        int scan_from = 0;                 // scan indices below this one are done or skipped
+        int tile = own_tile;
+        if (own_tile < 0) {
+            const int first = next_scan(0, __builtin_inff());
+            tile = tile_of(first);
+            scan_from = first + 1;
+        }
+        if (tile < ntiles) gload(tile, 0);
+        int step = 0;                      // multiplied tiles of this panel (buffer parity)
+        while (tile < ntiles) {
             const int col0 = tile * BN;
-            const int tpar = tile & 1;
+            const int tpar = step & 1;
             float* hcs = L.hcs + tpar * BN;
             int* ccol = L.ccol + tpar * BN;
+            int tile_after = ntiles;
 #pragma unroll
             for (int chunk = 0; chunk < DCH; ++chunk) {
                 // candidate buffer of this step: steps alternate between the two LDS buffers
-                float* Cb = (((DCH & 1) ? (tile + chunk) : chunk) & 1) ? L.Qs : L.Cs;
+                float* Cb = (((DCH & 1) ? (step + chunk) : chunk) & 1) ? L.Qs : L.Cs;
                 {
                     const bool live = chunk * KC + ld_col < d;
 #pragma unroll
@@ -542,10 +674,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     if (MASKED) ccol[tid] = in_range ? colreg : -1;
                 }
                 __syncthreads();
-                {
-                    int nt = tile, nc = chunk + 1;
-                    if (nc == DCH) { nc = 0; nt = tile + 1; }
-                    if (nt < ntiles) gload(nt, nc);
+                if (chunk + 1 < DCH) {
+                    gload(tile, chunk + 1);
+                } else {
+                    // thresholds published in the epilogue of the previous step (other parity)
+                    const float* wm = L.wmax + (tpar ^ 1) * 4;
+                    const float thr_max = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));
+                    const int nxt = next_scan(scan_from, thr_max);
+                    scan_from = nxt + 1;
+                    tile_after = tile_of(nxt);
+                    if (tile_after < ntiles) gload(tile_after, 0);
                 }
                 if (chunk == 0) {
 #pragma unroll
@@ -597,13 +735,33 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 if (__any(any)) flagged |= 1u << b;
             }
             if (__builtin_expect(flagged != 0, 0)) {
-                const int my_tag = MASKED ? my_qcol : my_qrow;
-                if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, X, N, d, k);
-                if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, X, N, d, k);
-                if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, X, N, d, k);
-                if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, X, N, d, k);
+                const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
+                if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
                 bound = bounds[my_q_local];
+                if (prune) {
+                    // largest threshold of this wavefront's 32 queries: thr = 2 (h_q - bound)
+                    float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
+                    t = fmaxf(t, __shfl_xor(t, 1));
+                    t = fmaxf(t, __shfl_xor(t, 2));
+                    t = fmaxf(t, __shfl_xor(t, 4));
+                    t = fmaxf(t, __shfl_xor(t, 8));
+                    t = fmaxf(t, __shfl_xor(t, 16));
+                    // 2 (h_q - bound) reproduces the threshold up to a few ulps of h_q; widen it
+                    wave_thr_max = t + 4.f * 1.1920929e-07f * fmaxf(fabsf(hqs[my_q_local]), t);
+                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 1));
+                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 2));
+                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 4));
+                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 8));
+                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
+                }
             }
+            if (prune && lane == 0) L.wmax[tpar * 4 + wave] = wave_thr_max;
+            ++tiles_done;
+            ++step;
+            tile = tile_after;
         }
 
         // ---- panel epilogue: lists are already ascending; write them out ----
@@ -616,14 +774,15 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 const float dist = __uint_as_float((unsigned int)(key >> 32));
                 int idx = (int)(unsigned int)(key & 0xffffffffull);
                 if (key == LIST_SENTINEL) idx = -1;
-                const size_t o = MASKED ? (size_t)(panel * BM + wave * 32 + ql)
-                                        : (size_t)row * k + lane;
+                const size_t o = MASKED ? (size_t)(aligned ? p.qslot[row] : panel * BM + wave * 32 + ql)
+                                        : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + lane;
                 p.out_idx[o] = idx;
                 p.out_dist[o] = dist;
             }
         }
     }
     if (p.survivors && lane == 0 && survivors) atomicAdd(p.survivors, survivors);
+    if (p.tiles_done && tid == 0 && tiles_done) atomicAdd(p.tiles_done, tiles_done);
 }
 
 // ------------------------------------------------------------------------------- launchers
@@ -680,13 +839,15 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     int cus = 0;
     hipError_t e = device_cus(&cus);
     if (e != hipSuccess) return e;
-    const int nq = MASKED ? p.m : p.N;
+    const bool aligned = MASKED && p.qslot != nullptr;
+    const int nq = (MASKED && !aligned) ? p.m : p.NQ;
     const int npanels = (nq + BM - 1) / BM;
+    if (npanels < 1) return hipSuccess;
     const size_t lds = sweep_lds_bytes(KL);
     const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
     int grid = cus * per_cu;
     if (grid > npanels) grid = npanels;
-    const bool vec4 = (p.d % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.X) & 15) == 0);
+    const bool vec4 = (p.d % 4 == 0) && (((reinterpret_cast<uintptr_t>(p.Xq) | reinterpret_cast<uintptr_t>(p.Xc)) & 15) == 0);
     if (vec4 && p.d <= 4 * KC) {
         // up to 128 features: query fragments live in registers
         const int dch = (p.d + KC - 1) / KC;
@@ -695,8 +856,17 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
         if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3>, grid, lds, p, stream);
         return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4>, grid, lds, p, stream);
     }
+    // tile pruning and the slot map exist in the register-resident-query variant only
+    if (p.tile_c || p.qslot || p.tile_colour) return hipErrorInvalidValue;
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
     return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
+}
+
+int sweep_grid_limit()
+{
+    int cus = 0;
+    if (device_cus(&cus) != hipSuccess) return 0;
+    return 2 * cus;
 }
 
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream)

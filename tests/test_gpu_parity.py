@@ -344,6 +344,60 @@ def test_slhc_tiny(lib):
         check_slhc(X, out, tie_free=True)
 
 
+# ----------------------------------------------------------------------------- tile pruning
+# Pruning (SLHC_PRUNE) only skips work that cannot change a list, and ties are ordered by the
+# caller's row ids in both modes, so its results must be bit-identical to the unpruned sweep.
+@pytest.mark.parametrize("name,n", [("c1", None), ("c2", 20000), ("c3", 12000), ("c5", 30000)])
+def test_pruned_knn_is_identical(lib, name, n):
+    X, _, k = gen.make(name, n=n)
+    print(f"pruned knn {name} N={X.shape[0]} d={X.shape[1]} k={k}", flush=True)
+    Xd = torch.from_numpy(X).cuda()
+    i0, d0 = lib.knn_graph(Xd, k, prune=False)
+    i1, d1 = lib.knn_graph(Xd, k, prune=True)
+    torch.cuda.synchronize()
+    assert torch.equal(i0, i1) and torch.equal(d0, d1)
+    rows = np.random.default_rng(5).choice(X.shape[0], size=300, replace=False)
+    check_knn(X, k, i1.cpu().numpy()[rows], d1.cpu().numpy()[rows], rows=rows, min_exact=0.9)
+
+
+def test_pruned_knn_lattice_and_ragged(lib):
+    X = gen.integer_lattice(9, 3, seed=4)                      # ties everywhere
+    Xd = torch.from_numpy(X).cuda()
+    i0, d0 = lib.knn_graph(Xd, 20, prune=False)
+    i1, d1 = lib.knn_graph(Xd, 20, prune=True)
+    torch.cuda.synchronize()
+    assert torch.equal(i0, i1) and torch.equal(d0, d1)
+    oi, od = oracle.knn_graph(X, 20)
+    assert np.array_equal(i1.cpu().numpy(), oi)
+    for N, d, k in [(2, 4, 1), (130, 20, 7), (1037, 36, 33), (5000, 128, 64)]:
+        X = np.random.default_rng(N).standard_normal((N, d)).astype(np.float32)
+        Xd = torch.from_numpy(X).cuda()
+        i0, d0 = lib.knn_graph(Xd, k, prune=False)
+        i1, d1 = lib.knn_graph(Xd, k, prune=True)
+        torch.cuda.synchronize()
+        assert torch.equal(i0, i1) and torch.equal(d0, d1), (N, d, k)
+
+
+@pytest.mark.parametrize("name,n", [("c1", None), ("c2", 15000), ("c3", 10000), ("c5", 20000)])
+def test_pruned_slhc_is_identical(lib, name, n):
+    X, _, k = gen.make(name, n=n)
+    print(f"pruned slhc {name} N={X.shape[0]} d={X.shape[1]} k={k}", flush=True)
+    Xd = torch.from_numpy(X).cuda()
+    a = lib.slhc(Xd, k, prune=False)
+    b = lib.slhc(Xd, k, prune=True)
+    assert a["stats"]["pruned"] == 0 and b["stats"]["pruned"] == 1
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(a[name_], b[name_]), name_
+    T = (X.shape[0] + 127) // 128
+    assert a["stats"]["knn_tile_steps"] == T * T
+    Ts = (b["stats"]["order_padded_rows"] + 127) // 128       # the reordered copy has padding rows
+    assert X.shape[0] <= b["stats"]["order_padded_rows"] <= X.shape[0] + X.shape[0] // 2 + 256
+    assert b["stats"]["knn_tile_steps"] <= Ts * Ts
+    print("tile steps", b["stats"]["knn_tile_steps"], "of", T * T, "connect", b["stats"]["connect_tile_steps"],
+          "vs", a["stats"]["connect_tile_steps"], "pivots", b["stats"]["order_pivots"], "padded rows",
+          b["stats"]["order_padded_rows"], "order ms", round(b["stats"]["ms_order"], 2), flush=True)
+
+
 # ----------------------------------------------------------------------------- full size (headline)
 def test_headline_full_size_properties(lib):
     """c3 at its full size (1M x 128, k=32), in the launch configuration bench.py times.  The
