@@ -41,6 +41,9 @@ hipError_t order_gather_padded(const float* X, const float* h, const int32_t* pe
 hipError_t order_tile_balls(const float* Xs, const int32_t* perm, int n_padded, int d, float* tile_c,
                             float* tile_r, hipStream_t s);
 
+// for j < m: row list[j] adopts pivot base + new_idx[j] (new_idx in [0, count)) when new_dist[j] < pdist[row]
+hipError_t order_adopt_pivots(const uint32_t* list, int m, int N, const int32_t* new_idx, const float* new_dist,
+                              int base, int count, int32_t* pid, float* pdist, hipStream_t s);
 // tile_colour[t] = the colour shared by all rows with colour_s >= 0 of tile t, or -1
 hipError_t order_tile_colours(const int32_t* colour_s, int n_padded, int32_t* tile_colour, hipStream_t s);
 // slot[inv[list[q]]] = q for q < m (slot pre-filled with -1 by the caller)

@@ -185,6 +185,20 @@ static bool vec4_ok(const void* a, const void* b, int d)
     return d % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0;
 }
 
+// row = list[j] adopts pivot base + new_idx[j] when that pivot is closer than its current one
+__global__ void __launch_bounds__(TB) k_adopt_pivots(const uint32_t* __restrict__ list, int m, int N,
+                                                     const int32_t* __restrict__ new_idx,
+                                                     const float* __restrict__ new_dist, int base, int count,
+                                                     int32_t* __restrict__ pid, float* __restrict__ pdist)
+{
+    const int j = blockIdx.x * TB + threadIdx.x;
+    if (j >= m) return;
+    const uint32_t row = list[j];
+    const int c = new_idx[j];
+    if (row >= (uint32_t)N || (unsigned int)c >= (unsigned int)count) return;
+    if (new_dist[j] < pdist[row]) { pid[row] = base + c; pdist[row] = new_dist[j]; }
+}
+
 // one wavefront per tile: the colour shared by all valid rows (colour >= 0), else -1
 __global__ void __launch_bounds__(TB) k_tile_colours(const int32_t* __restrict__ colour_s, int n_padded, int T,
                                                      int32_t* __restrict__ tile_colour)
@@ -331,6 +345,14 @@ hipError_t order_tile_balls(const float* Xs, const int32_t* perm, int n_padded, 
     const int T = (n_padded + TILE - 1) / TILE;
     hipLaunchKernelGGL(k_tile_balls, dim3(T), dim3(TB), (size_t)(d + 4) * sizeof(float), s, Xs, perm, n_padded, d,
                        tile_c, tile_r);
+    return hipGetLastError();
+}
+
+hipError_t order_adopt_pivots(const uint32_t* list, int m, int N, const int32_t* new_idx, const float* new_dist,
+                              int base, int count, int32_t* pid, float* pdist, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_adopt_pivots, dim3(blocks_for(m)), dim3(TB), 0, s, list, m, N, new_idx, new_dist, base, count,
+                       pid, pdist);
     return hipGetLastError();
 }
 

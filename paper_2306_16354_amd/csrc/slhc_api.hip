@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -88,6 +89,39 @@ struct EventPair {
     hipError_t create() { hipError_t e = hipEventCreate(&a); return e != hipSuccess ? e : hipEventCreate(&b); }
     ~EventPair() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
     float ms() const { float t = 0.f; return hipEventElapsedTime(&t, a, b) == hipSuccess ? t : -1.f; }
+};
+
+double now_ms()
+{
+    using clk = std::chrono::steady_clock;
+    return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
+}
+
+// SLHC_LOG=1 in the environment: phase times and per-round counters on stderr (each mark waits for
+// the stream, so the logged run is slower than a normal one).
+struct PhaseLog {
+    bool on;
+    hipStream_t s;
+    double t;
+    explicit PhaseLog(hipStream_t stream) : s(stream), t(0.0)
+    {
+        const char* e = std::getenv("SLHC_LOG");
+        on = e && e[0] && e[0] != '0';
+        if (on) t = now_ms();
+    }
+    void mark(const char* fmt, ...)
+    {
+        if (!on) return;
+        (void)hipStreamSynchronize(s);
+        const double now = now_ms();
+        char text[256];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(text, sizeof(text), fmt, ap);
+        va_end(ap);
+        std::fprintf(stderr, "[slhc] %8.2f ms  %s\n", now - t, text);
+        t = now_ms();
+    }
 };
 
 // Tile pruning is implemented by the register-resident-query sweep only (d <= 128, d % 4 == 0), and
@@ -229,6 +263,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
 {
     const int n = (int)N;
     const int P1 = o.P1;
+    PhaseLog log(s);
     PinnedHost pin;
     HIP_TRY(pin.alloc(((size_t)OrderWs::SAMPLE + 16 + 6 * (size_t)o.Pmax) * 4));
     float* h_sample = static_cast<float*>(pin.p);
@@ -248,6 +283,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
     HIP_TRY(slhc::order_pick_f32(o.pdist, n, S, o.sample, s));
     HIP_TRY(hipMemcpyAsync(h_sample, o.sample, (size_t)S * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    log.mark("row order: %d pivots, nearest pivot of every row", P1);
     float tau = __builtin_inff();          // 4 x median positive squared distance to the pivot
     {
         std::vector<float> v;
@@ -257,8 +293,11 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
             tau = 4.f * v[v.size() / 2];
         }
     }
+    // Rows much farther from their pivot than the typical row: clusters without a pivot.  Every 16th
+    // of them (in row order) becomes a pivot and the far rows alone are re-assigned among the new
+    // pivots; repeated until no row is far, the pivot budget is used, or four rounds are done.
     int P = P1;
-    if (std::isfinite(tau)) {
+    for (int round = 0; round < 4 && std::isfinite(tau) && P < o.Pmax; ++round) {
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(o.far_count), 64);
         HIP_TRY(hipGetLastError());
         HIP_TRY(slhc::order_mark_far(o.pdist, n, tau, o.tmp_a, o.far_count, s));
@@ -266,19 +305,26 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
         HIP_TRY(hipStreamSynchronize(s));
         const int far = h_count[0];
         if (far < 0 || far > n) { set_err("row order: bad far-row count %d", far); return SLHC_INTERNAL; }
-        if (far > 0) {
-            // far rows first, in row order (stable 1-bit sort); every 16th becomes a pivot
-            HIP_TRY(slhc::order_iota(reinterpret_cast<int32_t*>(o.tmp_b), n, s));
-            HIP_TRY(slhc::pair_sort_u32(o.tmp_a, o.tmp_c, o.tmp_b, reinterpret_cast<uint32_t*>(o.perm), n, 1,
-                                        o.sort_temp, o.sort_temp_bytes, s));
-            int P2 = (far + 15) / 16;
-            if (P2 > P1) P2 = P1;
-            HIP_TRY(slhc::order_pick_listed_rows(X, hn, reinterpret_cast<const uint32_t*>(o.perm), far, n, d, P2,
-                                                 o.Xp + (size_t)P1 * d, o.hp + P1, s));
-            P = P1 + P2;
-            rc = assign_to_pivots(X, N, d, hn, o, P, s);
-            if (rc != SLHC_OK) return rc;
-        }
+        if (far == 0) break;
+        // far rows first, in row order (stable 1-bit sort)
+        uint32_t* far_rows = reinterpret_cast<uint32_t*>(o.perm);
+        HIP_TRY(slhc::order_iota(reinterpret_cast<int32_t*>(o.tmp_b), n, s));
+        HIP_TRY(slhc::pair_sort_u32(o.tmp_a, o.tmp_c, o.tmp_b, far_rows, n, 1, o.sort_temp, o.sort_temp_bytes, s));
+        int P2 = (far + 15) / 16;
+        if (P2 > o.Pmax - P) P2 = o.Pmax - P;
+        HIP_TRY(slhc::order_pick_listed_rows(X, hn, far_rows, far, n, d, P2, o.Xp + (size_t)P * d, o.hp + P, s));
+        // the far rows as a compact query matrix (the buffer of the reordered copy is still free)
+        HIP_TRY(slhc::order_pick_listed_rows(X, hn, far_rows, far, n, d, far, o.Xs, o.hs, s));
+        slhc::SweepParams p{};
+        p.Xq = o.Xs; p.hq = o.hs; p.NQ = far;
+        p.Xc = o.Xp + (size_t)P * d; p.hc = o.hp + P; p.NC = P2;
+        p.d = d; p.k = 1;
+        p.out_idx = reinterpret_cast<int32_t*>(o.tmp_b); p.out_dist = reinterpret_cast<float*>(o.tmp_c);
+        HIP_TRY(slhc::launch_knn_sweep(p, s));
+        HIP_TRY(slhc::order_adopt_pivots(far_rows, far, n, reinterpret_cast<const int32_t*>(o.tmp_b),
+                                         reinterpret_cast<const float*>(o.tmp_c), P, P2, o.pid, o.pdist, s));
+        P += P2;
+        log.mark("row order: %d far rows -> %d more pivots", far, P2);
     }
     o.P = P;
 
@@ -324,6 +370,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
         order[0] = 0;
     }
     for (int r = 0; r < P; ++r) h_rank[order[(size_t)r]] = r;
+    log.mark("row order: single linkage of %d pivots, leaf order", P);
 
     // ---- 3. cell sizes and the padded layout
     HIP_TRY(slhc::order_fill_i32(o.counts, P, 0, s));
@@ -366,6 +413,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
     HIP_TRY(slhc::order_gather_padded(X, hn, o.perm, o.Ns, n, d, o.Xs, o.hs, s));
     HIP_TRY(slhc::order_tile_balls(o.Xs, o.perm, o.Ns, d, o.tile_c, o.tile_r, s));
     HIP_TRY(hipStreamSynchronize(s));        // the pinned staging buffer is released on return
+    log.mark("row order: %d rows placed in %d (tau %.4g, padding above %.4g), tile balls", n, o.Ns, (double)tau, (double)tau_pad);
     return SLHC_OK;
 }
 
@@ -399,18 +447,16 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         p.q_out_row = o.perm; p.c_id = o.perm;
         p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
         p.own_tile_first = 1;
+        p.panel_counter = reinterpret_cast<unsigned int*>(ws.counters + 8);     // zeroed above
+#ifdef SLHC_PHASE_TIMERS
+        p.phase_cycles = ws.counters + 16;
+#endif
     } else {
         p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
     }
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));
     return SLHC_OK;
-}
-
-double now_ms()
-{
-    using clk = std::chrono::steady_clock;
-    return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
 }
 
 // Linkage arrays from weight-sorted tree edges (paper Sec. 3.3.1): a union-find over the
@@ -572,6 +618,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     slhc_stats st;
     std::memset(&st, 0, sizeof(st));
     const double t_begin = now_ms();
+    PhaseLog log(s);
 
     // ---- k-NN graph (Alg. "cuSLINK Algorithm", first step)
     EventPair ev_norm, ev_order, ev_knn, ev_conn;
@@ -593,6 +640,8 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     st.ms_norm_kernel = ev_norm.ms();
     st.ms_order = ev_order.ms();
     st.ms_knn_kernel = ev_knn.ms();
+    log.mark("k-NN graph of %lld rows: order %.2f ms, sweep %.2f ms, %llu tile steps", (long long)N, st.ms_order,
+             st.ms_knn_kernel, h_surv[2]);
     const double t_knn = now_ms();
     st.ms_knn = (float)(t_knn - t_begin);
 
@@ -651,6 +700,12 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 p.c_id = o.perm;
                 p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
                 p.tile_colour = o.tile_colour;
+                p.panel_counter = reinterpret_cast<unsigned int*>(kws.counters + 8);
+#ifdef SLHC_PHASE_TIMERS
+                p.phase_cycles = kws.counters + 24;
+#endif
+                hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, p.panel_counter, 1);
+                HIP_TRY(hipGetLastError());
             } else {
                 p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
                 p.qcolour = p.ccolour = ws.colour;
@@ -663,6 +718,12 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
             HIP_TRY(hipStreamSynchronize(s));
             st.ms_connect_kernels += ev_conn.ms();
             ms_connect += now_ms() - tc0;
+            if (log.on) {
+                HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                log.mark("round %d: %d components, %d rows queried, sweep %.2f ms, %llu tile steps so far",
+                         st.boruvka_rounds, (int)(N - edges), nq, ev_conn.ms(), h_surv[3]);
+            }
         }
         HIP_TRY(slhc::forest_select_edges(f, s));
         HIP_TRY(slhc::forest_commit(f, s));
@@ -682,6 +743,17 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     }
     HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+#ifdef SLHC_PHASE_TIMERS
+    if (log.on) {
+        unsigned long long* h_ph = h_surv + 4;           // 64-byte staging buffer: not enough, use two copies
+        for (int part = 0; part < 4; ++part) {
+            HIP_TRY(hipMemcpyAsync(h_ph, kws.counters + 16 + 4 * part, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            std::fprintf(stderr, "[slhc] %s phase cycles %d..%d: %llu %llu %llu %llu\n", part < 2 ? "k-NN" : "connect",
+                         4 * (part & 1), 4 * (part & 1) + 3, h_ph[0], h_ph[1], h_ph[2], h_ph[3]);
+        }
+    }
+#endif
     st.connect_filter_survivors = (int64_t)h_surv[1];
     st.connect_tile_steps = (int64_t)h_surv[3];
     st.pruned = pruned ? 1 : 0;

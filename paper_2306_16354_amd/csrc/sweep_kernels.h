@@ -35,9 +35,14 @@ struct SweepParams {
     float* gap_ws;
     const int32_t* tile_colour;   // cross 1-NN only, optional [T]: the colour all valid rows of a tile
                                   // share, or -1; a tile in the colour of all the panel's queries is skipped
+    unsigned int* panel_counter;  // optional device word, zero at launch: panels are taken from it one at
+                                  // a time instead of round-robin (use when panel costs differ widely)
     int own_tile_first;    // self-join in the same row order: start each panel at its own tile
     unsigned long long* survivors;   // optional device counter: pairs that passed the filter
     unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
+#ifdef SLHC_PHASE_TIMERS
+    unsigned long long* phase_cycles;   // study builds: [8] cycles per phase of the panel loop
+#endif
 };
 
 float filter_slack_coefficient(int d);

@@ -40,7 +40,7 @@ constexpr unsigned long long LIST_SENTINEL = 0x7f8000007fffffffull;   // (+inf, 
 __host__ __device__ inline size_t sweep_lds_bytes(int KL)
 {
     return (size_t)(BM * LDK + BN * LDK + 2 * BN /*hc*/ + 2 * BN /*ccol*/ + BM /*bounds*/ + BM /*qid*/ +
-                    BM /*hq*/ + 8 /*wmax*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
+                    BM /*hq*/ + 8 /*wmax*/ + 8 /*next panel*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
 }
 
 // sum_t (a_t - b_t)^2 over d features by a group of 16 adjacent lanes; every lane of the group
@@ -78,6 +78,55 @@ __device__ inline float group16_sqdist(const float* __restrict__ a, const float*
     s += __shfl_xor(s, 4);
     s += __shfl_xor(s, 8);
     return s;
+}
+
+// The same sum, bit for bit, computed by a group of 8 adjacent lanes: lane g plays lanes g and g+8
+// of the 16-lane scheme with two accumulators, each set of eight partial sums goes through the
+// xor butterfly (1, 2, 4), and the two totals are added last - exactly the additions the 16-lane
+// butterfly performs.  Twice as many pairs per wavefront pass, and all loads are issued up front.
+template <bool VEC4>
+__device__ inline float group8_sqdist(const float* __restrict__ a, const float* __restrict__ b,
+                                      int d, int g, bool active)
+{
+    float s0 = 0.f, s1 = 0.f;
+    if (active) {
+        if (VEC4) {
+            for (int t = 4 * g; t < d; t += 64) {
+                const v4f va = *reinterpret_cast<const v4f*>(a + t);
+                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
+                float e;
+                e = va[0] - vb[0]; s0 = __builtin_fmaf(e, e, s0);
+                e = va[1] - vb[1]; s0 = __builtin_fmaf(e, e, s0);
+                e = va[2] - vb[2]; s0 = __builtin_fmaf(e, e, s0);
+                e = va[3] - vb[3]; s0 = __builtin_fmaf(e, e, s0);
+            }
+            for (int t = 4 * (g + 8); t < d; t += 64) {
+                const v4f va = *reinterpret_cast<const v4f*>(a + t);
+                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
+                float e;
+                e = va[0] - vb[0]; s1 = __builtin_fmaf(e, e, s1);
+                e = va[1] - vb[1]; s1 = __builtin_fmaf(e, e, s1);
+                e = va[2] - vb[2]; s1 = __builtin_fmaf(e, e, s1);
+                e = va[3] - vb[3]; s1 = __builtin_fmaf(e, e, s1);
+            }
+        } else {
+            for (int t0 = 4 * g; t0 < d; t0 += 64) {
+                const int te = (t0 + 4 < d) ? t0 + 4 : d;
+                for (int t = t0; t < te; ++t) { const float e = a[t] - b[t]; s0 = __builtin_fmaf(e, e, s0); }
+            }
+            for (int t0 = 4 * (g + 8); t0 < d; t0 += 64) {
+                const int te = (t0 + 4 < d) ? t0 + 4 : d;
+                for (int t = t0; t < te; ++t) { const float e = a[t] - b[t]; s1 = __builtin_fmaf(e, e, s1); }
+            }
+        }
+    }
+    s0 += __shfl_xor(s0, 1);
+    s0 += __shfl_xor(s0, 2);
+    s0 += __shfl_xor(s0, 4);
+    s1 += __shfl_xor(s1, 1);
+    s1 += __shfl_xor(s1, 2);
+    s1 += __shfl_xor(s1, 4);
+    return s0 + s1;
 }
 
 // h_i = (1-c)/2 * ||x_i||^2 ; one 16-lane group per row.
@@ -155,28 +204,26 @@ struct SweepLds {
         bounds = reinterpret_cast<float*>(ccol + 2 * BN);
         qid = reinterpret_cast<int*>(bounds + BM);
         hqs = reinterpret_cast<float*>(qid + BM);
-        wmax = hqs + BM;                                      // [2 parities][4 wavefronts]
-        lists = reinterpret_cast<unsigned long long*>(wmax + 8);
+        wmax = hqs + BM;                                      // [2 parities][4 wavefronts], then 8 spare words
+        lists = reinterpret_cast<unsigned long long*>(wmax + 16);
         queues = reinterpret_cast<unsigned short*>(lists + BM * KL);
     }
 };
 
 extern __shared__ __align__(16) unsigned char sweep_smem[];
 
-// Rare path of the tile epilogue for one 32x32 block of a wavefront (a real call, so that its
-// registers do not weigh on the multiply loop): compact the pairs that pass the filter into the
-// wavefront's queue, re-evaluate each exactly, insert into the query lists, refresh the bounds.
-// `t` holds the block's accumulators, `tag` the lane's query row (k-NN self-join: to skip itself;
-// -1 when nothing is to be skipped) or the lane's query colour (cross-colour 1-NN: to skip its
-// own component).  Returns the number of
-// pairs compacted (lane 0 only, 0 elsewhere).
-template <int KL, bool MASKED, bool VEC4>
-__device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
-                                                               int col0, int colbuf,
-                                                               const float* __restrict__ Xq,
-                                                               const float* __restrict__ Xc,
-                                                               const int32_t* __restrict__ c_id,
-                                                               int N, int d, int k)
+// Rare path of the tile epilogue, in two real calls so that its registers do not weigh on the
+// multiply loop.
+//
+// compact_block: stream-compacts the pairs of one 32x32 block that pass the filter into the
+// wavefront's queue (entry = query lane << 8 | candidate row within the tile).  `t` holds the
+// block's accumulators, `tag` the lane's query row (k-NN self-join: to skip itself; -1 when nothing
+// is to be skipped) or the lane's query colour (cross-colour 1-NN: to skip its own component).
+// Returns the new queue length, or -1 (nothing written) when the block does not fit: the caller
+// then resolves the queue and calls again.
+template <int KL, bool MASKED>
+__device__ __attribute__((noinline)) int compact_block(v16f t, int b, float bound, int tag, int col0,
+                                                       int colbuf, int N, int qcount)
 {
     const SweepLds<KL> L(sweep_smem);
     const int* ccol = L.ccol + colbuf * BN;
@@ -185,9 +232,9 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
     const int l32 = lane & 31;
     const int lhalf = lane >> 5;
     unsigned short* myq = L.queues + wave * QCAP;
-    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
-    int qcount = 0;
     const bool real_query = L.qid[wave * 32 + l32] >= 0;    // padding rows of the last panel
+    unsigned long long masks[16];
+    int total = 0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
@@ -196,19 +243,40 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
         bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
         if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
-        const unsigned long long mask = __ballot(pred);
+        masks[r] = __ballot(pred);
+        total += __popcll(masks[r]);
+    }
+    if (qcount + total > QCAP) return -1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const unsigned long long mask = masks[r];
         if (mask) {
+            const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
             const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
                               __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
-            if (pred) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
+            if ((mask >> lane) & 1ull) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
             qcount += __popcll(mask);
         }
     }
-    if (qcount == 0) return 0u;
+    return qcount;
+}
+
+// resolve_queue: re-evaluates every queued pair exactly (eight pairs per pass, 8 lanes each),
+// drops those that do not beat their query's current k-th entry, inserts the rest into the query
+// lists and refreshes the bounds.
+template <int KL, bool VEC4>
+__device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, const float* __restrict__ Xq,
+                                                        const float* __restrict__ Xc,
+                                                        const int32_t* __restrict__ c_id, int d, int k)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const unsigned short* myq = L.queues + wave * QCAP;
+    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
     __builtin_amdgcn_wave_barrier();
-    // exact re-evaluation, four queued pairs per pass (16 lanes each)
-    const int grp = lane >> 4, g16 = lane & 15;
-    for (int s = 0; s < qcount; s += 4) {
+    const int grp = lane >> 3, g8 = lane & 7;
+    for (int s = 0; s < qcount; s += 8) {
         const int e = s + grp;
         const bool valid = e < qcount;
         const unsigned int ent = valid ? myq[e] : 0u;
@@ -217,20 +285,50 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
         const int qrow = L.qid[wave * 32 + ql];
         const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
         const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
-        const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
-        const int cid = (c_id && valid) ? c_id[cg] : cg;      // id that orders ties and is reported
-        const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
-        for (int g = 0; g < npass; ++g) {
-            const float dg = __shfl(dist, g * 16);
-            const int qlg = __shfl(ql, g * 16);
-            const int cgg = __shfl(cid, g * 16);
-            wave_list_insert(mylists + (size_t)qlg * KL, k, make_key(dg, cgg),
+        const int cid = (c_id && valid) ? c_id[cg] : cg;          // id that orders ties and is reported
+        const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
+        const unsigned long long key = make_key(dist, cid);
+        // a stale k-th entry is only larger than the current one, so this test never drops a
+        // pair that belongs in the list; wave_list_insert tests again
+        const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
+        unsigned long long todo = __ballot(accept);
+        while (todo) {
+            const int src = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const unsigned int klo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)key, src);
+            const unsigned int khi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(key >> 32), src);
+            const int qlg = __builtin_amdgcn_readlane(ql, src);
+            wave_list_insert(mylists + (size_t)qlg * KL, k, ((unsigned long long)khi << 32) | klo,
                              L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
         }
     }
     __builtin_amdgcn_wave_barrier();
-    return lane == 0 ? (unsigned int)qcount : 0u;
 }
+
+// Tile epilogue after the hot filter flagged blocks `flagged` of this wavefront: all blocks go
+// through one queue, so the exact re-evaluation runs once per tile step.  Expands at its call site
+// with static block indices (a dynamic index into the accumulators would spill them).
+#define SLHC_SELECT_TILE(KL_, MASKED_, VEC4_)                                                               \
+    do {                                                                                                    \
+        int qn_ = 0;                                                                                        \
+        _Pragma("unroll") for (int b_ = 0; b_ < 4; ++b_) {                                                  \
+            if (flagged & (1u << b_)) {                                                                     \
+                int r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_);    \
+                if (r_ < 0) {                                                                               \
+                    survivors += (unsigned int)qn_;                                                         \
+                    resolve_queue<KL_, VEC4_>(qn_, col0, Xq, Xc, p.c_id, d, k);                             \
+                    bound = bounds[my_q_local];                                                             \
+                    r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, 0);      \
+                }                                                                                           \
+                qn_ = r_;                                                                                   \
+            }                                                                                               \
+        }                                                                                                   \
+        if (qn_ > 0) {                                                                                      \
+            survivors += (unsigned int)qn_;                                                                 \
+            resolve_queue<KL_, VEC4_>(qn_, col0, Xq, Xc, p.c_id, d, k);                                     \
+            bound = bounds[my_q_local];                                                                     \
+        }                                                                                                   \
+    } while (0)
 
 template <int KL, bool MASKED, bool VEC4>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
@@ -413,11 +511,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
             }
             if (__builtin_expect(flagged != 0, 0)) {
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
-                if (flagged & 1u) survivors += select_block<KL, MASKED, VEC4>(acc[0], 0, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 2u) survivors += select_block<KL, MASKED, VEC4>(acc[1], 1, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 4u) survivors += select_block<KL, MASKED, VEC4>(acc[2], 2, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 8u) survivors += select_block<KL, MASKED, VEC4>(acc[3], 3, bound, my_tag, col0, 0, Xq, Xc, p.c_id, N, d, k);
-                bound = bounds[my_q_local];
+                const int colbuf_ = 0;
+                SLHC_SELECT_TILE(KL, MASKED, VEC4);
             }
         }
 
@@ -459,6 +554,19 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 // shrink, so testing against an older maximum is safe; the maximum is exchanged between the four
 // wavefronts through LDS slots that alternate with the step parity, which makes the skip decision
 // identical in all wavefronts (they have to agree on the barrier sequence).
+// Study builds (-DSLHC_PHASE_TIMERS): thread 0 of every workgroup accumulates shader-clock cycles per
+// phase of the panel loop into p.phase_cycles[0..7].  Not compiled into the product library.
+#ifdef SLHC_PHASE_TIMERS
+#define PHASE_MARK(i)                                              \
+    do {                                                           \
+        const unsigned long long now_ = clock64();                 \
+        ph[i] += now_ - ph_t;                                      \
+        ph_t = now_;                                               \
+    } while (0)
+#else
+#define PHASE_MARK(i) do { } while (0)
+#endif
+
 template <int KL, bool MASKED, int DCH>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
 {
@@ -488,9 +596,22 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
     unsigned long long tiles_done = 0;
+#ifdef SLHC_PHASE_TIMERS
+    unsigned long long ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long ph_t = clock64();
+#endif
 
-    for (int panel = blockIdx.x; panel < npanels; panel += gridDim.x) {
+    int* next_panel = reinterpret_cast<int*>(L.wmax + 8);      // LDS word after the wmax slots
+    for (int panel = blockIdx.x;; panel += gridDim.x) {
         __syncthreads();          // previous panel fully written out before its state is reused
+        if (p.panel_counter) {
+            // panels are handed out one by one: with pruning their cost differs by orders of
+            // magnitude.  The counter only grows, so every workgroup reaches npanels and leaves.
+            if (tid == 0) *next_panel = (int)atomicAdd(p.panel_counter, 1u);
+            __syncthreads();
+            panel = *next_panel;
+        }
+        if (panel >= npanels) break;
         if (tid < BM) {
             const int qi = panel * BM + tid;
             int row = -1;
@@ -507,6 +628,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         __syncthreads();
         // a panel without a single query has nothing to do (every wavefront reads the same qid)
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
+        PHASE_MARK(0);
 
         if (prune) {
             // ---- bounding ball of the panel's query rows (L.Cs is free here: d <= 128 floats)
@@ -515,14 +637,29 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             int* col_lo = reinterpret_cast<int*>(L.Cs + 257);
             int* col_hi = reinterpret_cast<int*>(L.Cs + 258);
             if (tid == 0) { *rq_bits = 0u; *col_lo = 0x7fffffff; *col_hi = -0x7fffffff - 1; }
-            if (tid < d) {
-                float sum = 0.f;
-                int cnt = 0;
-                for (int r = 0; r < BM; ++r) {
-                    const int row = qid[r];
-                    if (row >= 0) { sum += Xq[(size_t)row * d + tid]; ++cnt; }
+            {
+                // partial column sums by groups of rows (fixed assignment and order: the centre is
+                // the same in every run), then one thread per column adds the partial sums
+                float* part = L.Cs + 512;           // [groups][d]
+                const int ncol4 = d >> 2;
+                const int groups = WG_THREADS / ncol4;
+                const int c4 = tid % ncol4, grp = tid / ncol4;
+                if (grp < groups) {
+                    v4f sum = {0.f, 0.f, 0.f, 0.f};
+                    for (int r = grp; r < BM; r += groups) {
+                        const int row = qid[r];
+                        if (row >= 0) sum += *reinterpret_cast<const v4f*>(Xq + (size_t)row * d + 4 * c4);
+                    }
+                    *reinterpret_cast<v4f*>(part + grp * d + 4 * c4) = sum;
                 }
-                qc[tid] = cnt > 0 ? sum / (float)cnt : 0.f;
+                __syncthreads();
+                if (tid < d) {
+                    int cnt = 0;
+                    for (int r = 0; r < BM; ++r) cnt += qid[r] >= 0 ? 1 : 0;
+                    float sum = 0.f;
+                    for (int gq = 0; gq < groups; ++gq) sum += part[gq * d + tid];
+                    qc[tid] = cnt > 0 ? sum / (float)cnt : 0.f;
+                }
             }
             __syncthreads();
             if (tid < BM && qid[tid] >= 0) {
@@ -564,6 +701,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
             __syncthreads();
         }
+        PHASE_MARK(1);
 
         const int my_q_local = wave * 32 + l32;
         const int my_qrow = qid[my_q_local];
@@ -648,7 +786,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             tile = tile_of(first);
             scan_from = first + 1;
         }
-        if (tile < ntiles) gload(tile, 0);
+ if (tile < ntiles) gload(tile, 0);
+        PHASE_MARK(2);
         int step = 0;                      // multiplied tiles of this panel (buffer parity)
         while (tile < ntiles) {
             const int col0 = tile * BN;
@@ -677,6 +816,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 if (chunk + 1 < DCH) {
                     gload(tile, chunk + 1);
                 } else {
+                    PHASE_MARK(3);
                     // thresholds published in the epilogue of the previous step (other parity)
                     const float* wm = L.wmax + (tpar ^ 1) * 4;
                     const float thr_max = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));
@@ -684,6 +824,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
                     if (tile_after < ntiles) gload(tile_after, 0);
+                    PHASE_MARK(4);
                 }
                 if (chunk == 0) {
 #pragma unroll
@@ -715,6 +856,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
 
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
+            PHASE_MARK(3);
             unsigned int flagged = 0;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -734,13 +876,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 }
                 if (__any(any)) flagged |= 1u << b;
             }
+            PHASE_MARK(5);
             if (__builtin_expect(flagged != 0, 0)) {
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
-                if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                bound = bounds[my_q_local];
+                const int colbuf_ = tpar;
+                SLHC_SELECT_TILE(KL, MASKED, true);
                 if (prune) {
                     // largest threshold of this wavefront's 32 queries: thr = 2 (h_q - bound)
                     float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
@@ -758,6 +898,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
                 }
             }
+            PHASE_MARK(6);
             if (prune && lane == 0) L.wmax[tpar * 4 + wave] = wave_thr_max;
             ++tiles_done;
             ++step;
@@ -780,7 +921,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 p.out_dist[o] = dist;
             }
         }
+        PHASE_MARK(7);
     }
+#ifdef SLHC_PHASE_TIMERS
+    if (p.phase_cycles && tid == 0)
+        for (int i = 0; i < 8; ++i) atomicAdd(p.phase_cycles + i, ph[i]);
+#endif
     if (p.survivors && lane == 0 && survivors) atomicAdd(p.survivors, survivors);
     if (p.tiles_done && tid == 0 && tiles_done) atomicAdd(p.tiles_done, tiles_done);
 }
@@ -857,7 +1003,7 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
         return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4>, grid, lds, p, stream);
     }
     // tile pruning and the slot map exist in the register-resident-query variant only
-    if (p.tile_c || p.qslot || p.tile_colour) return hipErrorInvalidValue;
+    if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter) return hipErrorInvalidValue;
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
     return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
 }

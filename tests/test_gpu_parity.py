@@ -422,9 +422,20 @@ def test_headline_full_size_properties(lib):
     assert (np.diff(gd.astype(np.float64), axis=1) >= 0).all()
     assert not (gi == np.arange(N)[:, None]).any()
 
+    print("headline: pruned knn", flush=True)
+    idx_p, dist_p = lib.knn_graph(Xd, k, prune=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx_p) and torch.equal(dist, dist_p)
+    del idx_p, dist_p
+
     print("headline: slhc", flush=True)
-    out = lib.slhc(Xd, k)
+    out = lib.slhc(Xd, k)                      # with tile pruning (the default)
     print("stats", out["stats"], flush=True)
+    brute = lib.slhc(Xd, k, prune=False)       # every tile multiplied: what bench.py's roofline step times
+    print("stats (every tile)", brute["stats"], flush=True)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(out[name_], brute[name_]), name_
+    del brute
     src, dst, w = (out[n].cpu().numpy() for n in ("mst_src", "mst_dst", "mst_w"))
     children, heights, sizes = (out[n].cpu().numpy() for n in ("children", "heights", "sizes"))
     assert (src < dst).all() and (np.diff(w.astype(np.float64)) >= 0).all()
