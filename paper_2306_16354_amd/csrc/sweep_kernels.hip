@@ -305,6 +305,70 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
     __builtin_amdgcn_wave_barrier();
 }
 
+// select_block: compaction and resolution of ONE 32x32 block in a single call (four pairs per
+// pass, 16 lanes each).  Used by the sweeps that multiply every tile: there a flagged block holds
+// one or two pairs, and the shorter call sequence is worth more than the batching above.
+// Returns the number of pairs compacted.
+template <int KL, bool MASKED, bool VEC4>
+__device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
+                                                               int col0, int colbuf,
+                                                               const float* __restrict__ Xq,
+                                                               const float* __restrict__ Xc,
+                                                               const int32_t* __restrict__ c_id,
+                                                               int N, int d, int k)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int* ccol = L.ccol + colbuf * BN;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int lhalf = lane >> 5;
+    unsigned short* myq = L.queues + wave * QCAP;
+    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
+    int qcount = 0;
+    const bool real_query = L.qid[wave * 32 + l32] >= 0;    // padding rows of the last panel
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+        const int cg = col0 + cl;
+        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
+        if (MASKED) pred = pred && (ccol[cl] != tag);
+        else pred = pred && (cg != tag);
+        const unsigned long long mask = __ballot(pred);
+        if (mask) {
+            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+            if (pred) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
+            qcount += __popcll(mask);
+        }
+    }
+    if (qcount == 0) return 0u;
+    __builtin_amdgcn_wave_barrier();
+    const int grp = lane >> 4, g16 = lane & 15;
+    for (int s = 0; s < qcount; s += 4) {
+        const int e = s + grp;
+        const bool valid = e < qcount;
+        const unsigned int ent = valid ? myq[e] : 0u;
+        const int ql = (int)(ent >> 8);
+        const int cg = col0 + (int)(ent & 255u);
+        const int qrow = L.qid[wave * 32 + ql];
+        const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
+        const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
+        const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
+        const int cid = (c_id && valid) ? c_id[cg] : cg;      // id that orders ties and is reported
+        const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
+        for (int g = 0; g < npass; ++g) {
+            const float dg = __shfl(dist, g * 16);
+            const int qlg = __shfl(ql, g * 16);
+            const int cgg = __shfl(cid, g * 16);
+            wave_list_insert(mylists + (size_t)qlg * KL, k, make_key(dg, cgg),
+                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    return (unsigned int)qcount;
+}
+
 // Tile epilogue after the hot filter flagged blocks `flagged` of this wavefront: all blocks go
 // through one queue, so the exact re-evaluation runs once per tile step.  Expands at its call site
 // with static block indices (a dynamic index into the accumulators would spill them).
@@ -567,7 +631,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 #define PHASE_MARK(i) do { } while (0)
 #endif
 
-template <int KL, bool MASKED, int DCH>
+template <int KL, bool MASKED, int DCH, bool PRUNE>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
 {
     const SweepLds<KL> L(sweep_smem);
@@ -585,13 +649,13 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     const float* __restrict__ hq = p.hq;
     const float* __restrict__ hc = p.hc;
     // cross 1-NN with a slot map: panel p holds the query rows among rows 128p .. 128p+127
-    const bool aligned = MASKED && p.qslot != nullptr;
+    const bool aligned = PRUNE && MASKED && p.qslot != nullptr;
     const int nq = (MASKED && !aligned) ? p.m : p.NQ;
     const int npanels = (nq + BM - 1) / BM;
     const int ntiles = (N + BN - 1) / BN;
     const int ld_row = tid >> 3;          // 0..31 (+32 i)
     const int ld_col = (tid & 7) * 4;     // 0..28
-    const bool prune = p.tile_c != nullptr;
+    constexpr bool prune = PRUNE;         // p.tile_c, p.tile_r and p.gap_ws are given
     float* __restrict__ gap = prune ? p.gap_ws + (size_t)blockIdx.x * ntiles : nullptr;
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
@@ -604,7 +668,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     int* next_panel = reinterpret_cast<int*>(L.wmax + 8);      // LDS word after the wmax slots
     for (int panel = blockIdx.x;; panel += gridDim.x) {
         __syncthreads();          // previous panel fully written out before its state is reused
-        if (p.panel_counter) {
+        if (PRUNE && p.panel_counter) {
             // panels are handed out one by one: with pruning their cost differs by orders of
             // magnitude.  The counter only grows, so every workgroup reaches npanels and leaves.
             if (tid == 0) *next_panel = (int)atomicAdd(p.panel_counter, 1u);
@@ -729,7 +793,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         // order the nearest rows sit in the neighbouring tiles, so the thresholds tighten early.
         // `scan` indices count from `base`; every lane of every wavefront evaluates next_scan on
         // the same data, so its result is workgroup-uniform.
-        const int own_tile = (!MASKED && p.own_tile_first && panel < ntiles) ? panel : -1;
+        const int own_tile = (PRUNE && !MASKED && p.own_tile_first && panel < ntiles) ? panel : -1;
         int base = 0;
         if (own_tile >= 0) base = own_tile + 1;
         else if (aligned) base = panel < ntiles ? panel : 0;
@@ -813,17 +877,23 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     if (MASKED) ccol[tid] = in_range ? colreg : -1;
                 }
                 __syncthreads();
+                // The loads of the next step are issued here, ahead of this step's multiplies, and
+                // must stay here: left to itself the scheduler sinks them towards their use at
+                // the end of the multiply block, which exposes their latency (measured: 6 % of
+                // the whole sweep).
                 if (chunk + 1 < DCH) {
                     gload(tile, chunk + 1);
+                    __builtin_amdgcn_sched_barrier(0);
                 } else {
                     PHASE_MARK(3);
                     // thresholds published in the epilogue of the previous step (other parity)
                     const float* wm = L.wmax + (tpar ^ 1) * 4;
-                    const float thr_max = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));
+                    const float thr_max = prune ? fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3])) : 0.f;
                     const int nxt = next_scan(scan_from, thr_max);
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
                     if (tile_after < ntiles) gload(tile_after, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                     PHASE_MARK(4);
                 }
                 if (chunk == 0) {
@@ -879,8 +949,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             PHASE_MARK(5);
             if (__builtin_expect(flagged != 0, 0)) {
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
-                const int colbuf_ = tpar;
-                SLHC_SELECT_TILE(KL, MASKED, true);
+                if (PRUNE) {
+                    const int colbuf_ = tpar;
+                    SLHC_SELECT_TILE(KL, MASKED, true);
+                } else {
+                    if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                    if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                    if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                    if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                    bound = bounds[my_q_local];
+                }
                 if (prune) {
                     // largest threshold of this wavefront's 32 queries: thr = 2 (h_q - bound)
                     float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
@@ -997,10 +1075,18 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     if (vec4 && p.d <= 4 * KC) {
         // up to 128 features: query fragments live in registers
         const int dch = (p.d + KC - 1) / KC;
-        if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1>, grid, lds, p, stream);
-        if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2>, grid, lds, p, stream);
-        if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3>, grid, lds, p, stream);
-        return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4>, grid, lds, p, stream);
+        if (p.tile_c) {
+            if (!p.tile_r || !p.gap_ws) return hipErrorInvalidValue;
+            if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, true>, grid, lds, p, stream);
+            if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, true>, grid, lds, p, stream);
+            if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, true>, grid, lds, p, stream);
+            return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, true>, grid, lds, p, stream);
+        }
+        if (p.qslot || p.tile_colour || p.panel_counter || p.own_tile_first) return hipErrorInvalidValue;
+        if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, false>, grid, lds, p, stream);
+        if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, false>, grid, lds, p, stream);
+        if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, false>, grid, lds, p, stream);
+        return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, false>, grid, lds, p, stream);
     }
     // tile pruning and the slot map exist in the register-resident-query variant only
     if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter) return hipErrorInvalidValue;
