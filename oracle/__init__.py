@@ -150,3 +150,41 @@ def slhc(X):
     out = dendrogram(src, dst, w, X.shape[0])
     out["total_weight"] = float(np.sum(np.sort(w)))
     return out
+
+
+def flat_clusters(children, n_clusters):
+    """Flat clustering of a dendrogram into n_clusters clusters (cuSLINK paper Sec. 3.3.2,
+    Alg. "extract_flattened_clusters" and Alg. "inherit_labels").
+
+    The dendrogram is cut after its first N - n_clusters merges.  The nodes that exist at that
+    level and have not been merged further are the cluster roots; they are numbered 0 .. n_clusters-1
+    in ascending order of their node id (a leaf keeps its row id, merge i has id N+i), which is the
+    paper's "sort the label roots", and every row gets the number of the root above it.
+
+    children: int [N-1, 2] in linkage layout.  Returns labels int32 [N].  Plain union of the kept
+    merges, written out; nothing here is shared with the GPU path."""
+    children = np.asarray(children, dtype=np.int64)
+    N = children.shape[0] + 1
+    if not (1 <= n_clusters <= N):
+        raise ValueError("need 1 <= n_clusters <= N")
+    kept = N - n_clusters
+    above = np.arange(2 * N - 1, dtype=np.int64)          # node directly above, or itself
+    for i in range(kept):
+        a, b = int(children[i, 0]), int(children[i, 1])
+        if not (0 <= a < N + i and 0 <= b < N + i and a != b):
+            raise ValueError("children do not form a dendrogram")
+        above[a] = N + i
+        above[b] = N + i
+    labels = np.empty(N, dtype=np.int32)
+    tops = np.empty(N, dtype=np.int64)
+    for v in range(N):
+        x = v
+        while above[x] != x:
+            x = int(above[x])
+        tops[v] = x
+    roots = np.unique(tops)
+    if roots.size != n_clusters:
+        raise ValueError("children do not form a dendrogram")
+    labels[:] = np.searchsorted(roots, tops)
+    return labels
+

@@ -6,6 +6,7 @@ import itertools
 import numpy as np
 import pytest
 import scipy.cluster.hierarchy as sch
+import scipy.sparse as sp
 import scipy.sparse.csgraph as csg
 from scipy.spatial.distance import cdist
 
@@ -308,3 +309,75 @@ def test_dendrogram_rejects_cycle():
 
 def test_oracle_reports_threads():
     assert oracle.num_threads() >= 1
+
+
+# ----------------------------------------------------------------------------- flat clusters
+def test_five_points_flat_clusters(golden_five_points):
+    g = golden_five_points
+    children = np.array(g["dendrogram"])[:, :2].astype(int)
+    assert oracle.flat_clusters(children, 2).tolist() == [int(v) for v in g["flat2"][0]]
+    assert oracle.flat_clusters(children, 3).tolist() == [int(v) for v in g["flat3"][0]]
+
+
+def _same_partition(a, b):
+    pairs = set(zip(a.tolist(), b.tolist()))
+    return len(pairs) == len(set(a.tolist())) == len(set(b.tolist()))
+
+
+@pytest.mark.parametrize("name,n", [("c1", 1500), ("c2", 900), ("c3", 700)])
+def test_flat_clusters_vs_scipy_fcluster(name, n):
+    X, _, _ = gen.make(name, n=n)
+    out = oracle.slhc(X)
+    Z = sch.linkage(X.astype(np.float64), method="single", metric="sqeuclidean")
+    for nc in (1, 2, 3, 7, 50, n // 2, n):
+        mine = oracle.flat_clusters(out["children"], nc)
+        ref = sch.fcluster(Z, nc, criterion="maxclust")
+        assert len(set(mine.tolist())) == nc
+        assert _same_partition(mine, ref), nc
+
+
+def test_flat_clusters_are_components_of_the_trimmed_tree():
+    # second definition: drop the n_clusters - 1 heaviest tree edges; the connected components of
+    # what is left are the clusters (tie-free data)
+    X, _, _ = gen.make("c1", n=800)
+    out = oracle.slhc(X)
+    N = X.shape[0]
+    for nc in (2, 5, 31):
+        keep = N - nc
+        graph = sp.coo_matrix((np.ones(keep), (out["src"][:keep], out["dst"][:keep])), shape=(N, N))
+        ncomp, comp = csg.connected_components(graph, directed=False)
+        assert ncomp == nc
+        assert _same_partition(oracle.flat_clusters(out["children"], nc), comp)
+
+
+def test_flat_clusters_numbering_and_extremes():
+    X, _, _ = gen.make("c2", n=300)
+    out = oracle.slhc(X)
+    N = X.shape[0]
+    ch = out["children"]
+    assert oracle.flat_clusters(ch, 1).tolist() == [0] * N
+    assert oracle.flat_clusters(ch, N).tolist() == list(range(N))          # every row its own root
+    # labels are the ranks of the root ids: rebuild the roots independently from the sizes array
+    nc = 9
+    lab = oracle.flat_clusters(ch, nc)
+    kept = N - nc
+    used = set(ch[:kept].ravel().tolist())
+    roots = sorted(set(range(N + kept)) - used)
+    assert len(roots) == nc
+    members = {r: set() for r in roots}
+    def leaves(node):
+        stack, acc = [node], []
+        while stack:
+            x = stack.pop()
+            if x < N:
+                acc.append(x)
+            else:
+                stack.extend(ch[x - N].tolist())
+        return acc
+    for rank, r in enumerate(roots):
+        assert {int(lab[v]) for v in leaves(r)} == {rank}
+    with pytest.raises(ValueError):
+        oracle.flat_clusters(ch, 0)
+    with pytest.raises(ValueError):
+        oracle.flat_clusters(ch, N + 1)
+
