@@ -162,6 +162,24 @@ int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k,
                   slhc_stats* stats, void* workspace, size_t workspace_bytes, void* stream,
                   uint32_t flags);
 
+/*
+ * Flat clusters (paper Sec. 3.3.2, Alg. "extract_flattened_clusters" and Alg. "inherit_labels").
+ *
+ * Cuts the dendrogram after its first N - n_clusters merges.  The nodes that exist at that level
+ * and are not merged further are the cluster roots; they are numbered 0 .. n_clusters-1 in
+ * ascending order of node id (a row keeps its id, merge i is node N+i), and labels[v] is the number
+ * of the root above row v.  With n_clusters = N every row is its own cluster (labels[v] = v).
+ *
+ *   children  DEVICE in   [(N-1)*2] int32, as written by slhc_slhc
+ *   labels    DEVICE out  [N] int32
+ * `children` must be a dendrogram in that layout (merge i joins two nodes with ids below N+i);
+ * entries that are not are ignored, and the labels of the rows they would have joined are then
+ * unspecified (never an out-of-range access).  Asynchronous on `stream`.
+ */
+int slhc_flat_clusters_workspace_bytes(int64_t N, size_t* bytes /* HOST out */);
+int slhc_flat_clusters(const int32_t* children, int64_t N, int64_t n_clusters, int32_t* labels,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

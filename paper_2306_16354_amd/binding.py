@@ -59,6 +59,10 @@ def load_library():
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
     lib.slhc_slhc.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats), vp, sz, vp]
     lib.slhc_slhc_opt.argtypes = lib.slhc_slhc.argtypes + [ctypes.c_uint32]
+    lib.slhc_flat_clusters_workspace_bytes.argtypes = [i64, ctypes.POINTER(sz)]
+    lib.slhc_flat_clusters.argtypes = [vp, i64, i64, vp, vp, sz, vp]
+    lib.slhc_flat_clusters_workspace_bytes.restype = ctypes.c_int
+    lib.slhc_flat_clusters.restype = ctypes.c_int
     for name in ("slhc_knn_workspace_bytes", "slhc_knn_graph", "slhc_knn_graph_opt",
                  "slhc_cross_1nn_workspace_bytes", "slhc_cross_1nn", "slhc_workspace_bytes", "slhc_slhc",
                  "slhc_slhc_opt"):
@@ -173,3 +177,26 @@ def slhc(X, k, workspace=None, out=None, prune=True):
                              workspace.numel(), _stream(), SLHC_PRUNE if prune else 0))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
+
+
+def flat_clusters_workspace_bytes(N):
+    out = ctypes.c_size_t(0)
+    _check(load_library().slhc_flat_clusters_workspace_bytes(N, ctypes.byref(out)))
+    return out.value
+
+
+def flat_clusters(children, n_clusters, workspace=None, out=None):
+    """slhc_flat_clusters: labels int32 [N] of the cut into n_clusters clusters.  `children` is the
+    int32 CUDA tensor [N-1, 2] slhc() returns.  Asynchronous on the current stream."""
+    if not (children.is_cuda and children.dtype == torch.int32 and children.dim() == 2
+            and children.shape[1] == 2 and children.is_contiguous()):
+        raise TypeError("children must be a contiguous int32 CUDA tensor [N-1, 2]")
+    N = children.shape[0] + 1
+    if workspace is None:
+        workspace = _workspace(flat_clusters_workspace_bytes(N), children.device)
+    if out is None:
+        out = torch.empty(N, dtype=torch.int32, device=children.device)
+    _check(load_library().slhc_flat_clusters(children.data_ptr(), N, int(n_clusters), out.data_ptr(),
+                                             workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslhc.so")
-SOURCES = ["sweep_kernels.hip", "forest_kernels.hip", "order_kernels.hip", "slhc_api.hip"]
+SOURCES = ["sweep_kernels.hip", "forest_kernels.hip", "order_kernels.hip", "cluster_kernels.hip", "slhc_api.hip"]
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     # packed fp32 VALU forms stay off for every device function of the library

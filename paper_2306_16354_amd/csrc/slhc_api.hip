@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/slhc.h"
+#include "cluster_kernels.h"
 #include "forest_kernels.h"
 #include "order_kernels.h"
 #include "sweep_kernels.h"
@@ -567,6 +568,44 @@ int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour, 
     p.qcolour = p.ccolour = colour; p.rows = rows; p.m = (int)m;
     p.survivors = counters;
     HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
+    return SLHC_OK;
+}
+
+static int flat_clusters_layout(void* ws, int64_t N, int32_t** above, int32_t** flag, int32_t** rank, void** temp,
+                                size_t* temp_bytes, size_t* total)
+{
+    Carver c(ws);
+    const size_t nodes = 2 * (size_t)N;
+    *above = c.take<int32_t>(nodes);
+    *flag = c.take<int32_t>(nodes);
+    *rank = c.take<int32_t>(nodes);
+    *temp_bytes = slhc::flat_clusters_scan_temp_bytes((int)N);
+    *temp = c.take<unsigned char>(*temp_bytes);
+    *total = c.off;
+    return SLHC_OK;
+}
+
+int slhc_flat_clusters_workspace_bytes(int64_t N, size_t* bytes)
+{
+    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+    if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
+    if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+    int32_t *a, *f, *r; void* t; size_t tb;
+    return flat_clusters_layout(nullptr, N, &a, &f, &r, &t, &tb, bytes);
+}
+
+int slhc_flat_clusters(const int32_t* children, int64_t N, int64_t n_clusters, int32_t* labels,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!children || !labels || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+    if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
+    if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+    if (n_clusters < 1 || n_clusters > N) { set_err("need 1 <= n_clusters <= N (n_clusters=%lld)", (long long)n_clusters); return SLHC_INVALID_ARG; }
+    int32_t *above, *flag, *rank; void* temp; size_t temp_bytes, total;
+    flat_clusters_layout(workspace, N, &above, &flag, &rank, &temp, &temp_bytes, &total);
+    if (workspace_bytes < total) { set_err("workspace %zu < %zu bytes", workspace_bytes, total); return SLHC_WORKSPACE_TOO_SMALL; }
+    HIP_TRY(slhc::flat_clusters(children, (int)N, (int)n_clusters, labels, above, flag, rank, temp, temp_bytes,
+                                static_cast<hipStream_t>(stream)));
     return SLHC_OK;
 }
 

@@ -398,6 +398,49 @@ def test_pruned_slhc_is_identical(lib, name, n):
           b["stats"]["order_padded_rows"], "order ms", round(b["stats"]["ms_order"], 2), flush=True)
 
 
+# ----------------------------------------------------------------------------- flat clusters
+# Integer work: labels must equal the oracle's exactly when both cut the same dendrogram.
+@pytest.mark.parametrize("name,n", [("c1", None), ("c2", 20000), ("c5", 30000)])
+def test_flat_clusters_match_oracle(lib, name, n):
+    X, _, k = gen.make(name, n=n)
+    N = X.shape[0]
+    out = lib.slhc(torch.from_numpy(X).cuda(), k)
+    children = out["children"].cpu().numpy()
+    for nc in (1, 2, 3, 10, 777, N // 3, N - 1, N):
+        print(f"flat clusters {name} N={N} n_clusters={nc}", flush=True)
+        got = lib.flat_clusters(out["children"], nc)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.flat_clusters(children, nc)), nc
+
+
+def test_flat_clusters_deep_chain_and_tiny(lib):
+    # increasing gaps on a line: the dendrogram is one chain of depth N-1 (worst case for walking up)
+    X, _ = gen.increasing_gaps_line(5000, 3, seed=1)
+    out = lib.slhc(torch.from_numpy(X).cuda(), 4)
+    children = out["children"].cpu().numpy()
+    for nc in (1, 2, 50, 4999, 5000):
+        got = lib.flat_clusters(out["children"], nc).cpu().numpy()
+        assert np.array_equal(got, oracle.flat_clusters(children, nc)), nc
+    ch = torch.tensor([[0, 1]], dtype=torch.int32, device="cuda")          # N = 2
+    assert lib.flat_clusters(ch, 1).tolist() == [0, 0]
+    assert lib.flat_clusters(ch, 2).tolist() == [0, 1]
+    with pytest.raises(lib.SlhcError) as e:
+        lib.flat_clusters(ch, 3)
+    assert e.value.status == 1
+    with pytest.raises(lib.SlhcError) as e:
+        lib.flat_clusters(ch, 0)
+    assert e.value.status == 1
+
+
+def test_flat_clusters_recover_the_blobs(lib):
+    # well separated blobs: cutting at the number of blobs gives back the generator's labels
+    X, labels, k = gen.make("c1")
+    out = lib.slhc(torch.from_numpy(X).cuda(), k)
+    got = lib.flat_clusters(out["children"], int(labels.max()) + 1).cpu().numpy()
+    pairs = set(zip(got.tolist(), labels.tolist()))
+    assert len(pairs) == int(labels.max()) + 1
+
+
 # ----------------------------------------------------------------------------- full size (headline)
 def test_headline_full_size_properties(lib):
     """c3 at its full size (1M x 128, k=32), in the launch configuration bench.py times.  The
