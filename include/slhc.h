@@ -126,6 +126,25 @@ int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Fused 1-NN between two matrices (paper Sec. 3.1.2, Alg. "Fused 1-NN"; the m x n shapes of the
+ * paper's 1-NN benchmark, few queries against a large index).
+ *
+ * For each query row q < m: the index row j < n that minimises (||Q_q - Y_j||^2, j), and that
+ * distance.  Same filter-then-re-evaluate arithmetic as slhc_knn_graph; nothing is excluded (a
+ * query that also is an index row finds itself at distance 0).  With few query rows the index rows
+ * are split over the workgroups and the partial minima are merged by a 64-bit atomic minimum over
+ * (distance bits, index), so the result does not depend on the split.
+ *
+ *   Q        DEVICE in  [m*d]        Y         DEVICE in  [n*d]
+ *   out_idx  DEVICE out [m] int32    out_dist  DEVICE out [m] float32
+ * Asynchronous on `stream`.
+ */
+int slhc_fused_1nn_workspace_bytes(int64_t m, int64_t n, int32_t d, size_t* bytes /* HOST out */);
+int slhc_fused_1nn(const float* Q, int64_t m, const float* Y, int64_t n, int32_t d,
+                   int32_t* out_idx, float* out_dist,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Single-linkage clustering (paper Alg. "cuSLINK Algorithm" without the final flat cut:
  * k-NN graph, Sec. 3.1.1; MST by Boruvka with colours, Sec. 3.2, Alg. "MST Algorithm";
  * connection of the forest, Sec. 3.1.2, Alg. "connect_graph"; sorted edges and dendrogram,

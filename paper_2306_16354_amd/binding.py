@@ -59,6 +59,10 @@ def load_library():
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
     lib.slhc_slhc.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp, vp, ctypes.POINTER(_Stats), vp, sz, vp]
     lib.slhc_slhc_opt.argtypes = lib.slhc_slhc.argtypes + [ctypes.c_uint32]
+    lib.slhc_fused_1nn_workspace_bytes.argtypes = [i64, i64, i32, ctypes.POINTER(sz)]
+    lib.slhc_fused_1nn.argtypes = [vp, i64, vp, i64, i32, vp, vp, vp, sz, vp]
+    lib.slhc_fused_1nn_workspace_bytes.restype = ctypes.c_int
+    lib.slhc_fused_1nn.restype = ctypes.c_int
     lib.slhc_flat_clusters_workspace_bytes.argtypes = [i64, ctypes.POINTER(sz)]
     lib.slhc_flat_clusters.argtypes = [vp, i64, i64, vp, vp, sz, vp]
     lib.slhc_flat_clusters_workspace_bytes.restype = ctypes.c_int
@@ -198,5 +202,25 @@ def flat_clusters(children, n_clusters, workspace=None, out=None):
         out = torch.empty(N, dtype=torch.int32, device=children.device)
     _check(load_library().slhc_flat_clusters(children.data_ptr(), N, int(n_clusters), out.data_ptr(),
                                              workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+def fused_1nn(Q, Y, workspace=None, out=None):
+    """slhc_fused_1nn: for every row of Q the nearest row of Y: (idx int32 [m], dist float32 [m])."""
+    Q = _device_matrix(Q)
+    Y = _device_matrix(Y)
+    m, d = Q.shape
+    n, d2 = Y.shape
+    if d != d2:
+        raise ValueError("Q and Y must have the same number of columns")
+    lib = load_library()
+    if workspace is None:
+        sz = ctypes.c_size_t(0)
+        _check(lib.slhc_fused_1nn_workspace_bytes(m, n, d, ctypes.byref(sz)))
+        workspace = _workspace(sz.value, Q.device)
+    if out is None:
+        out = (torch.empty(m, dtype=torch.int32, device=Q.device), torch.empty(m, dtype=torch.float32, device=Q.device))
+    _check(lib.slhc_fused_1nn(Q.data_ptr(), m, Y.data_ptr(), n, d, out[0].data_ptr(), out[1].data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), _stream()))
     return out
 

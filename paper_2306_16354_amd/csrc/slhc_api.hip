@@ -571,6 +571,46 @@ int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour, 
     return SLHC_OK;
 }
 
+static size_t fused_1nn_layout(void* ws, int64_t m, int64_t n, float** hq, float** hy, unsigned long long** keys)
+{
+    Carver c(ws);
+    *hq = c.take<float>((size_t)m);
+    *hy = c.take<float>((size_t)n);
+    *keys = c.take<unsigned long long>((size_t)m);
+    return c.off;
+}
+
+int slhc_fused_1nn_workspace_bytes(int64_t m, int64_t n, int32_t d, size_t* bytes)
+{
+    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+    if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
+    if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+    float *hq, *hy; unsigned long long* keys;
+    *bytes = fused_1nn_layout(nullptr, m, n, &hq, &hy, &keys);
+    return SLHC_OK;
+}
+
+int slhc_fused_1nn(const float* Q, int64_t m, const float* Y, int64_t n, int32_t d, int32_t* out_idx,
+                   float* out_dist, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!Q || !Y || !out_idx || !out_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+    if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
+    if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+    float *hq, *hy; unsigned long long* keys;
+    const size_t need = fused_1nn_layout(workspace, m, n, &hq, &hy, &keys);
+    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(slhc::launch_half_norms(Q, (int)m, d, hq, s));
+    HIP_TRY(slhc::launch_half_norms(Y, (int)n, d, hy, s));
+    slhc::SweepParams p{};
+    p.Xq = Q; p.hq = hq; p.NQ = (int)m;
+    p.Xc = Y; p.hc = hy; p.NC = (int)n;
+    p.d = d; p.k = 1;
+    p.out_idx = out_idx; p.out_dist = out_dist;
+    HIP_TRY(slhc::launch_segmented_1nn(p, keys, s));
+    return SLHC_OK;
+}
+
 static int flat_clusters_layout(void* ws, int64_t N, int32_t** above, int32_t** flag, int32_t** rank, void** temp,
                                 size_t* temp_bytes, size_t* total)
 {

@@ -38,6 +38,12 @@ struct SweepParams {
     unsigned int* panel_counter;  // optional device word, zero at launch: panels are taken from it one at
                                   // a time instead of round-robin (use when panel costs differ widely)
     int own_tile_first;    // self-join in the same row order: start each panel at its own tile
+    // k = 1 between two matrices with few query rows: the candidate tiles are split into `segments`
+    // parts, one work item per (panel, part); every item merges its result into out_key[q] with a
+    // 64-bit atomic minimum over (dist bits << 32 | idx), which is the (dist, idx) order.  Set by
+    // launch_segmented_1nn; 0 / nullptr otherwise.
+    int segments;
+    unsigned long long* out_key;
     unsigned long long* survivors;   // optional device counter: pairs that passed the filter
     unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
 #ifdef SLHC_PHASE_TIMERS
@@ -50,5 +56,9 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
 int sweep_grid_limit();   // upper bound of gridDim.x of a sweep launch (for sizing gap_ws); 0 on error
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream);
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);
+// Nearest candidate row of every query row (k-NN mode parameters with k = 1, no self exclusion
+// unless asked).  Splits the candidates over the chip when there are few query rows; `keys` is
+// scratch of NQ 64-bit words.
+hipError_t launch_segmented_1nn(const SweepParams& p, unsigned long long* keys, hipStream_t stream);
 
 }  // namespace slhc

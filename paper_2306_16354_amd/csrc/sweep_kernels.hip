@@ -421,7 +421,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
 
-    for (int panel = blockIdx.x; panel < npanels; panel += gridDim.x) {
+    // Work item = (query panel, segment of the candidate tiles).  With one segment a workgroup
+    // sweeps all candidates for its panel; with few query rows the candidates are split so that
+    // the whole chip works, and the partial results meet in p.out_key (see SweepParams).
+    const int nseg = p.segments > 1 ? p.segments : 1;
+    const int nitems = npanels * nseg;
+    for (int item = blockIdx.x; item < nitems; item += gridDim.x) {
+        const int panel = item % npanels;
+        const int seg = item / npanels;
+        const int t_begin = (int)((long long)seg * ntiles / nseg);
+        const int t_end = (int)((long long)(seg + 1) * ntiles / nseg);
         __syncthreads();          // previous panel fully written out before its state is reused
         if (tid < BM) {
             const int qi = panel * BM + tid;
@@ -493,8 +502,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         };
 
         v16f acc[4];
-        gload(0, 0);
-        for (int tile = 0; tile < ntiles; ++tile) {
+        if (t_begin < t_end) gload(t_begin, 0);
+        for (int tile = t_begin; tile < t_end; ++tile) {
             const int col0 = tile * BN;
             for (int chunk = 0; chunk < nchunks; ++chunk) {
                 __syncthreads();                       // everyone is done reading the staged step
@@ -522,7 +531,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 {
                     int nt = tile, nc = chunk + 1;
                     if (nc == nchunks) { nc = 0; nt = tile + 1; }
-                    if (nt < ntiles) gload(nt, nc);
+                    if (nt < t_end) gload(nt, nc);
                 }
                 if (chunk == 0) {
 #pragma unroll
@@ -592,8 +601,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 if (key == LIST_SENTINEL) idx = -1;
                 const size_t o = MASKED ? (size_t)(panel * BM + wave * 32 + ql)
                                         : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + lane;
-                p.out_idx[o] = idx;
-                p.out_dist[o] = dist;
+                if (p.out_key) {
+                    if (key != LIST_SENTINEL) atomicMin(p.out_key + o, key);
+                } else {
+                    p.out_idx[o] = idx;
+                    p.out_dist[o] = dist;
+                }
             }
         }
     }
@@ -1069,10 +1082,12 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     if (npanels < 1) return hipSuccess;
     const size_t lds = sweep_lds_bytes(KL);
     const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+    if (p.segments > 1 && (!p.out_key || p.k != 1 || p.tile_c)) return hipErrorInvalidValue;
+    const long long nitems = (long long)npanels * (p.segments > 1 ? p.segments : 1);
     int grid = cus * per_cu;
-    if (grid > npanels) grid = npanels;
+    if (grid > nitems) grid = (int)nitems;
     const bool vec4 = (p.d % 4 == 0) && (((reinterpret_cast<uintptr_t>(p.Xq) | reinterpret_cast<uintptr_t>(p.Xc)) & 15) == 0);
-    if (vec4 && p.d <= 4 * KC) {
+    if (vec4 && p.d <= 4 * KC && p.segments <= 1) {
         // up to 128 features: query fragments live in registers
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
@@ -1092,6 +1107,57 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter) return hipErrorInvalidValue;
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
     return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
+}
+
+// (dist bits << 32 | idx) keys of a segmented 1-NN sweep -> idx, dist; an untouched key: -1, +inf
+__global__ void __launch_bounds__(256) unpack_keys_kernel(const unsigned long long* __restrict__ keys, int m,
+                                                          int32_t* __restrict__ out_idx, float* __restrict__ out_dist)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= m) return;
+    const unsigned long long key = keys[i];
+    out_idx[i] = key == LIST_SENTINEL ? -1 : (int)(unsigned int)(key & 0xffffffffull);
+    out_dist[i] = __uint_as_float((unsigned int)(key >> 32));
+}
+
+__global__ void __launch_bounds__(256) fill_keys_kernel(unsigned long long* __restrict__ keys, int m)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < m) keys[i] = LIST_SENTINEL;
+}
+
+int sweep_segments_for(int m, int NC)
+{
+    int cus = 0;
+    if (device_cus(&cus) != hipSuccess) return 1;
+    const int npanels = (m + BM - 1) / BM;
+    const int ntiles = (NC + BN - 1) / BN;
+    if (npanels < 1 || ntiles < 1) return 1;
+    int seg = (2 * cus) / npanels;          // enough work items for two workgroups per CU
+    if (seg > ntiles) seg = ntiles;
+    return seg < 1 ? 1 : seg;
+}
+
+hipError_t launch_segmented_1nn(const SweepParams& p_in, unsigned long long* keys, hipStream_t stream)
+{
+    SweepParams p = p_in;
+    const int m = p.NQ;
+    if (m < 1) return hipSuccess;
+    p.k = 1;
+    p.segments = sweep_segments_for(m, p.NC);
+    if (p.segments <= 1) {
+        p.segments = 0;
+        p.out_key = nullptr;
+        return launch_knn_sweep(p, stream);
+    }
+    p.out_key = keys;
+    hipLaunchKernelGGL(fill_keys_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, keys, m);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_knn_sweep(p, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(unpack_keys_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, keys, m, p.out_idx, p.out_dist);
+    return hipGetLastError();
 }
 
 int sweep_grid_limit()

@@ -398,6 +398,52 @@ def test_pruned_slhc_is_identical(lib, name, n):
           b["stats"]["order_padded_rows"], "order ms", round(b["stats"]["ms_order"], 2), flush=True)
 
 
+# ----------------------------------------------------------------------------- 1-NN between two matrices
+# The oracle has no two-matrix search of its own; its cross-colour 1-NN on the stacked matrix
+# [Q; Y] with colour 0 for the query rows and 1 for the index rows is the same definition.
+def check_fused_1nn(lib, Q, Y, min_exact):
+    m, n = Q.shape[0], Y.shape[0]
+    gi, gd = lib.fused_1nn(torch.from_numpy(Q).cuda(), torch.from_numpy(Y).cuda())
+    torch.cuda.synchronize()
+    gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+    XY = np.concatenate([Q, Y])
+    colour = np.concatenate([np.zeros(m, np.int32), np.ones(n, np.int32)])
+    oi, od = oracle.cross_1nn(XY, colour, np.arange(m, dtype=np.int32))
+    oi = oi - m
+    assert gi.min() >= 0 and gi.max() < n
+    assert close(gd, od, RTOL_DIST).all()
+    true_d = pair_dist64(XY, np.arange(m), gi + m)
+    assert close(gd, true_d, RTOL_DIST).all()
+    assert (gi == oi).mean() >= min_exact
+
+
+@pytest.mark.parametrize("m,n,d", [(100, 20000, 64), (1000, 20000, 128), (3000, 10000, 256), (1, 700, 8),
+                                   (130, 129, 20), (257, 5, 33)])
+def test_fused_1nn_few_queries(lib, m, n, d):
+    # shapes of the paper's 1-NN benchmark, scaled: few queries against a large index (the index
+    # rows are split over workgroups and merged), plus ragged and tiny cases
+    print(f"fused 1-NN m={m} n={n} d={d}", flush=True)
+    rng = np.random.default_rng(m * 7 + d)
+    Y = rng.standard_normal((n, d)).astype(np.float32)
+    Q = rng.standard_normal((m, d)).astype(np.float32)
+    check_fused_1nn(lib, Q, Y, 0.999)
+
+
+def test_fused_1nn_finds_itself_and_ties(lib):
+    Y = gen.integer_lattice(7, 3, seed=2)                  # exact ties: smallest index must win
+    Q = Y[::5].copy()
+    gi, gd = lib.fused_1nn(torch.from_numpy(Q).cuda(), torch.from_numpy(Y).cuda())
+    assert (gd.cpu().numpy() == 0.0).all()
+    assert np.array_equal(gi.cpu().numpy(), np.arange(Y.shape[0])[::5])
+    Q2 = (Q + np.float32(0.5)).astype(np.float32)          # equidistant from 8 lattice points
+    XY = np.concatenate([Q2, Y])
+    colour = np.concatenate([np.zeros(Q2.shape[0], np.int32), np.ones(Y.shape[0], np.int32)])
+    oi, od = oracle.cross_1nn(XY, colour, np.arange(Q2.shape[0], dtype=np.int32))
+    gi, gd = lib.fused_1nn(torch.from_numpy(Q2).cuda(), torch.from_numpy(Y).cuda())
+    assert np.array_equal(gi.cpu().numpy(), oi - Q2.shape[0])
+    assert np.array_equal(gd.cpu().numpy().astype(np.float64), od)
+
+
 # ----------------------------------------------------------------------------- flat clusters
 # Integer work: labels must equal the oracle's exactly when both cut the same dendrogram.
 @pytest.mark.parametrize("name,n", [("c1", None), ("c2", 20000), ("c5", 30000)])
