@@ -182,6 +182,20 @@ def main():
                                         "achieved": ct, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                                         "frac": ct / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
 
+    if not args.knn_only:
+        # graph / Boruvka stage against the HBM roofline: per round every list entry (4 B index) and the
+        # colour it points to (4 B gather) may be read once, one distance per vertex, and ~40 B of
+        # per-vertex state are rewritten; ms_boruvka is host time including the per-round readbacks
+        rounds = float(stats[-1]["boruvka_rounds"])
+        forest_bytes = rounds * N * (8.0 * k + 44.0)
+        fms = mean("ms_boruvka")
+        if fms > 0:
+            gbs = forest_bytes / (fms * 1e-3) / 1e9
+            line["roofline_forest"] = {"kernel": "Boruvka rounds (scan lists, classify, select, commit, relabel)",
+                                       "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                                       "algorithmic_bytes": forest_bytes, "ms": fms, "rounds": int(rounds)}
+
     if not args.knn_only and not args.no_pruned_leg:
         # the default entry point (tile pruning on) on the same input, outside the timed region
         for _ in range(max(1, args.warmup)):
