@@ -44,8 +44,9 @@ def _load():
         lib.oracle_cross_1nn.argtypes = [p, i64, i32, p, p, i64, p, p]
         lib.oracle_mst_prim.argtypes = [p, i64, i32, p, p, p]
         lib.oracle_dendrogram.argtypes = [p, p, p, i64, p, p, p, p, p, p]
+        lib.oracle_csr_msf.argtypes = [p, p, p, i64, p, p, p, p, p]
         for f in (lib.oracle_knn_rows, lib.oracle_cross_1nn, lib.oracle_mst_prim,
-                  lib.oracle_dendrogram):
+                  lib.oracle_dendrogram, lib.oracle_csr_msf):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -187,4 +188,26 @@ def flat_clusters(children, n_clusters):
         raise ValueError("children do not form a dendrogram")
     labels[:] = np.searchsorted(roots, tops)
     return labels
+
+
+def csr_msf(offsets, indices, weights):
+    """Minimum spanning forest of an undirected CSR graph (paper Sec. 3.2), Kruskal under the strict
+    edge order (w, lo, hi).  Returns (lo, hi, w) of the forest edges ascending in that order, and
+    comp int32 [V] = smallest vertex id of each vertex's connected component."""
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    V = offsets.shape[0] - 1
+    if V < 1 or indices.shape != weights.shape or offsets[-1] != indices.shape[0]:
+        raise ValueError("bad CSR arrays")
+    lo = np.empty(max(V - 1, 1), dtype=np.int32)
+    hi = np.empty(max(V - 1, 1), dtype=np.int32)
+    w = np.empty(max(V - 1, 1), dtype=np.float32)
+    comp = np.empty(V, dtype=np.int32)
+    n = ctypes.c_int64(0)
+    rc = _load().oracle_csr_msf(_ptr(offsets), _ptr(indices), _ptr(weights), V, _ptr(lo), _ptr(hi),
+                                _ptr(w), ctypes.byref(n), _ptr(comp))
+    if rc != 0:
+        raise ValueError(f"oracle_csr_msf failed (rc={rc})")
+    return lo[:n.value].copy(), hi[:n.value].copy(), w[:n.value].copy(), comp
 

@@ -20,6 +20,11 @@
  *                       Prim (Sec. 1: the result is an exact solution of single-linkage
  *                       clustering; Sec. 2 notes SLINK is Prim's iteration).  This is the plain
  *                       definition of what the paper's Boruvka + connection loop must reach.
+ *   oracle_csr_msf      minimum spanning forest of an undirected weighted graph given in CSR form, by
+ *                       Kruskal over its edges in the strict order (weight, min endpoint, max
+ *                       endpoint) (Sec. 3.2 "Spanning Trees": the MST primitive takes a CSR graph and
+ *                       returns a forest when the graph is not connected).  Under a strict total
+ *                       order the forest is unique, so it can be compared edge by edge.
  *   oracle_dendrogram   edges sorted by weight, then a union-find pass that gives merge i the
  *                       node id N+i, in the scipy linkage layout (Sec. 3.3.1 "Relabel into
  *                       Dendrogram"; Sec. 2 last paragraph adopts scipy.hierarchy.linkage).
@@ -235,3 +240,63 @@ int oracle_dendrogram(const int32_t* src, const int32_t* dst, const double* w, i
     free(e); free(up); free(rnk); free(node); free(cnt);
     return rc;
 }
+
+/*
+ * Kruskal on the CSR graph (offsets[V+1], indices[E], weights[E]; every undirected edge may be stored
+ * in one or both rows).  Self loops are ignored.  Emits the forest edges ascending by
+ * (w, lo, hi) into out_lo/out_hi/out_w (capacity V-1), their number into *n_out, and comp[v] = the
+ * smallest vertex id of v's connected component.  Returns 0, or -1 on bad arguments.
+ */
+typedef struct { float w; int32_t lo, hi; } csr_edge;
+
+static int csr_edge_cmp(const void* pa, const void* pb)
+{
+    const csr_edge* a = (const csr_edge*)pa;
+    const csr_edge* b = (const csr_edge*)pb;
+    if (a->w != b->w) return a->w < b->w ? -1 : 1;
+    if (a->lo != b->lo) return a->lo < b->lo ? -1 : 1;
+    if (a->hi != b->hi) return a->hi < b->hi ? -1 : 1;
+    return 0;
+}
+
+int oracle_csr_msf(const int32_t* offsets, const int32_t* indices, const float* weights, int64_t V,
+                   int32_t* out_lo, int32_t* out_hi, float* out_w, int64_t* n_out, int32_t* comp)
+{
+    if (!offsets || !n_out || !comp || V < 1) return -1;
+    const int64_t E = offsets[V];
+    if (E < 0 || offsets[0] != 0) return -1;
+    csr_edge* edges = (csr_edge*)malloc(sizeof(csr_edge) * (size_t)(E > 0 ? E : 1));
+    int32_t* up = (int32_t*)malloc(sizeof(int32_t) * (size_t)V);
+    if (!edges || !up) { free(edges); free(up); return -1; }
+    int64_t m = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (offsets[v + 1] < offsets[v]) { free(edges); free(up); return -1; }
+        for (int64_t e = offsets[v]; e < offsets[v + 1]; ++e) {
+            const int32_t u = indices[e];
+            if (u < 0 || u >= V) { free(edges); free(up); return -1; }
+            if (u == v) continue;
+            edges[m].w = weights[e];
+            edges[m].lo = (int32_t)(v < u ? v : u);
+            edges[m].hi = (int32_t)(v < u ? u : v);
+            ++m;
+        }
+    }
+    qsort(edges, (size_t)m, sizeof(csr_edge), csr_edge_cmp);
+    for (int64_t v = 0; v < V; ++v) up[v] = (int32_t)v;
+    int64_t n = 0;
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t a = uf_find(up, edges[i].lo), b = uf_find(up, edges[i].hi);
+        if (a == b) continue;
+        up[a > b ? a : b] = a > b ? b : a;          /* the smaller id stays the representative */
+        out_lo[n] = edges[i].lo;
+        out_hi[n] = edges[i].hi;
+        out_w[n] = edges[i].w;
+        ++n;
+    }
+    for (int64_t v = 0; v < V; ++v) comp[v] = uf_find(up, (int32_t)v);
+    *n_out = n;
+    free(edges);
+    free(up);
+    return 0;
+}
+

@@ -188,3 +188,35 @@ def increasing_gaps_line(N, d, seed=None):
         perm = _rng(seed).permutation(N)
         X, pos = X[perm], pos[perm]
     return np.ascontiguousarray(X), pos
+
+
+def road_graph(side, seed, keep=0.625, integer_weights=False):
+    """Planar road-like graph: the vertices of a side x side grid, each of the 4-neighbour links kept
+    with probability `keep` (average degree 4 * keep = 2.5, as in road networks; the graph is usually
+    not connected), vertex ids shuffled.  Weights are uniform in [1, 100) (float32), or integers
+    1..10 when integer_weights is set (many ties).  Returns symmetric CSR arrays
+    (offsets int32 [V+1], indices int32 [E], weights float32 [E]); every undirected edge is stored
+    in both rows with the same weight."""
+    rng = _rng(seed)
+    V = side * side
+    ids = np.arange(V, dtype=np.int64).reshape(side, side)
+    a = np.concatenate([ids[:, :-1].ravel(), ids[:-1, :].ravel()])
+    b = np.concatenate([ids[:, 1:].ravel(), ids[1:, :].ravel()])
+    kept = rng.random(a.shape[0]) < keep
+    a, b = a[kept], b[kept]
+    if integer_weights:
+        w = rng.integers(1, 11, size=a.shape[0]).astype(np.float32)
+    else:
+        w = (1.0 + 99.0 * rng.random(a.shape[0])).astype(np.float32)
+    relabel = rng.permutation(V)
+    a, b = relabel[a], relabel[b]
+    src = np.concatenate([a, b])
+    dst = np.concatenate([b, a])
+    ww = np.concatenate([w, w])
+    order = np.lexsort((dst, src))
+    src, dst, ww = src[order], dst[order], ww[order]
+    offsets = np.zeros(V + 1, dtype=np.int64)
+    np.add.at(offsets, src + 1, 1)
+    offsets = np.cumsum(offsets)
+    return offsets.astype(np.int32), dst.astype(np.int32), np.ascontiguousarray(ww, dtype=np.float32)
+

@@ -381,3 +381,83 @@ def test_flat_clusters_numbering_and_extremes():
     with pytest.raises(ValueError):
         oracle.flat_clusters(ch, N + 1)
 
+
+# ----------------------------------------------------------------------------- CSR spanning forest
+def _dense_to_csr(D):
+    V = D.shape[0]
+    src, dst = np.nonzero(~np.eye(V, dtype=bool))
+    offsets = np.arange(V + 1, dtype=np.int32) * (V - 1)
+    return offsets, dst.astype(np.int32), D[src, dst].astype(np.float32)
+
+
+def test_csr_msf_equals_dense_prim_on_points():
+    # the complete squared-L2 graph of tie-free points: Kruskal on its CSR must give Prim's tree
+    X, _, _ = gen.make("c1", n=300)
+    D = cdist(X.astype(np.float64), X.astype(np.float64), "sqeuclidean")
+    lo, hi, w, comp = oracle.csr_msf(*_dense_to_csr(D))
+    out = oracle.slhc(X)
+    assert lo.tolist() == out["src"].tolist() and hi.tolist() == out["dst"].tolist()
+    assert np.allclose(w, out["w"], rtol=1e-6)
+    assert (comp == 0).all()
+
+
+@pytest.mark.parametrize("V", [4, 5, 6])
+def test_csr_msf_brute_force_all_spanning_trees(V):
+    rng = np.random.default_rng(V)
+    D = rng.permutation(V * V).reshape(V, V).astype(np.float64) + 1.0      # distinct weights
+    D = np.minimum(D, D.T)
+    lo, hi, w, _ = oracle.csr_msf(*_dense_to_csr(D))
+    pairs = list(itertools.combinations(range(V), 2))
+    best = None
+    for tree in itertools.combinations(pairs, V - 1):
+        up = list(range(V))
+        def find(a):
+            while up[a] != a:
+                a = up[a]
+            return a
+        ok = True
+        for a, b in tree:
+            ra, rb = find(a), find(b)
+            if ra == rb:
+                ok = False
+                break
+            up[ra] = rb
+        if ok:
+            tot = sum(D[a, b] for a, b in tree)
+            if best is None or tot < best[0]:
+                best = (tot, sorted(tree))
+    assert sorted(zip(lo.tolist(), hi.tolist())) == best[1]
+    assert float(w.sum()) == best[0]
+
+
+def test_csr_msf_forest_cycle_and_ties():
+    # two disjoint cycles: the forest drops exactly the heaviest edge of each; ties go by (lo, hi)
+    offsets = np.array([0, 2, 4, 6, 8, 10, 12, 14], dtype=np.int32)
+    und = [(0, 1, 1.0), (1, 2, 2.0), (0, 2, 3.0), (3, 4, 5.0), (4, 5, 5.0), (5, 6, 5.0), (3, 6, 5.0)]
+    rows = {v: [] for v in range(7)}
+    for a, b, w in und:
+        rows[a].append((b, w))
+        rows[b].append((a, w))
+    indices = np.array([u for v in range(7) for u, _ in sorted(rows[v])], dtype=np.int32)
+    weights = np.array([w for v in range(7) for _, w in sorted(rows[v])], dtype=np.float32)
+    lo, hi, w, comp = oracle.csr_msf(offsets, indices, weights)
+    assert list(zip(lo.tolist(), hi.tolist(), w.tolist())) == [(0, 1, 1.0), (1, 2, 2.0), (3, 4, 5.0), (3, 6, 5.0),
+                                                                 (4, 5, 5.0)]
+    assert comp.tolist() == [0, 0, 0, 3, 3, 3, 3]
+
+
+@pytest.mark.parametrize("integer_weights", [False, True])
+def test_csr_msf_road_graph_vs_scipy(integer_weights):
+    offsets, indices, weights = gen.road_graph(60, seed=3, integer_weights=integer_weights)
+    V = offsets.shape[0] - 1
+    lo, hi, w, comp = oracle.csr_msf(offsets, indices, weights)
+    G = sp.csr_matrix((weights.astype(np.float64), indices, offsets), shape=(V, V))
+    ncomp, ref_comp = csg.connected_components(G, directed=False)
+    assert lo.shape[0] == V - ncomp
+    assert _same_partition(comp, ref_comp)
+    T = csg.minimum_spanning_tree(G)                  # weights are >= 1: no zero-means-absent trap
+    assert abs(float(T.sum()) - float(w.astype(np.float64).sum())) < 1e-6 * float(T.sum())
+    assert (np.diff(w) >= 0).all() and (lo < hi).all()
+    deg = np.diff(offsets)
+    assert 2.2 < deg.mean() < 2.8
+
