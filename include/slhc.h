@@ -182,6 +182,37 @@ int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k,
                   uint32_t flags);
 
 /*
+ * Minimum spanning forest of a weighted undirected graph in CSR form (paper Sec. 3.2 "Spanning Trees",
+ * Alg. "MST Algorithm", Sec. 3.2.2 and 3.2.3; the API of the paper's MST listing: CSR graph in, edge
+ * list and colours out).
+ *
+ * Boruvka rounds with colours: every vertex finds its first outgoing edge in the strict order
+ * (weight, min endpoint, max endpoint), every component keeps the first of those, components hook and
+ * are relabelled, until a round adds no edge.  Under that order the forest is unique.  No weight
+ * alteration is applied (ties and zero weights are handled by the order).
+ *
+ *   offsets   DEVICE in   [V+1] int32, offsets[0] = 0, offsets[V] = E, non-decreasing
+ *   indices   DEVICE in   [E] int32 in [0, V)
+ *   weights   DEVICE in   [E] float32, finite and >= 0 (SLHC_INVALID_ARG otherwise; the maximum
+ *                         spanning tree by negated weights is not supported)
+ *             Every undirected edge must be stored in both rows with the same weight; self loops and
+ *             parallel edges are allowed.  An asymmetric graph can make the components hook in a cycle,
+ *             which is reported as SLHC_INTERNAL.
+ *   mst_src   DEVICE out  [V-1 capacity] int32, smaller endpoint     } the first *n_edges entries,
+ *   mst_dst   DEVICE out  [V-1 capacity] int32, larger endpoint      } ascending by (w, src, dst)
+ *   mst_w     DEVICE out  [V-1 capacity] float32                     }
+ *   n_edges   HOST   out  V minus the number of connected components
+ *   colours   DEVICE out  [V] int32: the same vertex id for all vertices of a connected component
+ *   rounds    HOST   out  optional: Boruvka rounds used
+ * Synchronous (the round loop reads a counter back every round, as the paper's host loop does).
+ */
+int slhc_csr_msf_workspace_bytes(int64_t V, int64_t E, size_t* bytes /* HOST out */);
+int slhc_csr_msf(const int32_t* offsets, const int32_t* indices, const float* weights,
+                 int64_t V, int64_t E, int32_t* mst_src, int32_t* mst_dst, float* mst_w,
+                 int64_t* n_edges, int32_t* colours, int32_t* rounds,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Flat clusters (paper Sec. 3.3.2, Alg. "extract_flattened_clusters" and Alg. "inherit_labels").
  *
  * Cuts the dendrogram after its first N - n_clusters merges.  The nodes that exist at that level

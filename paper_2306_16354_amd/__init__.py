@@ -7,5 +7,5 @@ not been built (``python -m paper_2306_16354_amd.build``) importing the binding'
 raises.
 """
 from .binding import (SlhcError, abi_version, cross_1nn, knn_graph, library_path, slhc,  # noqa: F401
-                      knn_workspace_bytes, slhc_workspace_bytes, load_library, flat_clusters, fused_1nn,
+                      knn_workspace_bytes, slhc_workspace_bytes, load_library, flat_clusters, fused_1nn, csr_msf,
                       flat_clusters_workspace_bytes)

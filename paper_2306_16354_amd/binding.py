@@ -63,6 +63,11 @@ def load_library():
     lib.slhc_fused_1nn.argtypes = [vp, i64, vp, i64, i32, vp, vp, vp, sz, vp]
     lib.slhc_fused_1nn_workspace_bytes.restype = ctypes.c_int
     lib.slhc_fused_1nn.restype = ctypes.c_int
+    lib.slhc_csr_msf_workspace_bytes.argtypes = [i64, i64, ctypes.POINTER(sz)]
+    lib.slhc_csr_msf.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, ctypes.POINTER(ctypes.c_int64), vp,
+                                 ctypes.POINTER(ctypes.c_int32), vp, sz, vp]
+    lib.slhc_csr_msf_workspace_bytes.restype = ctypes.c_int
+    lib.slhc_csr_msf.restype = ctypes.c_int
     lib.slhc_flat_clusters_workspace_bytes.argtypes = [i64, ctypes.POINTER(sz)]
     lib.slhc_flat_clusters.argtypes = [vp, i64, i64, vp, vp, sz, vp]
     lib.slhc_flat_clusters_workspace_bytes.restype = ctypes.c_int
@@ -223,4 +228,35 @@ def fused_1nn(Q, Y, workspace=None, out=None):
     _check(lib.slhc_fused_1nn(Q.data_ptr(), m, Y.data_ptr(), n, d, out[0].data_ptr(), out[1].data_ptr(),
                               workspace.data_ptr(), workspace.numel(), _stream()))
     return out
+
+
+def csr_msf(offsets, indices, weights, workspace=None):
+    """slhc_csr_msf: minimum spanning forest of a symmetric CSR graph (int32 offsets [V+1], int32
+    indices [E], float32 weights [E], CUDA tensors).  Returns a dict with mst_src, mst_dst, mst_w
+    (the forest edges, ascending by (w, src, dst)), colours [V] and rounds.  Synchronous."""
+    for t, dt in ((offsets, torch.int32), (indices, torch.int32), (weights, torch.float32)):
+        if not (t.is_cuda and t.dtype == dt and t.dim() == 1 and t.is_contiguous()):
+            raise TypeError("offsets/indices must be int32 and weights float32 contiguous CUDA vectors")
+    V = offsets.numel() - 1
+    E = indices.numel()
+    if weights.numel() != E:
+        raise ValueError("indices and weights differ in length")
+    lib = load_library()
+    if workspace is None:
+        sz = ctypes.c_size_t(0)
+        _check(lib.slhc_csr_msf_workspace_bytes(V, E, ctypes.byref(sz)))
+        workspace = _workspace(sz.value, offsets.device)
+    cap = max(V - 1, 1)
+    src = torch.empty(cap, dtype=torch.int32, device=offsets.device)
+    dst = torch.empty(cap, dtype=torch.int32, device=offsets.device)
+    w = torch.empty(cap, dtype=torch.float32, device=offsets.device)
+    colours = torch.empty(max(V, 1), dtype=torch.int32, device=offsets.device)
+    n = ctypes.c_int64(0)
+    rounds = ctypes.c_int32(0)
+    _check(lib.slhc_csr_msf(offsets.data_ptr(), indices.data_ptr() if E else None, weights.data_ptr() if E else None,
+                            V, E, src.data_ptr(), dst.data_ptr(), w.data_ptr(), ctypes.byref(n),
+                            colours.data_ptr(), ctypes.byref(rounds), workspace.data_ptr(), workspace.numel(),
+                            _stream()))
+    return dict(mst_src=src[:n.value], mst_dst=dst[:n.value], mst_w=w[:n.value], colours=colours,
+                rounds=rounds.value)
 

@@ -42,6 +42,14 @@ hipError_t forest_commit(const ForestState& f, hipStream_t s);
 hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step
 hipError_t forest_relabel(const ForestState& f, hipStream_t s);
 
+// CSR input (offsets [V+1], indices [E], weights [E]).  forest_csr_check flags malformed arrays or
+// weights that are negative / not finite in f.counters[3]; forest_csr_scan fills cand_w / cand_u with
+// every vertex's first outgoing edge in the (w, lo, hi) order and folds the weights into best_w.
+hipError_t forest_csr_check(const int32_t* offsets, const int32_t* indices, const float* weights, int V, int E,
+                            int32_t* counters, hipStream_t s);
+hipError_t forest_csr_scan(const int32_t* offsets, const int32_t* indices, const float* weights, int E,
+                           const ForestState& f, hipStream_t s);
+
 // Sort E edges ascending by (w, lo, hi).  keys/vals are scratch of E elements each; `temp` of
 // edge_sort_temp_bytes(E).  Result in out_lo/out_hi/out_w.
 size_t edge_sort_temp_bytes(int E);

@@ -224,6 +224,60 @@ __global__ void __launch_bounds__(TB) k_relabel(ForestState f)
     f.colour[v] = r;
 }
 
+// ------------------------------------------------------------------------------- CSR graphs
+// Sec. 3.2 takes the graph in CSR form.  Input check: offsets monotone from 0 to E, indices in
+// range, weights finite and non-negative (the edge order compares weight bit patterns).  A failed
+// check records its site in counters[3].
+__global__ void __launch_bounds__(TB) k_csr_check(const int32_t* __restrict__ offsets,
+                                                  const int32_t* __restrict__ indices,
+                                                  const float* __restrict__ weights, int V, int E,
+                                                  int32_t* __restrict__ counters)
+{
+    const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+    if (i < V) {
+        const int o0 = offsets[i], o1 = offsets[i + 1];
+        if (o0 < 0 || o1 < o0 || o1 > E) atomicCAS(&counters[3], 0, 20);
+        if (i == 0 && o0 != 0) atomicCAS(&counters[3], 0, 21);
+        if (i == V - 1 && o1 != E) atomicCAS(&counters[3], 0, 22);
+    }
+    if (i < E) {
+        if (!in_range(indices[i], V)) atomicCAS(&counters[3], 0, 23);
+        const float w = weights[i];
+        if (!(w >= 0.f) || w == __builtin_inff()) atomicCAS(&counters[3], 0, 24);
+    }
+}
+
+// Minimum outgoing edge of every vertex (Sec. 3.2.2 "Minimum Edge Per Vertex"): one thread scans
+// the vertex's row for the edge to another colour that is first in the order (w, lo, hi).  The
+// paper gives a warp to each vertex; road-like graphs have 2-3 edges per vertex, where a 64-wide
+// wavefront per vertex would idle, so a thread per vertex is used (a row with thousands of edges
+// is then scanned by one thread: correct, slow).
+__global__ void __launch_bounds__(TB) k_csr_scan(const int32_t* __restrict__ offsets,
+                                                 const int32_t* __restrict__ indices,
+                                                 const float* __restrict__ weights, int E, ForestState f)
+{
+    const int v = blockIdx.x * TB + threadIdx.x;
+    if (v >= f.N) return;
+    const int c = f.colour[v];
+    if (!in_range(c, f.N)) { report(f, 25); return; }
+    int o0 = offsets[v], o1 = offsets[v + 1];
+    o0 = o0 < 0 ? 0 : o0;
+    o1 = o1 > E ? E : o1;
+    uint32_t bw = INF_BITS;
+    unsigned int blo = ~0u, bhi = ~0u;
+    int bu = -1;
+    for (int e = o0; e < o1; ++e) {
+        const int u = indices[e];
+        if (!in_range(u, f.N) || f.colour[u] == c) continue;      // also drops self loops
+        const uint32_t wb = __float_as_uint(weights[e]);
+        const unsigned int lo = (unsigned int)(v < u ? v : u), hi = (unsigned int)(v < u ? u : v);
+        if (wb < bw || (wb == bw && (lo < blo || (lo == blo && hi < bhi)))) { bw = wb; blo = lo; bhi = hi; bu = u; }
+    }
+    f.cand_u[v] = bu;
+    f.cand_w[v] = __uint_as_float(bw);
+    if (bu >= 0) min_into(&f.best_w[c], bw);
+}
+
 #define LAUNCH1(kern, n, s, ...)                                                       \
     do {                                                                               \
         hipLaunchKernelGGL(kern, dim3(blocks_for(n)), dim3(TB), 0, s, __VA_ARGS__);    \
@@ -253,6 +307,18 @@ hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_
 hipError_t forest_commit(const ForestState& f, hipStream_t s) { LAUNCH1(k_commit, f.N, s, f); }
 hipError_t forest_jump(const ForestState& f, hipStream_t s) { LAUNCH1(k_jump, f.N, s, f); }
 hipError_t forest_relabel(const ForestState& f, hipStream_t s) { LAUNCH1(k_relabel, f.N, s, f); }
+
+hipError_t forest_csr_check(const int32_t* offsets, const int32_t* indices, const float* weights, int V, int E,
+                            int32_t* counters, hipStream_t s)
+{
+    LAUNCH1(k_csr_check, (V > E ? V : E), s, offsets, indices, weights, V, E, counters);
+}
+
+hipError_t forest_csr_scan(const int32_t* offsets, const int32_t* indices, const float* weights, int E,
+                           const ForestState& f, hipStream_t s)
+{
+    LAUNCH1(k_csr_scan, f.N, s, offsets, indices, weights, E, f);
+}
 
 // ------------------------------------------------------------------------------- edge sort
 __global__ void __launch_bounds__(TB) k_pack_edges(const int32_t* __restrict__ lo,

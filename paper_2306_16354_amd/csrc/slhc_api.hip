@@ -571,6 +571,113 @@ int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour, 
     return SLHC_OK;
 }
 
+struct CsrWs {
+    int32_t *colour, *ptr, *ext_idx, *cand_u, *hook, *counters, *e_lo, *e_hi;
+    float *ext_dist, *cand_w, *e_w;
+    uint32_t *best_w, *min_lb, *vals_a, *vals_b;
+    unsigned long long *best_e, *keys_a, *keys_b;
+    void* sort_temp; size_t sort_temp_bytes;
+    size_t bytes;
+    CsrWs(void* ws, int64_t V)
+    {
+        Carver c(ws);
+        const size_t n = (size_t)V;
+        colour = c.take<int32_t>(n); ptr = c.take<int32_t>(n); ext_idx = c.take<int32_t>(n);
+        cand_u = c.take<int32_t>(n); hook = c.take<int32_t>(n); counters = c.take<int32_t>(64);
+        e_lo = c.take<int32_t>(n); e_hi = c.take<int32_t>(n);
+        ext_dist = c.take<float>(n); cand_w = c.take<float>(n); e_w = c.take<float>(n);
+        best_w = c.take<uint32_t>(n); min_lb = c.take<uint32_t>(n);
+        vals_a = c.take<uint32_t>(n); vals_b = c.take<uint32_t>(n);
+        best_e = c.take<unsigned long long>(n); keys_a = c.take<unsigned long long>(n); keys_b = c.take<unsigned long long>(n);
+        sort_temp_bytes = slhc::edge_sort_temp_bytes((int)(V > 1 ? V - 1 : 1));
+        sort_temp = c.take<unsigned char>(sort_temp_bytes);
+        bytes = c.off;
+    }
+};
+
+static int csr_shape(int64_t V, int64_t E)
+{
+    if (V < 1 || E < 0) { set_err("need V >= 1 and E >= 0 (V=%lld E=%lld)", (long long)V, (long long)E); return SLHC_INVALID_ARG; }
+    if (V > 2147483646LL || E > 2147483647LL) { set_err("V or E exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+    return SLHC_OK;
+}
+
+int slhc_csr_msf_workspace_bytes(int64_t V, int64_t E, size_t* bytes)
+{
+    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+    const int rc = csr_shape(V, E);
+    if (rc != SLHC_OK) return rc;
+    *bytes = CsrWs(nullptr, V).bytes;
+    return SLHC_OK;
+}
+
+int slhc_csr_msf(const int32_t* offsets, const int32_t* indices, const float* weights, int64_t V, int64_t E,
+                 int32_t* mst_src, int32_t* mst_dst, float* mst_w, int64_t* n_edges, int32_t* colours,
+                 int32_t* rounds, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!offsets || (E > 0 && (!indices || !weights)) || !mst_src || !mst_dst || !mst_w || !n_edges || !colours || !workspace) {
+        set_err("NULL pointer argument");
+        return SLHC_INVALID_ARG;
+    }
+    const int rc = csr_shape(V, E);
+    if (rc != SLHC_OK) return rc;
+    CsrWs ws(workspace, V);
+    if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    slhc::ForestState f{};
+    f.N = (int)V; f.k = 1;
+    f.colour = ws.colour; f.ptr = ws.ptr; f.ext_idx = ws.ext_idx; f.ext_dist = ws.ext_dist;
+    f.cand_w = ws.cand_w; f.cand_u = ws.cand_u; f.best_w = ws.best_w; f.best_e = ws.best_e;
+    f.min_lb = ws.min_lb; f.hook = ws.hook; f.qlist = ws.ptr; f.counters = ws.counters;
+    f.e_lo = ws.e_lo; f.e_hi = ws.e_hi; f.e_w = ws.e_w;
+    HIP_TRY(slhc::forest_init(f, s));
+    HIP_TRY(slhc::forest_csr_check(offsets, indices, weights, (int)V, (int)E, ws.counters, s));
+    PinnedHost pin_cnt;
+    HIP_TRY(pin_cnt.alloc(64));
+    int32_t* h_cnt = static_cast<int32_t*>(pin_cnt.p);
+    HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (h_cnt[3] != 0) {
+        set_err("CSR input check %d failed (20-22: offsets, 23: index out of range, 24: weight negative or not finite)", h_cnt[3]);
+        return SLHC_INVALID_ARG;
+    }
+    int edges = 0, nrounds = 0;
+    int max_rounds = 2;
+    for (int64_t t = 1; t < V; t *= 2) ++max_rounds;
+    // Alg. "MST Algorithm": min edge per vertex, min edge per supervertex, label propagation, until a
+    // round adds no edge (the graph's components are then the forest's trees)
+    while (edges < V - 1) {
+        if (nrounds >= max_rounds) { set_err("no steady state after %d rounds", max_rounds); return SLHC_INTERNAL; }
+        ++nrounds;
+        HIP_TRY(slhc::forest_round_reset(f, s));
+        HIP_TRY(slhc::forest_csr_scan(offsets, indices, weights, (int)E, f, s));
+        HIP_TRY(slhc::forest_select_edges(f, s));
+        HIP_TRY(slhc::forest_commit(f, s));
+        int jumps = 0;
+        do {
+            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(slhc::forest_jump(f, s));
+            HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            if (++jumps > 64) { set_err("component hooks do not form a forest (is every edge stored in both rows with one weight?)"); return SLHC_INTERNAL; }
+            if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+        } while (h_cnt[2] != 0);
+        HIP_TRY(slhc::forest_relabel(f, s));
+        if (h_cnt[1] < edges || h_cnt[1] > V - 1) { set_err("round left %d edges (had %d)", h_cnt[1], edges); return SLHC_INTERNAL; }
+        if (h_cnt[1] == edges) break;                 // steady state: a spanning forest
+        edges = h_cnt[1];
+    }
+    if (edges > 0)
+        HIP_TRY(slhc::edge_sort(ws.e_lo, ws.e_hi, ws.e_w, edges, ws.keys_a, ws.keys_b, ws.vals_a, ws.vals_b,
+                                ws.sort_temp, ws.sort_temp_bytes, mst_src, mst_dst, mst_w, s));
+    HIP_TRY(hipMemcpyAsync(colours, ws.colour, (size_t)V * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *n_edges = edges;
+    if (rounds) *rounds = nrounds;
+    return SLHC_OK;
+}
+
 static size_t fused_1nn_layout(void* ws, int64_t m, int64_t n, float** hq, float** hy, unsigned long long** keys)
 {
     Carver c(ws);

@@ -444,6 +444,69 @@ def test_fused_1nn_finds_itself_and_ties(lib):
     assert np.array_equal(gd.cpu().numpy().astype(np.float64), od)
 
 
+# ----------------------------------------------------------------------------- CSR spanning forest
+# Under the strict edge order (w, lo, hi) the forest is unique: integer work, compared exactly.
+def check_csr_msf(lib, offsets, indices, weights):
+    got = lib.csr_msf(torch.from_numpy(offsets).cuda(), torch.from_numpy(indices).cuda(),
+                      torch.from_numpy(weights).cuda())
+    lo, hi, w, comp = oracle.csr_msf(offsets, indices, weights)
+    assert np.array_equal(got["mst_src"].cpu().numpy(), lo)
+    assert np.array_equal(got["mst_dst"].cpu().numpy(), hi)
+    assert np.array_equal(got["mst_w"].cpu().numpy(), w)
+    col = got["colours"].cpu().numpy()
+    pairs = set(zip(col.tolist(), comp.tolist()))
+    assert len(pairs) == len(set(comp.tolist())) == len(set(col.tolist()))
+    assert (col[col] == col).all()                       # a colour is a vertex of its own component
+    return got
+
+
+@pytest.mark.parametrize("side,integer_weights", [(40, False), (300, False), (300, True), (700, False)])
+def test_csr_msf_road_graphs(lib, side, integer_weights):
+    print(f"csr msf side={side} integer_weights={integer_weights}", flush=True)
+    offsets, indices, weights = gen.road_graph(side, seed=side, integer_weights=integer_weights)
+    got = check_csr_msf(lib, offsets, indices, weights)
+    assert 1 <= got["rounds"] <= int(np.ceil(np.log2(side * side))) + 2
+
+
+def test_csr_msf_complete_graph_equals_point_mst(lib):
+    # the complete squared-L2 graph of a point set, fed as CSR: same tree as the point pipeline
+    X, _, k = gen.make("c1", n=600)
+    N = X.shape[0]
+    D = ((X[:, None, :].astype(np.float64) - X[None, :, :].astype(np.float64)) ** 2).sum(-1).astype(np.float32)
+    src, dst = np.nonzero(~np.eye(N, dtype=bool))
+    offsets = (np.arange(N + 1) * (N - 1)).astype(np.int32)
+    got = check_csr_msf(lib, offsets, dst.astype(np.int32), D[src, dst])
+    out = lib.slhc(torch.from_numpy(X).cuda(), k)
+    assert np.array_equal(got["mst_src"].cpu().numpy(), out["mst_src"].cpu().numpy())
+    assert np.array_equal(got["mst_dst"].cpu().numpy(), out["mst_dst"].cpu().numpy())
+
+
+def test_csr_msf_degenerate_and_errors(lib):
+    z = lambda a, dt: torch.tensor(a, dtype=dt, device="cuda")
+    # no edges at all: every vertex its own component
+    got = lib.csr_msf(z([0, 0, 0, 0], torch.int32), z([], torch.int32), z([], torch.float32))
+    assert got["mst_src"].numel() == 0 and got["colours"].tolist() == [0, 1, 2]
+    # self loops and parallel edges of different weight
+    offsets = np.array([0, 3, 6], dtype=np.int32)
+    indices = np.array([0, 1, 1, 0, 0, 1], dtype=np.int32)
+    weights = np.array([0.5, 3.0, 2.0, 3.0, 2.0, 0.25], dtype=np.float32)
+    got = check_csr_msf(lib, offsets, indices, weights)
+    assert got["mst_w"].tolist() == [2.0]
+    # zero weights and duplicates of them
+    offsets, indices, weights = gen.road_graph(30, seed=9, integer_weights=True)
+    check_csr_msf(lib, offsets, indices, (weights - 1.0).astype(np.float32) * (weights < 4))
+    for bad_w in (-1.0, float("nan"), float("inf")):
+        with pytest.raises(lib.SlhcError) as e:
+            lib.csr_msf(z([0, 1, 2], torch.int32), z([1, 0], torch.int32), z([bad_w, bad_w], torch.float32))
+        assert e.value.status == 1
+    with pytest.raises(lib.SlhcError) as e:
+        lib.csr_msf(z([0, 1, 2], torch.int32), z([1, 7], torch.int32), z([1.0, 1.0], torch.float32))
+    assert e.value.status == 1
+    with pytest.raises(lib.SlhcError) as e:
+        lib.csr_msf(z([0, 2, 1], torch.int32), z([1, 0], torch.int32), z([1.0, 1.0], torch.float32))
+    assert e.value.status == 1
+
+
 # ----------------------------------------------------------------------------- flat clusters
 # Integer work: labels must equal the oracle's exactly when both cut the same dendrogram.
 @pytest.mark.parametrize("name,n", [("c1", None), ("c2", 20000), ("c5", 30000)])
