@@ -398,6 +398,53 @@ def test_pruned_slhc_is_identical(lib, name, n):
           b["stats"]["order_padded_rows"], "order ms", round(b["stats"]["ms_order"], 2), flush=True)
 
 
+def _pruned_equals_every_tile(lib, X, k):
+    Xd = torch.from_numpy(np.ascontiguousarray(X, dtype=np.float32)).cuda()
+    i0, d0 = lib.knn_graph(Xd, k, prune=False)
+    i1, d1 = lib.knn_graph(Xd, k, prune=True)
+    torch.cuda.synchronize()
+    assert torch.equal(i0, i1) and torch.equal(d0, d1)
+    a = lib.slhc(Xd, k, prune=False)
+    b = lib.slhc(Xd, k, prune=True)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(a[name_], b[name_]), name_
+    return b
+
+
+def test_pruned_with_outliers_uniform_and_duplicates(lib):
+    rng = np.random.default_rng(11)
+    # blobs plus 5 % uniform noise: the noise rows end up far from every pivot
+    X, _, _ = gen.make("c1", n=19000)
+    noise = rng.uniform(-12, 12, size=(1000, X.shape[1])).astype(np.float32)
+    Xn = np.concatenate([X, noise])[rng.permutation(20000)]
+    print("pruned: blobs + outliers", flush=True)
+    b = _pruned_equals_every_tile(lib, Xn, 16)
+    assert b["stats"]["pruned"] == 1
+    check_slhc(Xn[:3000], lib.slhc(torch.from_numpy(np.ascontiguousarray(Xn[:3000])).cuda(), 16), tie_free=True)
+    # no cluster structure at all
+    print("pruned: uniform cube", flush=True)
+    _pruned_equals_every_tile(lib, gen.uniform_cube(15000, 8, seed=5), 8)
+    # half of the rows are exact copies of other rows (zero distances, mass ties)
+    print("pruned: duplicates", flush=True)
+    base = rng.standard_normal((4000, 12)).astype(np.float32)
+    Xdup = np.concatenate([base, base[rng.integers(0, 4000, size=4000)]])[rng.permutation(8000)]
+    _pruned_equals_every_tile(lib, Xdup, 4)
+    # one single point repeated: every distance is zero
+    print("pruned: one point", flush=True)
+    _pruned_equals_every_tile(lib, np.ones((700, 8), dtype=np.float32), 3)
+
+
+@pytest.mark.parametrize("N,d,k", [(512, 4, 3), (513, 36, 7), (1000, 128, 64), (2049, 20, 1), (6000, 100, 32)])
+def test_pruned_ragged_shapes(lib, N, d, k):
+    print(f"pruned ragged N={N} d={d} k={k}", flush=True)
+    rng = np.random.default_rng(N + d)
+    centres = rng.uniform(-20, 20, size=(7, d))
+    X = (centres[rng.integers(0, 7, size=N)] + rng.standard_normal((N, d))).astype(np.float32)
+    b = _pruned_equals_every_tile(lib, X, k)
+    assert b["stats"]["pruned"] == 1
+    check_slhc(X, b, tie_free=True)
+
+
 # ----------------------------------------------------------------------------- 1-NN between two matrices
 # The oracle has no two-matrix search of its own; its cross-colour 1-NN on the stacked matrix
 # [Q; Y] with colour 0 for the query rows and 1 for the index rows is the same definition.
@@ -548,6 +595,36 @@ def test_flat_clusters_recover_the_blobs(lib):
     got = lib.flat_clusters(out["children"], int(labels.max()) + 1).cpu().numpy()
     pairs = set(zip(got.tolist(), labels.tolist()))
     assert len(pairs) == int(labels.max()) + 1
+
+
+# ----------------------------------------------------------------------------- full size (c5)
+def test_c5_full_size_pruned_equals_every_tile(lib):
+    """c5 at its full size (2M x 32, k=8; 20 000 small blobs, exact duplicates): sampled rows of the
+    k-NN graph against the oracle, and the pruned path against the every-tile path bit for bit."""
+    X, _, k = gen.make("c5")
+    N = X.shape[0]
+    Xd = torch.from_numpy(X).cuda()
+    print("c5 full: knn", flush=True)
+    idx, dist = lib.knn_graph(Xd, k)
+    idx_p, dist_p = lib.knn_graph(Xd, k, prune=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx_p) and torch.equal(dist, dist_p)
+    gi, gd = idx.cpu().numpy(), dist.cpu().numpy()
+    rows = np.random.default_rng(55).choice(N, size=256, replace=False)
+    check_knn(X, k, gi[rows], gd[rows], rows=rows, min_exact=0.9)
+    del idx_p, dist_p
+    print("c5 full: slhc", flush=True)
+    a = lib.slhc(Xd, k, prune=False)
+    b = lib.slhc(Xd, k, prune=True)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(a[name_], b[name_]), name_
+    w = b["mst_w"].cpu().numpy()
+    src, dst = b["mst_src"].cpu().numpy(), b["mst_dst"].cpu().numpy()
+    es = np.random.default_rng(56).choice(N - 1, size=200_000, replace=False)
+    assert close(w[es], pair_dist64(X, src[es], dst[es]), RTOL_DIST).all()
+    assert int(b["sizes"][-1]) == N
+    # the 1 % exact copies give at least that many zero-weight tree edges
+    assert int((w == 0.0).sum()) >= 15_000
 
 
 # ----------------------------------------------------------------------------- full size (headline)
