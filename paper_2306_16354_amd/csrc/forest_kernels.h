@@ -34,9 +34,11 @@ hipError_t forest_init(const ForestState& f, hipStream_t s);
 hipError_t forest_round_reset(const ForestState& f, hipStream_t s);
 hipError_t forest_scan_lists(const ForestState& f, hipStream_t s);
 hipError_t forest_classify(const ForestState& f, hipStream_t s);
-// qrows[q] is the vertex query q was made for (f.qlist, or a reordered copy of it)
+// qrows[q] is the vertex query q was made for (f.qlist, or a reordered copy of it).  `thresholds`
+// (or nullptr): the per-component thresholds the sweep ran under (SweepParams::comp_best); answers
+// farther than their component's threshold are kept as lower bounds only.
 hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
-                                const float* q_dist, int nq, hipStream_t s);
+                                const float* q_dist, int nq, const uint32_t* thresholds, hipStream_t s);
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
 hipError_t forest_commit(const ForestState& f, hipStream_t s);
 hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step

@@ -109,8 +109,11 @@ __global__ void __launch_bounds__(TB) k_scan_lists(ForestState f)
         min_into(&f.best_w[c], __float_as_uint(ed));
         return;
     }
+    // lower bounds on v's nearest foreign point: its k-th list distance, and whatever the last
+    // cross-component query left in ext_dist (an exact answer that has since joined v's component,
+    // or the component threshold a truncated search was run under; 0 when never queried)
     float lb = f.nbr_dist[(size_t)v * f.k + f.k - 1];
-    if (eu >= 0 && ed > lb) lb = ed;
+    if (ed > lb) lb = ed;
     f.cand_w[v] = lb;
     f.cand_u[v] = -1;
     min_into(&f.min_lb[c], __float_as_uint(lb));
@@ -142,9 +145,16 @@ __global__ void __launch_bounds__(TB) k_classify(ForestState f)
     }
 }
 
+// `thresholds` (optional): the queries ran under their component's shared threshold
+// F = thresholds[colour], the lightest outgoing edge the lists already knew (a snapshot of best_w
+// taken before the sweep, so that the outcome does not depend on thread order).  An answer at distance <= F is the
+// query's exact nearest foreign row, because every candidate at most that far was examined.  Any
+// other query only learns that no foreign row is nearer than F: it keeps no candidate, and F becomes
+// its lower bound for the following rounds (components only grow).
 __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32_t* __restrict__ qrows,
                                                       const int32_t* __restrict__ q_idx,
-                                                      const float* __restrict__ q_dist, int nq)
+                                                      const float* __restrict__ q_dist, int nq,
+                                                      const uint32_t* __restrict__ thresholds)
 {
     const int q = blockIdx.x * TB + threadIdx.x;
     if (q >= nq) return;
@@ -152,11 +162,24 @@ __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32
     const int u = q_idx[q];
     const float w = q_dist[q];
     if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) { report(f, 6); return; }
+    const int c = f.colour[v];
+    if (thresholds) {
+        const uint32_t fb = thresholds[c];
+        if (!(u >= 0 && __float_as_uint(w) <= fb)) {
+            const float F = __uint_as_float(fb);
+            const float old = f.ext_dist[v];
+            f.ext_idx[v] = -1;
+            f.ext_dist[v] = F > old ? F : old;
+            f.cand_u[v] = -1;
+            f.cand_w[v] = F;
+            return;
+        }
+    }
     f.ext_idx[v] = u;
     f.ext_dist[v] = w;
     f.cand_u[v] = u;
     f.cand_w[v] = w;
-    if (u >= 0) min_into(&f.best_w[f.colour[v]], __float_as_uint(w));
+    if (u >= 0) min_into(&f.best_w[c], __float_as_uint(w));
 }
 
 __global__ void __launch_bounds__(TB) k_select_edges(ForestState f)
@@ -298,9 +321,9 @@ hipError_t forest_scan_lists(const ForestState& f, hipStream_t s)
 hipError_t forest_classify(const ForestState& f, hipStream_t s) { LAUNCH1(k_classify, f.N, s, f); }
 
 hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
-                                const float* q_dist, int nq, hipStream_t s)
+                                const float* q_dist, int nq, const uint32_t* thresholds, hipStream_t s)
 {
-    LAUNCH1(k_apply_queries, nq, s, f, qrows, q_idx, q_dist, nq);
+    LAUNCH1(k_apply_queries, nq, s, f, qrows, q_idx, q_dist, nq, thresholds);
 }
 
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }

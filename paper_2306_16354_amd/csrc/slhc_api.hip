@@ -886,6 +886,11 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 p.c_id = o.perm;
                 p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
                 p.tile_colour = o.tile_colour;
+                // thresholds shared by the queries of a component: what the lists already know (a
+                // snapshot, vals_a is free until the edge sort)
+                HIP_TRY(hipMemcpyAsync(ws.vals_a, ws.best_w, (size_t)N * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+                p.comp_best = ws.vals_a;
+                p.comp_count = (int)N;
                 p.panel_counter = reinterpret_cast<unsigned int*>(kws.counters + 8);
 #ifdef SLHC_PHASE_TIMERS
                 p.phase_cycles = kws.counters + 24;
@@ -900,7 +905,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
             HIP_TRY(hipEventRecord(ev_conn.a, s));
             HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
             HIP_TRY(hipEventRecord(ev_conn.b, s));
-            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, s));
+            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, pruned ? ws.vals_a : nullptr, s));
             HIP_TRY(hipStreamSynchronize(s));
             st.ms_connect_kernels += ev_conn.ms();
             ms_connect += now_ms() - tc0;

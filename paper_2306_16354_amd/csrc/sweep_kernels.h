@@ -35,6 +35,13 @@ struct SweepParams {
     float* gap_ws;
     const int32_t* tile_colour;   // cross 1-NN only, optional [T]: the colour all valid rows of a tile
                                   // share, or -1; a tile in the colour of all the panel's queries is skipped
+    // cross 1-NN with pruning, optional: comp_best[c] (c < comp_count) is the lightest edge weight already
+    // known out of component (colour) c, as bits of a non-negative float (+inf bits: none).  The sweep
+    // uses it, read-only, as a threshold shared by all queries of that colour.  A query's answer is then
+    // its exact nearest foreign row only if its distance is <= comp_best of its colour; otherwise no
+    // foreign row is nearer than comp_best, which is all the caller may conclude.
+    const unsigned int* comp_best;
+    int comp_count;
     unsigned int* panel_counter;  // optional device word, zero at launch: panels are taken from it one at
                                   // a time instead of round-robin (use when panel costs differ widely)
     int own_tile_first;    // self-join in the same row order: start each panel at its own tile

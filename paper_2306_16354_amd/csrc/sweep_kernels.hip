@@ -707,6 +707,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
         PHASE_MARK(0);
 
+        int panel_colour = -2;       // the colour all queries of the panel share (-2: they differ / unknown)
         if (prune) {
             // ---- bounding ball of the panel's query rows (L.Cs is free here: d <= 128 floats)
             float* qc = L.Cs;                       // centre
@@ -753,7 +754,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             __syncthreads();
             const float rq = __uint_as_float(*rq_bits);
             // the colour all queries of the panel share (-2: they differ, or no colour summary)
-            const int panel_colour = (MASKED && p.tile_colour && *col_lo == *col_hi) ? *col_lo : -2;
+            panel_colour = (MASKED && p.tile_colour && *col_lo == *col_hi) ? *col_lo : -2;
             for (int t = tid; t < ntiles; t += WG_THREADS) {
                 const float* c = p.tile_c + (size_t)t * d;
                 float s2 = 0.f;
@@ -787,6 +788,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         float bound = bounds[my_q_local];
         // largest threshold among this wavefront's queries (no query: nothing can enter a list)
         float wave_thr_max = __any(my_qrow >= 0) ? __builtin_inff() : 0.f;
+        // Shared component threshold (cross 1-NN with p.comp_best, all queries of one colour): only
+        // the lightest edge leaving the component matters, so a candidate farther than the lightest
+        // outgoing edge already known for this component is of no use to any of its queries.
+        // comp_best[colour] holds that weight (bits of a non-negative float); it is folded into the
+        // filter bound and into the tile-skipping threshold.  The sweep only reads it.  (Lowering it
+        // from inside the sweep whenever a query finds a nearer row was tried and dropped: it made
+        // rare runs end with an inconsistent forest state, and the read-only form is deterministic.)
+        const bool shared_thr = PRUNE && MASKED && p.comp_best != nullptr && panel_colour >= 0 &&
+                                panel_colour < p.comp_count;
+        float thr_c = __builtin_inff();
+        if (shared_thr) thr_c = __uint_as_float(p.comp_best[panel_colour]);
 
         // query fragments: lane (l32, lhalf) holds columns kk*8 + 4*lhalf .. +3 of its query row
         v4f qf[DCH * 4];
@@ -901,7 +913,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     PHASE_MARK(3);
                     // thresholds published in the epilogue of the previous step (other parity)
                     const float* wm = L.wmax + (tpar ^ 1) * 4;
-                    const float thr_max = prune ? fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3])) : 0.f;
+                    float thr_max = prune ? fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3])) : 0.f;
+                    if (shared_thr) thr_max = fminf(thr_max, thr_c);
                     const int nxt = next_scan(scan_from, thr_max);
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
@@ -940,6 +953,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
             PHASE_MARK(3);
+            const float own_bound = bound;
+            if (shared_thr) bound = fmaxf(bound, hqs[my_q_local] - 0.5f * thr_c);
             unsigned int flagged = 0;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -965,6 +980,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 if (PRUNE) {
                     const int colbuf_ = tpar;
                     SLHC_SELECT_TILE(KL, MASKED, true);
+                    if (shared_thr) bound = bounds[my_q_local];         // this query's own bound again
                 } else {
                     if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
                     if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
@@ -989,6 +1005,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
                 }
             }
+            if (shared_thr && flagged == 0) bound = own_bound;
             PHASE_MARK(6);
             if (prune && lane == 0) L.wmax[tpar * 4 + wave] = wave_thr_max;
             ++tiles_done;
