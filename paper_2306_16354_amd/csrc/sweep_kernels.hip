@@ -1,8 +1,11 @@
 // Fused distance + selection sweeps for gfx950 (MI355X).
 //
-// One kernel template serves the two nearest-neighbour primitives of the cuSLINK paper:
+// The two nearest-neighbour primitives of the cuSLINK paper share one tile/filter/select design:
 //   - fused k-NN      (Sec. 3.1.1, Alg. "Fused k-NN"; epilogues of Appendix A)
 //   - fused 1-NN restricted to points of another colour (Sec. 3.1.2, Alg. "Fused 1-NN")
+// in two kernels: sweep_kernel streams query and candidate chunks through LDS (any d), and
+// sweep_kernel_qreg keeps the query fragments in registers (d <= 128, d % 4 == 0) and can skip
+// candidate tiles that provably hold nothing of use (tile pruning, not in the paper).
 //
 // Structure (our own design for 64-wide wavefronts, not the paper's CUDA tiling):
 //   * a workgroup (4 wavefronts) owns a panel of 128 query rows and sweeps all N candidate rows
