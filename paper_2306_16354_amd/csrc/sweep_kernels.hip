@@ -293,6 +293,16 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
         const unsigned long long key = make_key(dist, cid);
         // a stale k-th entry is only larger than the current one, so this test never drops a
         // pair that belongs in the list; wave_list_insert tests again
+        if constexpr (KL == 1) {
+            // k = 1: a list is one key, so the eight group leaders update their queries at once
+            // (64-bit LDS minimum; two pairs of one query in the same pass are ordered by it) and
+            // then refresh the bounds from what the lists hold, exactly as wave_list_insert would
+            if (valid && g8 == 0) atomicMin(&mylists[ql], key);
+            __builtin_amdgcn_wave_barrier();
+            if (valid && g8 == 0)
+                L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
+            continue;
+        }
         const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
         unsigned long long todo = __ballot(accept);
         while (todo) {
