@@ -369,6 +369,15 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
         const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
         const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
         const int cid = (c_id && valid) ? c_id[cg] : cg;      // id that orders ties and is reported
+        if constexpr (KL == 1) {
+            // k = 1: one key per query; the four group leaders update their queries at once
+            // (64-bit LDS minimum), then refresh the bounds as wave_list_insert would
+            if (valid && g16 == 0) atomicMin(&mylists[ql], make_key(dist, cid));
+            __builtin_amdgcn_wave_barrier();
+            if (valid && g16 == 0)
+                L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
+            continue;
+        }
         const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
         for (int g = 0; g < npass; ++g) {
             const float dg = __shfl(dist, g * 16);
