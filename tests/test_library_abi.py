@@ -26,7 +26,10 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ("slhc_knn_graph", "slhc_slhc", "slhc_cross_1nn", "slhc_workspace_bytes",
-                 "slhc_knn_workspace_bytes", "slhc_last_error", "slhc_strerror", "slhc_abi_version"):
+                 "slhc_knn_workspace_bytes", "slhc_last_error", "slhc_strerror", "slhc_abi_version",
+                 "slhc_knn_graph_opt", "slhc_slhc_opt", "slhc_flat_clusters", "slhc_fused_1nn", "slhc_csr_msf",
+                 "slhc_flat_clusters_workspace_bytes", "slhc_fused_1nn_workspace_bytes",
+                 "slhc_csr_msf_workspace_bytes"):
         assert must in names
 
 
@@ -62,6 +65,38 @@ def test_null_pointers_are_rejected_before_any_device_work(cdll):
     assert cdll.slhc_knn_graph(None, 10, 4, 2, None, None, None, 0, None) == 1
     assert cdll.slhc_slhc(None, 10, 4, 2, None, None, None, None, None, None, None, None, 0, None) == 1
     assert cdll.slhc_cross_1nn(None, 10, 4, None, None, 5, None, None, None, 0, None) == 1
+
+
+def test_later_entry_points_check_arguments_on_the_host(cdll):
+    out = ctypes.c_size_t(0)
+    # flat clusters
+    assert cdll.slhc_flat_clusters_workspace_bytes(1_000_000, ctypes.byref(out)) == 0
+    assert out.value >= 3 * 8 * 1_000_000 and out.value % 256 == 0
+    assert cdll.slhc_flat_clusters_workspace_bytes(1, ctypes.byref(out)) == 1
+    assert cdll.slhc_flat_clusters_workspace_bytes(1 << 30, ctypes.byref(out)) == 2
+    assert cdll.slhc_flat_clusters(None, 10, 2, None, None, 0, None) == 1
+    one = ctypes.c_int32(0)
+    ptr = ctypes.cast(ctypes.pointer(one), ctypes.c_void_p)          # never dereferenced: checks come first
+    assert cdll.slhc_flat_clusters(ptr, 10, 0, ptr, ptr, 1 << 20, None) == 1       # n_clusters < 1
+    assert cdll.slhc_flat_clusters(ptr, 10, 11, ptr, ptr, 1 << 20, None) == 1      # n_clusters > N
+    assert cdll.slhc_flat_clusters(ptr, 10, 2, ptr, ptr, 16, None) == 3            # workspace too small
+    # fused 1-NN between two matrices
+    assert cdll.slhc_fused_1nn_workspace_bytes(1000, 100_000, 128, ctypes.byref(out)) == 0
+    assert out.value >= 4 * 101_000 + 8 * 1000
+    assert cdll.slhc_fused_1nn_workspace_bytes(0, 10, 4, ctypes.byref(out)) == 1
+    assert cdll.slhc_fused_1nn_workspace_bytes(10, 1 << 29, 8, ctypes.byref(out)) == 2
+    assert cdll.slhc_fused_1nn(None, 10, None, 10, 4, None, None, None, 0, None) == 1
+    assert cdll.slhc_fused_1nn(ptr, 10, ptr, 10, 4, ptr, ptr, ptr, 16, None) == 3
+    # spanning forest of a CSR graph
+    assert cdll.slhc_csr_msf_workspace_bytes(1_000_000, 2_500_000, ctypes.byref(out)) == 0
+    assert out.value >= 60 * 1_000_000
+    assert cdll.slhc_csr_msf_workspace_bytes(0, 0, ctypes.byref(out)) == 1
+    assert cdll.slhc_csr_msf_workspace_bytes(10, -1, ctypes.byref(out)) == 1
+    assert cdll.slhc_csr_msf_workspace_bytes(1 << 31, 10, ctypes.byref(out)) == 2
+    assert cdll.slhc_csr_msf(None, None, None, 10, 5, None, None, None, None, None, None, None, 0, None) == 1
+    n = ctypes.c_int64(0)
+    assert cdll.slhc_csr_msf(ptr, ptr, ptr, 10, 5, ptr, ptr, ptr, ctypes.byref(n), ptr, None, ptr, 16, None) == 3
+    assert b"workspace" in cdll.slhc_last_error()
 
 
 def test_binding_refuses_cpu_tensors():
