@@ -49,8 +49,8 @@ def main():
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here shards across "
-              "GPUs, see DESIGN.md for how the path would)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (nothing here shards across GPUs; "
+              "the path would shard by query rows with one all-gather of the neighbour lists)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
