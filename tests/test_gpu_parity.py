@@ -445,6 +445,37 @@ def test_pruned_ragged_shapes(lib, N, d, k):
     check_slhc(X, b, tie_free=True)
 
 
+def test_pruned_random_shapes(lib):
+    """Seeded random shapes (rows, features, k, number and spread of blobs, duplicates, quantised
+    coordinates): pruned and every-tile paths agree bit for bit, twice in a row with the same
+    counters, and the small cases also match the oracle."""
+    rng = np.random.default_rng(2023)
+    for case in range(24):
+        N = int(rng.integers(520, 30000)) if case % 4 else int(rng.integers(520, 3000))
+        d = int(rng.choice([4, 8, 12, 16, 20, 32, 36, 64, 100, 128]))
+        k = int(rng.integers(1, 65))
+        nb = int(rng.integers(1, 200))
+        spread = float(rng.choice([3.0, 20.0, 1000.0]))
+        sigma = float(rng.choice([0.05, 1.0, 3.0]))
+        centres = rng.uniform(-spread, spread, size=(nb, d))
+        X = (centres[rng.integers(0, nb, size=N)] + sigma * rng.standard_normal((N, d))).astype(np.float32)
+        ties = False
+        if rng.random() < 0.3:
+            m = N // 10
+            X[rng.integers(0, N, size=m)] = X[rng.integers(0, N, size=m)]
+            ties = True
+        if rng.random() < 0.3:
+            X = (np.round(X * 2) / 2).astype(np.float32)
+            ties = True
+        print(f"random case {case}: N={N} d={d} k={k} blobs={nb} spread={spread} sigma={sigma} ties={ties}", flush=True)
+        b = _pruned_equals_every_tile(lib, X, k)
+        b2 = lib.slhc(torch.from_numpy(np.ascontiguousarray(X)).cuda(), k)
+        assert b2["stats"]["connect_query_rows"] == b["stats"]["connect_query_rows"]
+        assert b2["stats"]["connect_tile_steps"] == b["stats"]["connect_tile_steps"]
+        if N <= 3000:
+            check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
+
+
 # ----------------------------------------------------------------------------- 1-NN between two matrices
 # The oracle has no two-matrix search of its own; its cross-colour 1-NN on the stacked matrix
 # [Q; Y] with colour 0 for the query rows and 1 for the index rows is the same definition.
