@@ -157,7 +157,7 @@ struct OrderWs {
     {
         const size_t n = (size_t)N;
         P1 = first_level_pivots(N);
-        Pmax = 2 * P1;
+        Pmax = 4 * P1;            // budget for pivots added for clusters the first level missed
         Nmax = padded_rows_limit(N);
         Tmax = (int)((Nmax + 127) / 128);
         const size_t nm = (size_t)Nmax, pm = (size_t)Pmax;
@@ -285,7 +285,11 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
     HIP_TRY(hipMemcpyAsync(h_sample, o.sample, (size_t)S * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     log.mark("row order: %d pivots, nearest pivot of every row", P1);
-    float tau = __builtin_inff();          // 4 x median positive squared distance to the pivot
+    // Scale of a well-placed cell: 4 x the median positive squared distance to the pivot.  (When the
+    // clusters are much smaller than the pivot spacing the median is an inter-cluster distance and no
+    // row counts as far; such data cannot be pruned at tile granularity anyway, and the connection
+    // sweeps then fall back to multiplying every tile, see run_slhc.)
+    float tau = __builtin_inff();
     {
         std::vector<float> v;
         for (int i = 0; i < S; ++i) if (h_sample[i] > 0.f && std::isfinite(h_sample[i])) v.push_back(h_sample[i]);
@@ -849,6 +853,12 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     for (int64_t t = 1; t < N; t *= 2) ++max_rounds;
     double ms_connect = 0.0;
     bool first_connect = true;
+    // cleared when pruning stops paying: at once when the k-NN sweep already had to multiply more
+    // than a quarter of all tile pairs (the data has no structure at the scale of a tile), else by
+    // the per-round test below
+    const unsigned long long tiles_1d = (unsigned long long)((N + 127) / 128);
+    bool connect_pruned = (unsigned long long)st.knn_tile_steps * 4 <= tiles_1d * tiles_1d;
+    unsigned long long conn_steps_seen = 0;
     st.components_after_knn = 1;
     while (edges < N - 1) {
         if (st.boruvka_rounds >= max_rounds) { set_err("no single component after %d rounds", max_rounds); return SLHC_INTERNAL; }
@@ -872,7 +882,8 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
             p.survivors = kws.counters + 1;
             p.tiles_done = kws.counters + 3;
             const int32_t* qrows = ws.qlist;
-            if (pruned) {
+            const bool round_pruned = pruned && connect_pruned;
+            if (round_pruned) {
                 // colours in the reordered copy, one colour summary per tile, and the queried rows
                 // marked in place so that query panels coincide with candidate tiles
                 const OrderWs& o = kws.order;
@@ -905,10 +916,21 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
             HIP_TRY(hipEventRecord(ev_conn.a, s));
             HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
             HIP_TRY(hipEventRecord(ev_conn.b, s));
-            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, pruned ? ws.vals_a : nullptr, s));
+            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, round_pruned ? ws.vals_a : nullptr, s));
+            if (round_pruned) HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
             HIP_TRY(hipStreamSynchronize(s));
             st.ms_connect_kernels += ev_conn.ms();
             ms_connect += now_ms() - tc0;
+            if (round_pruned) {
+                // Did skipping pay?  A pruned tile step costs more than an every-tile one (queries
+                // stay aligned with tiles, so panels are partly empty, and the surviving tiles are
+                // the dense ones); when a large round still multiplied more than a third of what the
+                // every-tile sweep would, the remaining rounds run without pruning.
+                const unsigned long long steps = h_surv[3] - conn_steps_seen;
+                conn_steps_seen = h_surv[3];
+                const unsigned long long every = (unsigned long long)((nq + 127) / 128) * (unsigned long long)((N + 127) / 128);
+                if ((int64_t)nq * 8 >= N && steps * 3 > every) connect_pruned = false;
+            }
             if (log.on) {
                 HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
                 HIP_TRY(hipStreamSynchronize(s));
