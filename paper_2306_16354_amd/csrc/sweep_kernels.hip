@@ -391,6 +391,122 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
     return (unsigned int)qcount;
 }
 
+// Deferred form of the rare path, for the sweeps that multiply every tile.  After the first tiles of
+// a panel a step leaves one or two surviving pairs per wavefront, and resolving them at once costs a
+// full dependent chain (queue, two row loads from L2, reduction, insert) in every step.  Here a step
+// only compacts a small number of survivors into a queue that lives across steps (its length sits in
+// LDS, one word per wavefront); the queue is resolved when it holds DEFER_MIN pairs, eight pairs per
+// pass, and at the end of the panel.  Thresholds are then a few steps stale, which is safe: a stale
+// threshold is larger and only lets more pairs through.  Entries are 32-bit (query lane << 27 |
+// candidate row) so that they outlive the step they were found in (candidate sets of 2^27 rows and
+// more are not deferred); the queue shares the LDS bytes of the immediate path's queue, so the
+// immediate path (blocks with many survivors) flushes it first.
+constexpr int QCAP_WIDE = QCAP / 2;
+constexpr int DEFER_MIN = 8;           // measured best at N = 1M, d = 128, k = 32 (4, 16, 32, 64 are slower)
+constexpr int DEFER_BLOCK_MAX = 32;
+constexpr int DEFER_ROW_BITS = 27;
+
+template <int KL>
+__device__ inline int* deferred_count(const SweepLds<KL>& L, int wave)
+{
+    return reinterpret_cast<int*>(L.wmax + 12) + wave;
+}
+
+// Resolves the first `qcount` entries of the deferred queue and empties it.
+template <int KL, bool VEC4>
+__device__ __attribute__((noinline)) void resolve_deferred(int qcount, const float* __restrict__ Xq,
+                                                           const float* __restrict__ Xc,
+                                                           const int32_t* __restrict__ c_id, int d, int k)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const unsigned int* myq = reinterpret_cast<const unsigned int*>(L.queues + wave * QCAP);
+    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
+    __builtin_amdgcn_wave_barrier();
+    const int grp = lane >> 3, g8 = lane & 7;
+    for (int s = 0; s < qcount; s += 8) {
+        const int e = s + grp;
+        const bool valid = e < qcount;
+        const unsigned int ent = valid ? myq[e] : 0u;
+        const int ql = (int)(ent >> DEFER_ROW_BITS);
+        const int cg = (int)(ent & ((1u << DEFER_ROW_BITS) - 1u));
+        const int qrow = L.qid[wave * 32 + ql];
+        const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
+        const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
+        const int cid = (c_id && valid) ? c_id[cg] : cg;
+        const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
+        const unsigned long long key = make_key(dist, cid);
+        if constexpr (KL == 1) {
+            if (valid && g8 == 0) atomicMin(&mylists[ql], key);
+            __builtin_amdgcn_wave_barrier();
+            if (valid && g8 == 0)
+                L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
+            continue;
+        }
+        const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
+        unsigned long long todo = __ballot(accept);
+        while (todo) {
+            const int src = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const unsigned int klo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)key, src);
+            const unsigned int khi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(key >> 32), src);
+            const int qlg = __builtin_amdgcn_readlane(ql, src);
+            wave_list_insert(mylists + (size_t)qlg * KL, k, ((unsigned long long)khi << 32) | klo,
+                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) *deferred_count(L, wave) = 0;
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Appends the passing pairs of one 32x32 block to the deferred queue and returns its new length,
+// or -1 (nothing written) when the block has more than DEFER_BLOCK_MAX of them, the queue is full or
+// a candidate row does not fit an entry.
+template <int KL, bool MASKED>
+__device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound, int tag, int col0, int colbuf, int N)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int* ccol = L.ccol + colbuf * BN;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    const int lhalf = lane >> 5;
+    unsigned int* myq = reinterpret_cast<unsigned int*>(L.queues + wave * QCAP);
+    int* cnt = deferred_count(L, wave);
+    int qcount = *cnt;
+    const bool real_query = L.qid[wave * 32 + l32] >= 0;
+    unsigned long long masks[16];
+    int total = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+        const int cg = col0 + cl;
+        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
+        if (MASKED) pred = pred && (ccol[cl] != tag);
+        else pred = pred && (cg != tag);
+        masks[r] = __ballot(pred);
+        total += __popcll(masks[r]);
+    }
+    if (total > DEFER_BLOCK_MAX || qcount + total > QCAP_WIDE || N > (1 << DEFER_ROW_BITS)) return -1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const unsigned long long mask = masks[r];
+        if (mask) {
+            const int cg = col0 + b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+            if ((mask >> lane) & 1ull) myq[qcount + pre] = ((unsigned int)l32 << DEFER_ROW_BITS) | (unsigned int)cg;
+            qcount += __popcll(mask);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) *cnt = qcount;
+    __builtin_amdgcn_wave_barrier();
+    return qcount;
+}
+
 // Tile epilogue after the hot filter flagged blocks `flagged` of this wavefront: all blocks go
 // through one queue, so the exact re-evaluation runs once per tile step.  Expands at its call site
 // with static block indices (a dynamic index into the accumulators would spill them).
@@ -724,6 +840,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
         for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
         if (tid < 8) L.wmax[tid] = __builtin_inff();
+        if (tid < 4) *deferred_count(L, tid) = 0;
         __syncthreads();
         // a panel without a single query has nothing to do (every wavefront reads the same qid)
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
@@ -1004,10 +1121,25 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     SLHC_SELECT_TILE(KL, MASKED, true);
                     if (shared_thr) bound = bounds[my_q_local];         // this query's own bound again
                 } else {
-                    if (flagged & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                    if (flagged & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                    if (flagged & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                    if (flagged & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                    // few survivors: queue them for a later batch; many (the first tiles of a
+                    // panel): resolve what waits, then this block, at once
+#define SLHC_DEFER_OR_SELECT(B_)                                                                            \
+    if (flagged & (1u << B_)) {                                                                             \
+        if (defer_block<KL, MASKED>(acc[B_], B_, bound, my_tag, col0, tpar, N) < 0) {                       \
+            const int waiting_ = *deferred_count(L, wave);                                                  \
+            if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); } \
+            survivors += select_block<KL, MASKED, true>(acc[B_], B_, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k); \
+        }                                                                                                   \
+    }
+                    SLHC_DEFER_OR_SELECT(0)
+                    SLHC_DEFER_OR_SELECT(1)
+                    SLHC_DEFER_OR_SELECT(2)
+                    SLHC_DEFER_OR_SELECT(3)
+#undef SLHC_DEFER_OR_SELECT
+                    {
+                        const int waiting_ = *deferred_count(L, wave);
+                        if (waiting_ >= DEFER_MIN) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
+                    }
                     bound = bounds[my_q_local];
                 }
                 if (prune) {
@@ -1036,6 +1168,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
 
         // ---- panel epilogue: lists are already ascending; write them out ----
+        if (!PRUNE) {
+            const int waiting_ = *deferred_count(L, wave);
+            if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
+        }
         __builtin_amdgcn_wave_barrier();
         for (int ql = 0; ql < 32; ++ql) {
             const int row = qid[wave * 32 + ql];
