@@ -458,6 +458,9 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
 #endif
     } else {
         p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
+#ifdef SLHC_PHASE_TIMERS
+        p.phase_cycles = ws.counters + 16;
+#endif
     }
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));

@@ -264,6 +264,59 @@ __device__ __attribute__((noinline)) int compact_block(v16f t, int b, float boun
     return qcount;
 }
 
+// group_list_insert: inserts the keys held by the lanes of `todo` (one bit per lane that holds an
+// accepted key and its query lane `ql`) into their queries' lists, 64/KL lists at a time: lane group
+// g = lane / KL serves the g-th pending key, one lane per list entry, so that a pass costs one LDS read,
+// one ballot and the shifted write whatever the number of lists.  Two pending keys of one query go to
+// different passes.  Per list this does what wave_list_insert does, bound refresh included.
+template <int KL>
+__device__ inline void group_list_insert(unsigned long long todo, unsigned long long key, int ql,
+                                         unsigned long long* mylists, int k, const float* hqs,
+                                         float* bounds, int lane)
+{
+    constexpr int NG = 64 / KL;
+    const int g = lane / KL, l = lane % KL;
+    while (todo) {
+        unsigned long long rest = todo;
+        int picked_q[NG];
+        int mysrc = -1;
+#pragma unroll
+        for (int j = 0; j < NG; ++j) {
+            picked_q[j] = -1;
+            if (rest) {
+                const int src = __builtin_ctzll(rest);
+                rest &= rest - 1;
+                const int q = __builtin_amdgcn_readlane(ql, src);
+                bool clash = false;
+#pragma unroll
+                for (int i = 0; i < j; ++i) clash = clash || (picked_q[i] == q);
+                if (!clash) {
+                    picked_q[j] = q;
+                    todo &= ~(1ull << src);
+                    if (g == j) mysrc = src;
+                }
+            }
+        }
+        const bool act = mysrc >= 0;
+        const int from = act ? mysrc : lane;
+        const unsigned int klo = (unsigned int)__shfl((int)(unsigned int)key, from);
+        const unsigned int khi = (unsigned int)__shfl((int)(unsigned int)(key >> 32), from);
+        const int myq = __shfl(ql, from);
+        const unsigned long long mykey = ((unsigned long long)khi << 32) | klo;
+        unsigned long long* lst = mylists + (size_t)myq * KL;
+        const unsigned long long old = (act && l < k) ? lst[l] : ~0ull;
+        const bool less = act && (l < k) && (old < mykey);
+        const unsigned long long m = __ballot(less);
+        const unsigned long long gm = (KL == 64) ? m : ((m >> (g * KL)) & ((1ull << (KL & 63)) - 1ull));
+        const int pos = __popcll(gm);
+        const bool ins = act && pos < k;                       // the key beats the k-th entry
+        if (ins && l >= pos && l < k - 1) lst[l + 1] = old;
+        if (ins && l == pos) lst[pos] = mykey;
+        if (ins && pos == k - 1 && l == k - 1) bounds[myq] = hqs[myq] - 0.5f * __uint_as_float(khi);
+        if (ins && pos < k - 1 && l == k - 2) bounds[myq] = hqs[myq] - 0.5f * __uint_as_float((unsigned int)(old >> 32));
+    }
+}
+
 // resolve_queue: re-evaluates every queued pair exactly (eight pairs per pass, 8 lanes each),
 // drops those that do not beat their query's current k-th entry, inserts the rest into the query
 // lists and refreshes the bounds.
@@ -304,16 +357,7 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
             continue;
         }
         const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
-        unsigned long long todo = __ballot(accept);
-        while (todo) {
-            const int src = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const unsigned int klo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)key, src);
-            const unsigned int khi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(key >> 32), src);
-            const int qlg = __builtin_amdgcn_readlane(ql, src);
-            wave_list_insert(mylists + (size_t)qlg * KL, k, ((unsigned long long)khi << 32) | klo,
-                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
-        }
+        if constexpr (KL > 1) group_list_insert<KL>(__ballot(accept), key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -445,16 +489,7 @@ __device__ __attribute__((noinline)) void resolve_deferred(int qcount, const flo
             continue;
         }
         const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
-        unsigned long long todo = __ballot(accept);
-        while (todo) {
-            const int src = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const unsigned int klo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)key, src);
-            const unsigned int khi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(key >> 32), src);
-            const int qlg = __builtin_amdgcn_readlane(ql, src);
-            wave_list_insert(mylists + (size_t)qlg * KL, k, ((unsigned long long)khi << 32) | klo,
-                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
-        }
+        if constexpr (KL > 1) group_list_insert<KL>(__ballot(accept), key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
     }
     __builtin_amdgcn_wave_barrier();
     if (lane == 0) *deferred_count(L, wave) = 0;
@@ -462,8 +497,11 @@ __device__ __attribute__((noinline)) void resolve_deferred(int qcount, const flo
 }
 
 // Appends the passing pairs of one 32x32 block to the deferred queue and returns its new length,
-// or -1 (nothing written) when the block has more than DEFER_BLOCK_MAX of them, the queue is full or
-// a candidate row does not fit an entry.
+// or -1 when the block has more than DEFER_BLOCK_MAX of them, the queue is full or a candidate row does
+// not fit an entry (what was written then lies beyond the queue's length and is ignored).  A flagged
+// block holds one or two such pairs in one or two of its 16 accumulator rows, so a row is first tested
+// with a single compare and a wavefront-uniform branch; rows beyond N need no test of their own here:
+// the pair test includes cg < N.
 template <int KL, bool MASKED>
 __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound, int tag, int col0, int colbuf, int N)
 {
@@ -475,35 +513,33 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
     const int lhalf = lane >> 5;
     unsigned int* myq = reinterpret_cast<unsigned int*>(L.queues + wave * QCAP);
     int* cnt = deferred_count(L, wave);
-    int qcount = *cnt;
+    const int qcount0 = *cnt;
     const bool real_query = L.qid[wave * 32 + l32] >= 0;
-    unsigned long long masks[16];
-    int total = 0;
+    if (N > (1 << DEFER_ROW_BITS)) return -1;
+    const int limit = (qcount0 + DEFER_BLOCK_MAX < QCAP_WIDE) ? qcount0 + DEFER_BLOCK_MAX : QCAP_WIDE;
+    int qcount = qcount0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
+        if (__ballot(t[r] >= bound) == 0ull) continue;
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
         const int cg = col0 + cl;
-        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
+        bool pred = real_query && (t[r] >= bound) && (cg < N);
         if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
-        masks[r] = __ballot(pred);
-        total += __popcll(masks[r]);
+        const unsigned long long mask = __ballot(pred);
+        if (mask == 0ull) continue;
+        const int more = __popcll(mask);
+        if (qcount + more > limit) return -1;
+        const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+        if (pred) myq[qcount + pre] = ((unsigned int)l32 << DEFER_ROW_BITS) | (unsigned int)cg;
+        qcount += more;
     }
-    if (total > DEFER_BLOCK_MAX || qcount + total > QCAP_WIDE || N > (1 << DEFER_ROW_BITS)) return -1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const unsigned long long mask = masks[r];
-        if (mask) {
-            const int cg = col0 + b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
-                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
-            if ((mask >> lane) & 1ull) myq[qcount + pre] = ((unsigned int)l32 << DEFER_ROW_BITS) | (unsigned int)cg;
-            qcount += __popcll(mask);
-        }
+    if (qcount != qcount0) {
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) *cnt = qcount;
+        __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_wave_barrier();
-    if (lane == 0) *cnt = qcount;
-    __builtin_amdgcn_wave_barrier();
     return qcount;
 }
 
@@ -1115,33 +1151,37 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
             PHASE_MARK(5);
             if (__builtin_expect(flagged != 0, 0)) {
+                // the rare path is a chain of short dependent steps: let it issue ahead of the
+                // multiplies of the other workgroup's wavefront on this SIMD (measured: 0.8 %)
+                __builtin_amdgcn_s_setprio(1);
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
                 if (PRUNE) {
                     const int colbuf_ = tpar;
                     SLHC_SELECT_TILE(KL, MASKED, true);
                     if (shared_thr) bound = bounds[my_q_local];         // this query's own bound again
                 } else {
-                    // few survivors: queue them for a later batch; many (the first tiles of a
-                    // panel): resolve what waits, then this block, at once
-#define SLHC_DEFER_OR_SELECT(B_)                                                                            \
-    if (flagged & (1u << B_)) {                                                                             \
-        if (defer_block<KL, MASKED>(acc[B_], B_, bound, my_tag, col0, tpar, N) < 0) {                       \
-            const int waiting_ = *deferred_count(L, wave);                                                  \
-            if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); } \
-            survivors += select_block<KL, MASKED, true>(acc[B_], B_, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k); \
-        }                                                                                                   \
-    }
-                    SLHC_DEFER_OR_SELECT(0)
-                    SLHC_DEFER_OR_SELECT(1)
-                    SLHC_DEFER_OR_SELECT(2)
-                    SLHC_DEFER_OR_SELECT(3)
-#undef SLHC_DEFER_OR_SELECT
-                    {
-                        const int waiting_ = *deferred_count(L, wave);
-                        if (waiting_ >= DEFER_MIN) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
+                    // few survivors: queue them for a later batch.  Blocks with many (the first tiles
+                    // of a panel) are resolved at once afterwards, behind what already waits; their
+                    // calls sit apart so that the common sequence keeps the accumulators in registers.
+                    unsigned int heavy = 0;
+                    if ((flagged & 1u) && defer_block<KL, MASKED>(acc[0], 0, bound, my_tag, col0, tpar, N) < 0) heavy |= 1u;
+                    if ((flagged & 2u) && defer_block<KL, MASKED>(acc[1], 1, bound, my_tag, col0, tpar, N) < 0) heavy |= 2u;
+                    if ((flagged & 4u) && defer_block<KL, MASKED>(acc[2], 2, bound, my_tag, col0, tpar, N) < 0) heavy |= 4u;
+                    if ((flagged & 8u) && defer_block<KL, MASKED>(acc[3], 3, bound, my_tag, col0, tpar, N) < 0) heavy |= 8u;
+                    PHASE_MARK(1);
+                    int waiting_ = *deferred_count(L, wave);
+                    if (__builtin_expect(heavy != 0, 0)) {
+                        if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
+                        waiting_ = 0;
+                        if (heavy & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                        if (heavy & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                        if (heavy & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                        if (heavy & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
                     }
+                    if (waiting_ >= DEFER_MIN) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
                     bound = bounds[my_q_local];
                 }
+                __builtin_amdgcn_s_setprio(0);
                 if (prune) {
                     // largest threshold of this wavefront's 32 queries: thr = 2 (h_q - bound)
                     float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
