@@ -467,31 +467,38 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     return SLHC_OK;
 }
 
-// Linkage arrays from weight-sorted tree edges (paper Sec. 3.3.1): a union-find over the
-// 2N-1 dendrogram nodes in which the representative of a set is the node created by its last
-// merge; merge i creates node N+i.
+// Linkage arrays from weight-sorted tree edges (paper Sec. 3.3.1): a union-find over the N points
+// (union by size, path halving) in which every set carries the dendrogram node created by its last
+// merge; merge i creates node N+i.  The edges arrive in weight order, so their end points are
+// scattered over the whole array: one 16-byte record per point keeps a find step to one cache
+// line, and the records of the edges a few iterations ahead are prefetched.
 void build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* children, int32_t* sizes)
 {
-    const int64_t total = 2 * N - 1;
-    std::vector<int32_t> up_node((size_t)total);
-    std::vector<int32_t> count((size_t)total, 1);
-    for (int64_t i = 0; i < total; ++i) up_node[(size_t)i] = (int32_t)i;
-    auto top = [&](int32_t a) {
-        while (up_node[(size_t)a] != a) {                       // path halving
-            up_node[(size_t)a] = up_node[(size_t)up_node[(size_t)a]];
-            a = up_node[(size_t)a];
+    struct PointSet { int32_t up, count, node, unused; };
+    std::vector<PointSet> set((size_t)N);
+    for (int64_t v = 0; v < N; ++v) set[(size_t)v] = PointSet{(int32_t)v, 1, (int32_t)v, 0};
+    auto root = [&](int32_t a) {
+        while (set[(size_t)a].up != a) {
+            set[(size_t)a].up = set[(size_t)set[(size_t)a].up].up;
+            a = set[(size_t)a].up;
         }
         return a;
     };
+    constexpr int64_t AHEAD = 8;
     for (int64_t i = 0; i < N - 1; ++i) {
-        const int32_t a = top(lo[i]), b = top(hi[i]);
-        const int32_t node = (int32_t)(N + i);
+        if (i + AHEAD < N - 1) {
+            __builtin_prefetch(&set[(size_t)lo[i + AHEAD]]);
+            __builtin_prefetch(&set[(size_t)hi[i + AHEAD]]);
+        }
+        int32_t ra = root(lo[i]), rb = root(hi[i]);
+        const int32_t a = set[(size_t)ra].node, b = set[(size_t)rb].node;
         children[2 * i] = a < b ? a : b;
         children[2 * i + 1] = a < b ? b : a;
-        up_node[(size_t)a] = node;
-        up_node[(size_t)b] = node;
-        count[(size_t)node] = count[(size_t)a] + count[(size_t)b];
-        sizes[i] = count[(size_t)node];
+        if (set[(size_t)ra].count < set[(size_t)rb].count) std::swap(ra, rb);
+        set[(size_t)rb].up = ra;
+        set[(size_t)ra].count += set[(size_t)rb].count;
+        set[(size_t)ra].node = (int32_t)(N + i);
+        sizes[i] = set[(size_t)ra].count;
     }
 }
 
