@@ -435,6 +435,54 @@ __device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, fl
     return (unsigned int)qcount;
 }
 
+// Seeding of 1-NN sweeps.  In the first tile of a panel no query has a threshold yet, so all of its
+// 128 x 32 pairs per wavefront would pass the filter and be re-evaluated one after the other, which
+// costs as much as dozens of later tiles when a panel only multiplies a few hundred of them (row
+// order, pruned connection sweeps).  The accumulators already rank the candidates: every lane takes
+// the admissible candidate with the largest accumulator among the 64 it holds (seed_block, one call
+// per block), those 64 pairs per wavefront are evaluated exactly and recorded (seed_resolve), and the
+// tile then goes through the filter with the thresholds they leave.  The seeds are ordinary exact
+// candidates, so the result of the sweep does not depend on them.
+struct SeedPick { float v; int cl; };
+
+template <int KL, bool MASKED>
+__device__ __attribute__((noinline)) SeedPick seed_block(v16f t, int b, SeedPick cur, int tag, int col0,
+                                                         int colbuf, int N)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int* ccol = L.ccol + colbuf * BN;
+    const int lhalf = (threadIdx.x & 63) >> 5;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+        const int cg = col0 + cl;
+        bool ok = cg < N;
+        if (MASKED) ok = ok && (ccol[cl] != tag);
+        else ok = ok && (cg != tag);
+        if (ok && t[r] > cur.v) { cur.v = t[r]; cur.cl = cl; }
+    }
+    return cur;
+}
+
+template <int KL, bool VEC4>
+__device__ __attribute__((noinline)) void seed_resolve(SeedPick pick, int col0, const float* __restrict__ Xq,
+                                                       const float* __restrict__ Xc,
+                                                       const int32_t* __restrict__ c_id, int d, int k)
+{
+    const SweepLds<KL> L(sweep_smem);
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int l32 = lane & 31;
+    unsigned short* myq = L.queues + wave * QCAP;
+    const bool has = pick.cl >= 0 && L.qid[wave * 32 + l32] >= 0;
+    const unsigned long long mask = __ballot(has);
+    if (mask == 0ull) return;
+    const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                      __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+    if (has) myq[pre] = (unsigned short)((l32 << 8) | pick.cl);
+    resolve_queue<KL, VEC4>(__popcll(mask), col0, Xq, Xc, c_id, d, k);
+}
+
 // Deferred form of the rare path, for the sweeps that multiply every tile.  After the first tiles of
 // a panel a step leaves one or two surviving pairs per wavefront, and resolving them at once costs a
 // full dependent chain (queue, two row loads from L2, reduction, insert) in every step.  Here a step
@@ -736,6 +784,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                 }
             }
 
+            // ---- first tile of a 1-NN work item: seed the thresholds (see seed_block) ----
+            if (k == 1 && tile == t_begin) {
+                const int seed_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
+                SeedPick pick{-__builtin_inff(), -1};
+                pick = seed_block<KL, MASKED>(acc[0], 0, pick, seed_tag, col0, 0, N);
+                pick = seed_block<KL, MASKED>(acc[1], 1, pick, seed_tag, col0, 0, N);
+                pick = seed_block<KL, MASKED>(acc[2], 2, pick, seed_tag, col0, 0, N);
+                pick = seed_block<KL, MASKED>(acc[3], 3, pick, seed_tag, col0, 0, N);
+                seed_resolve<KL, VEC4>(pick, col0, Xq, Xc, p.c_id, d, k);
+                bound = bounds[my_q_local];
+            }
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
             unsigned int flagged = 0;
 #pragma unroll
@@ -1126,6 +1185,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 }
             }
 
+            // ---- first tile of a 1-NN panel: seed the thresholds (see seed_block) ----
+            if (k == 1 && step == 0) {
+                const int seed_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
+                SeedPick pick{-__builtin_inff(), -1};
+                pick = seed_block<KL, MASKED>(acc[0], 0, pick, seed_tag, col0, tpar, N);
+                pick = seed_block<KL, MASKED>(acc[1], 1, pick, seed_tag, col0, tpar, N);
+                pick = seed_block<KL, MASKED>(acc[2], 2, pick, seed_tag, col0, tpar, N);
+                pick = seed_block<KL, MASKED>(acc[3], 3, pick, seed_tag, col0, tpar, N);
+                seed_resolve<KL, true>(pick, col0, Xq, Xc, p.c_id, d, k);
+                bound = bounds[my_q_local];
+            }
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
             PHASE_MARK(3);
             const float own_bound = bound;
