@@ -18,7 +18,7 @@
 //     x_c.x_q - h_c and the filter "expanded distance <= threshold (+ rounding slack)" is the
 //     single compare  acc >= h_q - threshold/2;
 //   * pairs that pass are stream-compacted into a per-wavefront LDS queue (the paper's
-//     compaction step, Sec. 3.1.1), re-evaluated exactly as sum_t (x_qt - x_ct)^2 by 16-lane
+//     compaction step, Sec. 3.1.1), re-evaluated exactly as sum_t (x_qt - x_ct)^2 by 8-lane
 //     groups, and inserted into the query's sorted list in LDS (one list entry per lane).
 //   Each wavefront owns its 32 queries outright (lists, thresholds, queue), so selection needs
 //   no synchronisation between wavefronts and no mutex in global memory (the paper's
@@ -46,47 +46,12 @@ __host__ __device__ inline size_t sweep_lds_bytes(int KL)
                     BM /*hq*/ + 8 /*wmax*/ + 8 /*next panel*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
 }
 
-// sum_t (a_t - b_t)^2 over d features by a group of 16 adjacent lanes; every lane of the group
-// returns the total.  Lane g of the group owns features 4g..4g+3 of every 64-wide slab, adds them
-// in ascending t with fused multiply-adds, and the 16 partial sums are combined by an xor
-// butterfly.  (a-b)^2 == (b-a)^2 exactly, so the result is symmetric in its arguments bit for bit.
-template <bool VEC4>
-__device__ inline float group16_sqdist(const float* __restrict__ a, const float* __restrict__ b,
-                                       int d, int g, bool active)
-{
-    float s = 0.f;
-    if (active) {
-        if (VEC4) {
-            for (int t = 4 * g; t < d; t += 64) {
-                const v4f va = *reinterpret_cast<const v4f*>(a + t);
-                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
-                float e;
-                e = va[0] - vb[0]; s = __builtin_fmaf(e, e, s);
-                e = va[1] - vb[1]; s = __builtin_fmaf(e, e, s);
-                e = va[2] - vb[2]; s = __builtin_fmaf(e, e, s);
-                e = va[3] - vb[3]; s = __builtin_fmaf(e, e, s);
-            }
-        } else {
-            for (int t0 = 4 * g; t0 < d; t0 += 64) {
-                const int te = (t0 + 4 < d) ? t0 + 4 : d;
-                for (int t = t0; t < te; ++t) {
-                    const float e = a[t] - b[t];
-                    s = __builtin_fmaf(e, e, s);
-                }
-            }
-        }
-    }
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    s += __shfl_xor(s, 4);
-    s += __shfl_xor(s, 8);
-    return s;
-}
-
-// The same sum, bit for bit, computed by a group of 8 adjacent lanes: lane g plays lanes g and g+8
-// of the 16-lane scheme with two accumulators, each set of eight partial sums goes through the
-// xor butterfly (1, 2, 4), and the two totals are added last - exactly the additions the 16-lane
-// butterfly performs.  Twice as many pairs per wavefront pass, and all loads are issued up front.
+// sum_t (a_t - b_t)^2 over d features by a group of 8 adjacent lanes; every lane of the group returns
+// the total.  The features are cut into 64-wide slabs; lane g adds features 4g..4g+3 of every slab
+// into one accumulator and features 4(g+8)..4(g+8)+3 into a second one, in ascending t with fused
+// multiply-adds; each set of eight partial sums goes through an xor butterfly (1, 2, 4) and the two
+// totals are added last.  (a-b)^2 == (b-a)^2 exactly, so the result is symmetric in its arguments
+// bit for bit, and every code path that re-evaluates a pair uses this one order of additions.
 template <bool VEC4>
 __device__ inline float group8_sqdist(const float* __restrict__ a, const float* __restrict__ b,
                                       int d, int g, bool active)
@@ -170,29 +135,6 @@ __device__ inline unsigned long long make_key(float dist, int idx)
     return ((unsigned long long)__float_as_uint(dist) << 32) | (unsigned int)idx;
 }
 
-// Insert `key` into the ascending list of `k` 64-bit keys at `list` (LDS), dropping the last
-// entry; executed by a whole wavefront, lane l holding entry l.  Returns without change when the
-// key does not precede the last entry.  On change, the query's filter bound is refreshed:
-// bound = h_q - worst/2.
-__device__ inline void wave_list_insert(unsigned long long* list, int k, unsigned long long key,
-                                        float hq, float* bound_slot, int lane)
-{
-    const unsigned long long worst = list[k - 1];
-    if (key >= worst) return;
-    const unsigned long long old = (lane < k) ? list[lane] : ~0ull;
-    const bool less = (lane < k) && (old < key);
-    const int pos = __popcll(__ballot(less));
-    if (lane >= pos && lane < k - 1) list[lane + 1] = old;
-    if (lane == pos) list[pos] = key;
-    unsigned int hi;
-    if (pos == k - 1) {
-        hi = (unsigned int)(key >> 32);
-    } else {
-        hi = (unsigned int)__builtin_amdgcn_readlane((int)(old >> 32), k - 2);
-    }
-    if (lane == 0) *bound_slot = hq - 0.5f * __uint_as_float(hi);
-}
-
 // LDS layout of a sweep workgroup (dynamic shared memory).
 template <int KL>
 struct SweepLds {
@@ -268,7 +210,10 @@ __device__ __attribute__((noinline)) int compact_block(v16f t, int b, float boun
 // accepted key and its query lane `ql`) into their queries' lists, 64/KL lists at a time: lane group
 // g = lane / KL serves the g-th pending key, one lane per list entry, so that a pass costs one LDS read,
 // one ballot and the shifted write whatever the number of lists.  Two pending keys of one query go to
-// different passes.  Per list this does what wave_list_insert does, bound refresh included.
+// different passes.  Per list: the key goes in front of the first entry that is not smaller, the
+// entries behind it move down by one and the last one drops out; nothing changes when the key does
+// not precede the last entry.  On change the query's filter bound is refreshed from the new k-th
+// entry: bound = h_q - worst/2.
 template <int KL>
 __device__ inline void group_list_insert(unsigned long long todo, unsigned long long key, int ql,
                                          unsigned long long* mylists, int k, const float* hqs,
@@ -345,11 +290,11 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
         const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
         const unsigned long long key = make_key(dist, cid);
         // a stale k-th entry is only larger than the current one, so this test never drops a
-        // pair that belongs in the list; wave_list_insert tests again
+        // pair that belongs in the list; group_list_insert tests again
         if constexpr (KL == 1) {
             // k = 1: a list is one key, so the eight group leaders update their queries at once
             // (64-bit LDS minimum; two pairs of one query in the same pass are ordered by it) and
-            // then refresh the bounds from what the lists hold, exactly as wave_list_insert would
+            // then refresh the bounds from what the lists hold, as group_list_insert would
             if (valid && g8 == 0) atomicMin(&mylists[ql], key);
             __builtin_amdgcn_wave_barrier();
             if (valid && g8 == 0)
@@ -360,79 +305,6 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
         if constexpr (KL > 1) group_list_insert<KL>(__ballot(accept), key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
     }
     __builtin_amdgcn_wave_barrier();
-}
-
-// select_block: compaction and resolution of ONE 32x32 block in a single call (four pairs per
-// pass, 16 lanes each).  Used by the sweeps that multiply every tile: there a flagged block holds
-// one or two pairs, and the shorter call sequence is worth more than the batching above.
-// Returns the number of pairs compacted.
-template <int KL, bool MASKED, bool VEC4>
-__device__ __attribute__((noinline)) unsigned int select_block(v16f t, int b, float bound, int tag,
-                                                               int col0, int colbuf,
-                                                               const float* __restrict__ Xq,
-                                                               const float* __restrict__ Xc,
-                                                               const int32_t* __restrict__ c_id,
-                                                               int N, int d, int k)
-{
-    const SweepLds<KL> L(sweep_smem);
-    const int* ccol = L.ccol + colbuf * BN;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int l32 = lane & 31;
-    const int lhalf = lane >> 5;
-    unsigned short* myq = L.queues + wave * QCAP;
-    unsigned long long* mylists = L.lists + (size_t)wave * 32 * KL;
-    int qcount = 0;
-    const bool real_query = L.qid[wave * 32 + l32] >= 0;    // padding rows of the last panel
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        const int cg = col0 + cl;
-        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
-        if (MASKED) pred = pred && (ccol[cl] != tag);
-        else pred = pred && (cg != tag);
-        const unsigned long long mask = __ballot(pred);
-        if (mask) {
-            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
-                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
-            if (pred) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
-            qcount += __popcll(mask);
-        }
-    }
-    if (qcount == 0) return 0u;
-    __builtin_amdgcn_wave_barrier();
-    const int grp = lane >> 4, g16 = lane & 15;
-    for (int s = 0; s < qcount; s += 4) {
-        const int e = s + grp;
-        const bool valid = e < qcount;
-        const unsigned int ent = valid ? myq[e] : 0u;
-        const int ql = (int)(ent >> 8);
-        const int cg = col0 + (int)(ent & 255u);
-        const int qrow = L.qid[wave * 32 + ql];
-        const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
-        const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
-        const float dist = group16_sqdist<VEC4>(xa, xb, d, g16, valid);
-        const int cid = (c_id && valid) ? c_id[cg] : cg;      // id that orders ties and is reported
-        if constexpr (KL == 1) {
-            // k = 1: one key per query; the four group leaders update their queries at once
-            // (64-bit LDS minimum), then refresh the bounds as wave_list_insert would
-            if (valid && g16 == 0) atomicMin(&mylists[ql], make_key(dist, cid));
-            __builtin_amdgcn_wave_barrier();
-            if (valid && g16 == 0)
-                L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
-            continue;
-        }
-        const int npass = (qcount - s) < 4 ? (qcount - s) : 4;
-        for (int g = 0; g < npass; ++g) {
-            const float dg = __shfl(dist, g * 16);
-            const int qlg = __shfl(ql, g * 16);
-            const int cgg = __shfl(cid, g * 16);
-            wave_list_insert(mylists + (size_t)qlg * KL, k, make_key(dg, cgg),
-                             L.hqs[wave * 32 + qlg], L.bounds + wave * 32 + qlg, lane);
-        }
-    }
-    __builtin_amdgcn_wave_barrier();
-    return (unsigned int)qcount;
 }
 
 // Seeding of 1-NN sweeps.  In the first tile of a panel no query has a threshold yet, so all of its
@@ -491,8 +363,8 @@ __device__ __attribute__((noinline)) void seed_resolve(SeedPick pick, int col0, 
 // pass, and at the end of the panel.  Thresholds are then a few steps stale, which is safe: a stale
 // threshold is larger and only lets more pairs through.  Entries are 32-bit (query lane << 27 |
 // candidate row) so that they outlive the step they were found in (candidate sets of 2^27 rows and
-// more are not deferred); the queue shares the LDS bytes of the immediate path's queue, so the
-// immediate path (blocks with many survivors) flushes it first.
+// more are not deferred); the queue shares the LDS bytes of the 16-bit queue that compact_block and
+// resolve_queue use for blocks with many survivors, so that path resolves the deferred pairs first.
 constexpr int QCAP_WIDE = QCAP / 2;
 constexpr int DEFER_MIN = 8;           // measured best at N = 1M, d = 128, k = 32 (4, 16, 32, 64 are slower)
 constexpr int DEFER_BLOCK_MAX = 32;
@@ -1243,10 +1115,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     if (__builtin_expect(heavy != 0, 0)) {
                         if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
                         waiting_ = 0;
-                        if (heavy & 1u) survivors += select_block<KL, MASKED, true>(acc[0], 0, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                        if (heavy & 2u) survivors += select_block<KL, MASKED, true>(acc[1], 1, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                        if (heavy & 4u) survivors += select_block<KL, MASKED, true>(acc[2], 2, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
-                        if (heavy & 8u) survivors += select_block<KL, MASKED, true>(acc[3], 3, bound, my_tag, col0, tpar, Xq, Xc, p.c_id, N, d, k);
+                        const unsigned int all_flagged = flagged;
+                        flagged = heavy;
+                        const int colbuf_ = tpar;
+                        SLHC_SELECT_TILE(KL, MASKED, true);
+                        flagged = all_flagged;
                     }
                     if (waiting_ >= DEFER_MIN) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
                     bound = bounds[my_q_local];
