@@ -39,6 +39,14 @@ hipError_t forest_classify(const ForestState& f, hipStream_t s);
 // farther than their component's threshold are kept as lower bounds only.
 hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
                                 const float* q_dist, int nq, const uint32_t* thresholds, hipStream_t s);
+// Two-phase connection sweeps (n > 0): rows of `list` in every `stride`-th 128-row panel of the row
+// order (inv[v] = position of row v) go to part_a, the others to part_b; counts[0], counts[1] (zeroed by
+// the caller) receive the part sizes.  forest_still_needed keeps the rows of `list` that the test of
+// forest_classify would still list after best_w has dropped; *count zeroed by the caller.
+hipError_t forest_split_queries(const ForestState& f, const int32_t* list, int n, const int32_t* inv, int stride,
+                                int32_t* part_a, int32_t* part_b, int32_t* counts, hipStream_t s);
+hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n, int32_t* out, int32_t* count,
+                               hipStream_t s);
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
 hipError_t forest_commit(const ForestState& f, hipStream_t s);
 hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step

@@ -182,6 +182,38 @@ __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32
     if (u >= 0) min_into(&f.best_w[c], __float_as_uint(w));
 }
 
+// Two-phase connection sweeps.  k_split_queries sends the listed rows whose 128-row panel in the row
+// order is a sampled one (every `stride`-th panel) to part A and the others to part B.  After the
+// sweep over part A has lowered best_w, k_still_needed keeps of part B only the rows whose bound still
+// does not exceed their component's best exact weight (the test of k_classify again).
+__global__ void __launch_bounds__(TB) k_split_queries(ForestState f, const int32_t* __restrict__ list, int n,
+                                                      const int32_t* __restrict__ inv, int stride,
+                                                      int32_t* __restrict__ part_a, int32_t* __restrict__ part_b,
+                                                      int32_t* __restrict__ counts)
+{
+    const int q = blockIdx.x * TB + threadIdx.x;
+    if (q >= n) return;
+    const int v = list[q];
+    if (!in_range(v, f.N)) { report(f, 10); return; }
+    const bool sampled = ((inv[v] >> 7) % stride) == 0;
+    const int slot = atomicAdd(&counts[sampled ? 0 : 1], 1);
+    if (!in_range(slot, f.N)) { report(f, 10); return; }
+    (sampled ? part_a : part_b)[slot] = v;
+}
+
+__global__ void __launch_bounds__(TB) k_still_needed(ForestState f, const int32_t* __restrict__ list, int n,
+                                                     int32_t* __restrict__ out, int32_t* __restrict__ count)
+{
+    const int q = blockIdx.x * TB + threadIdx.x;
+    if (q >= n) return;
+    const int v = list[q];
+    if (!in_range(v, f.N) || !in_range(f.colour[v], f.N)) { report(f, 11); return; }
+    if (__float_as_uint(f.cand_w[v]) > f.best_w[f.colour[v]]) return;
+    const int slot = atomicAdd(count, 1);
+    if (!in_range(slot, f.N)) { report(f, 11); return; }
+    out[slot] = v;
+}
+
 __global__ void __launch_bounds__(TB) k_select_edges(ForestState f)
 {
     const int v = blockIdx.x * TB + threadIdx.x;
@@ -324,6 +356,18 @@ hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, cons
                                 const float* q_dist, int nq, const uint32_t* thresholds, hipStream_t s)
 {
     LAUNCH1(k_apply_queries, nq, s, f, qrows, q_idx, q_dist, nq, thresholds);
+}
+
+hipError_t forest_split_queries(const ForestState& f, const int32_t* list, int n, const int32_t* inv, int stride,
+                                int32_t* part_a, int32_t* part_b, int32_t* counts, hipStream_t s)
+{
+    LAUNCH1(k_split_queries, n, s, f, list, n, inv, stride, part_a, part_b, counts);
+}
+
+hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n, int32_t* out, int32_t* count,
+                               hipStream_t s)
+{
+    LAUNCH1(k_still_needed, n, s, f, list, n, out, count);
 }
 
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }

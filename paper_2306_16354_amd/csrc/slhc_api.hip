@@ -131,6 +131,16 @@ struct PhaseLog {
 #define SLHC_PRUNE_MIN_ROWS 512      // compile-time knob so that small harnesses can exercise the reordered path
 #endif
 constexpr int64_t PRUNE_MIN_ROWS = SLHC_PRUNE_MIN_ROWS;
+// two-phase pruned connection sweeps (see run_slhc): rows, tile steps per panel of the round before
+#ifndef SLHC_TWO_PHASE_MIN_ROWS
+#define SLHC_TWO_PHASE_MIN_ROWS 262144
+#endif
+constexpr int64_t TWO_PHASE_MIN_ROWS = SLHC_TWO_PHASE_MIN_ROWS;
+#ifndef SLHC_TWO_PHASE_MIN_STEPS
+#define SLHC_TWO_PHASE_MIN_STEPS 128.0
+#endif
+constexpr double TWO_PHASE_MIN_STEPS = SLHC_TWO_PHASE_MIN_STEPS;
+constexpr int TWO_PHASE_STRIDE = 16;
 constexpr int NESTED_K = 8;
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
 int first_level_pivots(int64_t N) { return (int)((N + 63) / 64); }
@@ -869,6 +879,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     const unsigned long long tiles_1d = (unsigned long long)((N + 127) / 128);
     bool connect_pruned = (unsigned long long)st.knn_tile_steps * 4 <= tiles_1d * tiles_1d;
     unsigned long long conn_steps_seen = 0;
+    double prev_steps_per_panel = 0.0;     // tile steps per query panel in the last pruned round
     st.components_after_knn = 1;
     while (edges < N - 1) {
         if (st.boruvka_rounds >= max_rounds) { set_err("no single component after %d rounds", max_rounds); return SLHC_INTERNAL; }
@@ -884,52 +895,94 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
             const double tc0 = now_ms();
             if (first_connect) { st.components_after_knn = (int32_t)(N - edges); first_connect = false; }
             ++st.connect_rounds;
-            st.connect_query_rows += nq;
-            slhc::SweepParams p{};
-            p.d = d; p.k = 1;
-            p.out_idx = ws.q_idx; p.out_dist = ws.q_dist;
-            p.m = nq;
-            p.survivors = kws.counters + 1;
-            p.tiles_done = kws.counters + 3;
-            const int32_t* qrows = ws.qlist;
             const bool round_pruned = pruned && connect_pruned;
             if (round_pruned) {
-                // colours in the reordered copy, one colour summary per tile, and the queried rows
-                // marked in place so that query panels coincide with candidate tiles
+                // colours in the reordered copy and one colour summary per tile
                 const OrderWs& o = kws.order;
                 HIP_TRY(slhc::order_gather_i32(ws.colour, o.perm, o.Ns, (int)N, -1, o.colour_s, s));
                 HIP_TRY(slhc::order_tile_colours(o.colour_s, o.Ns, o.tile_colour, s));
-                HIP_TRY(slhc::order_fill_i32(o.qslot, o.Ns, -1, s));
-                HIP_TRY(slhc::order_scatter_slots(o.inv, ws.qlist, nq, (int)N, o.Ns, o.qslot, s));
-                p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-                p.qcolour = p.ccolour = o.colour_s;
-                p.qslot = o.qslot;
-                p.c_id = o.perm;
-                p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
-                p.tile_colour = o.tile_colour;
-                // thresholds shared by the queries of a component: what the lists already know (a
-                // snapshot, vals_a is free until the edge sort)
-                HIP_TRY(hipMemcpyAsync(ws.vals_a, ws.best_w, (size_t)N * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
-                p.comp_best = ws.vals_a;
-                p.comp_count = (int)N;
-                p.panel_counter = reinterpret_cast<unsigned int*>(kws.counters + 8);
-#ifdef SLHC_PHASE_TIMERS
-                p.phase_cycles = kws.counters + 24;
-#endif
-                hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, p.panel_counter, 1);
-                HIP_TRY(hipGetLastError());
-            } else {
-                p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
-                p.qcolour = p.ccolour = ws.colour;
-                p.rows = ws.qlist;
             }
-            HIP_TRY(hipEventRecord(ev_conn.a, s));
-            HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
-            HIP_TRY(hipEventRecord(ev_conn.b, s));
-            HIP_TRY(slhc::forest_apply_queries(f, qrows, ws.q_idx, ws.q_dist, nq, round_pruned ? ws.vals_a : nullptr, s));
+            float ms_round_kernels = 0.f;
+            // one cross-colour 1-NN sweep for `n` listed rows, and its answers applied to the forest
+            auto sweep_rows = [&](const int32_t* rows, int n) -> int {
+                slhc::SweepParams p{};
+                p.d = d; p.k = 1;
+                p.out_idx = ws.q_idx; p.out_dist = ws.q_dist;
+                p.m = n;
+                p.survivors = kws.counters + 1;
+                p.tiles_done = kws.counters + 3;
+                if (round_pruned) {
+                    // the queried rows marked in place so that query panels coincide with candidate tiles
+                    const OrderWs& o = kws.order;
+                    HIP_TRY(slhc::order_fill_i32(o.qslot, o.Ns, -1, s));
+                    HIP_TRY(slhc::order_scatter_slots(o.inv, rows, n, (int)N, o.Ns, o.qslot, s));
+                    p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
+                    p.qcolour = p.ccolour = o.colour_s;
+                    p.qslot = o.qslot;
+                    p.c_id = o.perm;
+                    p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
+                    p.tile_colour = o.tile_colour;
+                    // thresholds shared by the queries of a component: what the forest already knows (a
+                    // snapshot, vals_a is free until the edge sort)
+                    HIP_TRY(hipMemcpyAsync(ws.vals_a, ws.best_w, (size_t)N * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+                    p.comp_best = ws.vals_a;
+                    p.comp_count = (int)N;
+                    p.panel_counter = reinterpret_cast<unsigned int*>(kws.counters + 8);
+#ifdef SLHC_PHASE_TIMERS
+                    p.phase_cycles = kws.counters + 24;
+#endif
+                    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, p.panel_counter, 1);
+                    HIP_TRY(hipGetLastError());
+                } else {
+                    p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
+                    p.qcolour = p.ccolour = ws.colour;
+                    p.rows = rows;
+                }
+                HIP_TRY(hipEventRecord(ev_conn.a, s));
+                HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
+                HIP_TRY(hipEventRecord(ev_conn.b, s));
+                HIP_TRY(slhc::forest_apply_queries(f, rows, ws.q_idx, ws.q_dist, n, round_pruned ? ws.vals_a : nullptr, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                ms_round_kernels += ev_conn.ms();
+                return SLHC_OK;
+            };
+            int queried = nq;
+            if (round_pruned && (int64_t)nq * 2 >= N && (int64_t)nq >= TWO_PHASE_MIN_ROWS &&
+                prev_steps_per_panel >= TWO_PHASE_MIN_STEPS) {
+                // Two phases, for a round that queries most rows while the thresholds the forest has
+                // are loose (the last pruned round multiplied hundreds of tiles per panel).  The rows
+                // of every 16th panel go first; what they find lowers their components' best
+                // weights, and the other rows (those the lower weights still leave on the list) then
+                // run under thresholds close to the final ones, which lets their panels skip tiles.
+                int32_t* part_a = reinterpret_cast<int32_t*>(ws.keys_a);      // free until the edge sort
+                int32_t* part_b = part_a + N;
+                int32_t* counts = ws.counters + 8;
+                hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(counts), 3);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(slhc::forest_split_queries(f, ws.qlist, nq, kws.order.inv, TWO_PHASE_STRIDE, part_a, part_b, counts, s));
+                HIP_TRY(hipMemcpyAsync(h_cnt + 4, counts, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                const int na = h_cnt[4], nb = h_cnt[5];
+                if (na < 0 || nb < 0 || na + nb != nq) { set_err("query split lost rows (%d + %d of %d)", na, nb, nq); return SLHC_INTERNAL; }
+                if (na > 0) { const int rc = sweep_rows(part_a, na); if (rc != SLHC_OK) return rc; }
+                int nb_left = 0;
+                if (nb > 0) {
+                    HIP_TRY(slhc::forest_still_needed(f, part_b, nb, ws.qlist, counts + 2, s));
+                    HIP_TRY(hipMemcpyAsync(h_cnt + 4, counts + 2, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+                    HIP_TRY(hipStreamSynchronize(s));
+                    nb_left = h_cnt[4];
+                    if (nb_left < 0 || nb_left > nb) { set_err("query re-filter kept %d of %d rows", nb_left, nb); return SLHC_INTERNAL; }
+                    if (nb_left > 0) { const int rc = sweep_rows(ws.qlist, nb_left); if (rc != SLHC_OK) return rc; }
+                }
+                queried = na + nb_left;
+            } else {
+                const int rc = sweep_rows(ws.qlist, nq);
+                if (rc != SLHC_OK) return rc;
+            }
+            st.connect_query_rows += queried;
             if (round_pruned) HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
             HIP_TRY(hipStreamSynchronize(s));
-            st.ms_connect_kernels += ev_conn.ms();
+            st.ms_connect_kernels += ms_round_kernels;
             ms_connect += now_ms() - tc0;
             if (round_pruned) {
                 // Did skipping pay?  A pruned tile step costs more than an every-tile one (queries
@@ -938,14 +991,15 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 // every-tile sweep would, the remaining rounds run without pruning.
                 const unsigned long long steps = h_surv[3] - conn_steps_seen;
                 conn_steps_seen = h_surv[3];
+                prev_steps_per_panel = (double)steps / (double)((queried + 127) / 128 > 0 ? (queried + 127) / 128 : 1);
                 const unsigned long long every = (unsigned long long)((nq + 127) / 128) * (unsigned long long)((N + 127) / 128);
                 if ((int64_t)nq * 8 >= N && steps * 3 > every) connect_pruned = false;
             }
             if (log.on) {
                 HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
                 HIP_TRY(hipStreamSynchronize(s));
-                log.mark("round %d: %d components, %d rows queried, sweep %.2f ms, %llu tile steps so far",
-                         st.boruvka_rounds, (int)(N - edges), nq, ev_conn.ms(), h_surv[3]);
+                log.mark("round %d: %d components, %d of %d listed rows queried, sweeps %.2f ms, %llu tile steps so far",
+                         st.boruvka_rounds, (int)(N - edges), queried, nq, ms_round_kernels, h_surv[3]);
             }
         }
         HIP_TRY(slhc::forest_select_edges(f, s));
