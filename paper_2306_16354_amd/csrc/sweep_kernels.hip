@@ -919,32 +919,38 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
         }
 
-        // Order in which the candidate tiles are visited: the panel's own tile first (self-join in
-        // the same row order), then the tiles after it, wrapping around.  In a spatially coherent
-        // order the nearest rows sit in the neighbouring tiles, so the thresholds tighten early.
-        // `scan` indices count from `base`; every lane of every wavefront evaluates next_scan on
-        // the same data, so its result is workgroup-uniform.
+        // Order in which the candidate tiles are visited.  Every-tile sweeps: 0, 1, 2, ...  Pruned
+        // sweeps start at the tile the panel's own rows sit in (a self-join in the same row order
+        // visits that tile before the scan starts) and move outwards on both sides in turn: c+1, c-1,
+        // c+2, c-2, ... and on along the longer side once the shorter one is used up.  In a spatially
+        // coherent order the nearest rows sit in the neighbouring tiles on either side, so the
+        // thresholds tighten early and the gap test skips more of what follows.
+        // `scan` indices count positions in that order; every lane of every wavefront evaluates
+        // next_scan on the same data, so its result is workgroup-uniform.
         const int own_tile = (PRUNE && !MASKED && p.own_tile_first && panel < ntiles) ? panel : -1;
-        int base = 0;
-        if (own_tile >= 0) base = own_tile + 1;
-        else if (aligned) base = panel < ntiles ? panel : 0;
-        else if (prune && MASKED && qid[0] >= 0) base = qid[0] / BN;
+        int centre = 0;
+        if (own_tile >= 0) centre = own_tile;
+        else if (aligned) centre = panel < ntiles ? panel : 0;
+        else if (prune && MASKED && qid[0] >= 0) centre = qid[0] / BN;
+        if (centre >= ntiles) centre = ntiles - 1;
+        const int with_centre = own_tile >= 0 ? 0 : 1;        // the scan itself begins at the centre tile
         const int nscan = own_tile >= 0 ? ntiles - 1 : ntiles;
-        auto tile_of = [&](int i) -> int {
-            if (i >= nscan) return ntiles;
-            const int t = base + i;
-            return t >= ntiles ? t - ntiles : t;
+        const int side_r = ntiles - 1 - centre, side_l = centre;
+        const int side_min = side_r < side_l ? side_r : side_l;
+        auto scan_tile = [&](int i) -> int {                   // 0 <= i < nscan
+            if (!prune) return i;
+            if (with_centre) { if (i == 0) return centre; --i; }
+            if (i < 2 * side_min) { const int j = (i >> 1) + 1; return (i & 1) ? centre - j : centre + j; }
+            const int r = i - 2 * side_min;
+            return side_r > side_l ? centre + side_min + 1 + r : centre - side_min - 1 - r;
         };
+        auto tile_of = [&](int i) -> int { return i >= nscan ? ntiles : scan_tile(i); };
         auto next_scan = [&](int i, float thr_max) -> int {
             if (!prune) return i;
             while (i < nscan) {
                 const int ii = i + lane;
                 bool need = false;
-                if (ii < nscan) {
-                    int t = base + ii;
-                    t = t >= ntiles ? t - ntiles : t;
-                    need = gap[t] <= thr_max;          // false for NaN
-                }
+                if (ii < nscan) need = gap[scan_tile(ii)] <= thr_max;          // false for NaN
                 const unsigned long long mask = __ballot(need);
                 if (mask) return i + __builtin_ctzll(mask);
                 i += 64;
