@@ -939,7 +939,8 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.rows = rows;
                 }
                 HIP_TRY(hipEventRecord(ev_conn.a, s));
-                HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
+                // keys_a is free until the edge sort (the two-phase split above uses it in pruned rounds only)
+                HIP_TRY(slhc::launch_segmented_cross_1nn(p, round_pruned ? nullptr : ws.keys_a, s));
                 HIP_TRY(hipEventRecord(ev_conn.b, s));
                 HIP_TRY(slhc::forest_apply_queries(f, rows, ws.q_idx, ws.q_dist, n, round_pruned ? ws.vals_a : nullptr, s));
                 HIP_TRY(hipStreamSynchronize(s));

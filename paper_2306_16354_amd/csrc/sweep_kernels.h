@@ -67,5 +67,8 @@ hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);
 // unless asked).  Splits the candidates over the chip when there are few query rows; `keys` is
 // scratch of NQ 64-bit words.
 hipError_t launch_segmented_1nn(const SweepParams& p, unsigned long long* keys, hipStream_t stream);
+// launch_cross_1nn_sweep for a short row list: candidate tiles split into segments when the panels alone
+// would not fill the chip; `keys`: p.m 64-bit words of scratch (may be nullptr: no segmentation).
+hipError_t launch_segmented_cross_1nn(const SweepParams& p, unsigned long long* keys, hipStream_t stream);
 
 }  // namespace slhc

@@ -1324,6 +1324,32 @@ hipError_t launch_segmented_1nn(const SweepParams& p_in, unsigned long long* key
     return hipGetLastError();
 }
 
+// The cross-colour sweep for a short row list (p.m rows, p.rows): with fewer panels than the chip has
+// workgroup slots a panel's pass over all candidate tiles is pure latency, so the tiles are split
+// into segments exactly as in launch_segmented_1nn (streaming kernel, 64-bit minimum per query).
+// Falls back to launch_cross_1nn_sweep when one segment is enough or the sweep is a pruned one.
+hipError_t launch_segmented_cross_1nn(const SweepParams& p_in, unsigned long long* keys, hipStream_t stream)
+{
+    SweepParams p = p_in;
+    const int m = p.m;
+    if (m < 1) return hipSuccess;
+    p.k = 1;
+    p.segments = (p.tile_c || p.qslot || !keys) ? 1 : sweep_segments_for(m, p.NC);
+    if (p.segments <= 1) {
+        p.segments = 0;
+        p.out_key = nullptr;
+        return launch_cross_1nn_sweep(p, stream);
+    }
+    p.out_key = keys;
+    hipLaunchKernelGGL(fill_keys_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, keys, m);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_cross_1nn_sweep(p, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(unpack_keys_kernel, dim3((m + 255) / 256), dim3(256), 0, stream, keys, m, p.out_idx, p.out_dist);
+    return hipGetLastError();
+}
+
 int sweep_grid_limit()
 {
     int cus = 0;
