@@ -1058,7 +1058,9 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     HIP_TRY(hipMemcpyAsync(h_lo, mst_src, E * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(h_hi, mst_dst, E * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    log.mark("dendrogram: %zu edges staged on the host", E);
     build_dendrogram(h_lo, h_hi, N, h_children, h_sizes);
+    log.mark("dendrogram: union-find");
     HIP_TRY(hipMemcpyAsync(children, h_children, E * 8, hipMemcpyHostToDevice, s));
     HIP_TRY(hipMemcpyAsync(sizes, h_sizes, E * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
