@@ -1290,16 +1290,42 @@ __global__ void __launch_bounds__(256) fill_keys_kernel(unsigned long long* __re
     if (i < m) keys[i] = LIST_SENTINEL;
 }
 
-int sweep_segments_for(int m, int NC)
+// Number of candidate segments for a 1-NN sweep of m query rows.  With so few panels that 16 segments
+// each would not fill the workgroup slots: one work item per slot.  Otherwise the S up to 16 (and at
+// least 16 tiles per segment) that minimises the time of the busiest slot, in panel passes:
+// (full rounds of work items + the last, partial round) / S, where a last round that leaves every CU
+// at most one workgroup counts 0.6 (a workgroup alone on its CU is that much faster; measured).
+// Segmented sweeps run in the streaming kernel; where the unsegmented sweep would run in the faster
+// register-resident-query kernel (`fast_unsegmented`) a split has to win by more than that kernel's
+// edge, and any split by 10 %.
+int sweep_segments_for(int m, int NC, bool fast_unsegmented)
 {
     int cus = 0;
     if (device_cus(&cus) != hipSuccess) return 1;
-    const int npanels = (m + BM - 1) / BM;
+    const long long npanels = (m + BM - 1) / BM;
     const int ntiles = (NC + BN - 1) / BN;
     if (npanels < 1 || ntiles < 1) return 1;
-    int seg = (2 * cus) / npanels;          // enough work items for two workgroups per CU
-    if (seg > ntiles) seg = ntiles;
-    return seg < 1 ? 1 : seg;
+    const long long slots = 2LL * cus;
+    if (npanels * 16 <= slots) {
+        long long seg = slots / npanels;
+        if (seg > ntiles) seg = ntiles;
+        return seg < 1 ? 1 : (int)seg;
+    }
+    auto passes = [&](int seg) {
+        const long long items = npanels * seg;
+        const long long full = items / slots, last = items % slots;
+        const double tail = last == 0 ? 0.0 : (last * 2 <= slots ? 0.6 : 1.0);
+        return ((double)full + tail) / seg;
+    };
+    int best = 1;
+    double best_cost = passes(1);
+    const double bar = 0.9 * best_cost;
+    for (int seg = 2; seg <= 16 && ntiles / seg >= 16; ++seg) {
+        double cost = passes(seg) * (1.0 + 0.004 * seg);   // per-item set-up and the merge of the minima
+        if (fast_unsegmented) cost *= 1.18;
+        if (cost < bar && cost < best_cost) { best = seg; best_cost = cost; }
+    }
+    return best;
 }
 
 hipError_t launch_segmented_1nn(const SweepParams& p_in, unsigned long long* keys, hipStream_t stream)
@@ -1308,7 +1334,7 @@ hipError_t launch_segmented_1nn(const SweepParams& p_in, unsigned long long* key
     const int m = p.NQ;
     if (m < 1) return hipSuccess;
     p.k = 1;
-    p.segments = sweep_segments_for(m, p.NC);
+    p.segments = sweep_segments_for(m, p.NC, p.d % 4 == 0 && p.d <= 4 * KC);
     if (p.segments <= 1) {
         p.segments = 0;
         p.out_key = nullptr;
@@ -1334,7 +1360,7 @@ hipError_t launch_segmented_cross_1nn(const SweepParams& p_in, unsigned long lon
     const int m = p.m;
     if (m < 1) return hipSuccess;
     p.k = 1;
-    p.segments = (p.tile_c || p.qslot || !keys) ? 1 : sweep_segments_for(m, p.NC);
+    p.segments = (p.tile_c || p.qslot || !keys) ? 1 : sweep_segments_for(m, p.NC, p.d % 4 == 0 && p.d <= 4 * KC);
     if (p.segments <= 1) {
         p.segments = 0;
         p.out_key = nullptr;
