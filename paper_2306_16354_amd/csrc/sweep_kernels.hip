@@ -1385,6 +1385,7 @@ int sweep_grid_limit()
 
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream)
 {
+    if (p.k == 1) return launch_sweep_t<1, false>(p, stream);
     if (p.k <= 8) return launch_sweep_t<8, false>(p, stream);
     if (p.k <= 16) return launch_sweep_t<16, false>(p, stream);
     if (p.k <= 32) return launch_sweep_t<32, false>(p, stream);
