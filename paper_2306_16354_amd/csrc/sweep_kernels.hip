@@ -355,6 +355,36 @@ __device__ __attribute__((noinline)) void seed_resolve(SeedPick pick, int col0, 
     resolve_queue<KL, VEC4>(__popcll(mask), col0, Xq, Xc, c_id, d, k);
 }
 
+// Seeding of pruned k-NN sweeps (k > 1).  The same problem as above, but a list has to be full before
+// its query has a threshold, so the first tile must deliver at least k candidates per query, and
+// should not deliver many more.  Each of the two lanes that hold a query's 128 accumulators finds, by
+// bisection with counting (seed_range, seed_count: one call per block and step), a value that at least
+// k/2 + 1 of its 64 accumulators reach; the smaller of the two values is the provisional bound of the
+// query, the pairs that reach it go through the batched path (which fills the list and sets the
+// threshold), and their accumulators are then set to -inf so that the ordinary epilogue of the tile,
+// which runs next under the real threshold, only sees the others.
+struct SeedRange { float lo, hi; };
+
+__device__ __attribute__((noinline)) SeedRange seed_range(v16f t, SeedRange cur)
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (t[r] > -__builtin_inff()) {
+            cur.lo = fminf(cur.lo, t[r]);
+            cur.hi = fmaxf(cur.hi, t[r]);
+        }
+    }
+    return cur;
+}
+
+__device__ __attribute__((noinline)) int seed_count(v16f t, float x)
+{
+    int n = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) n += (t[r] >= x) ? 1 : 0;
+    return n;
+}
+
 // Deferred form of the rare path, for the sweeps that multiply every tile.  After the first tiles of
 // a panel a step leaves one or two surviving pairs per wavefront, and resolving them at once costs a
 // full dependent chain (queue, two row loads from L2, reduction, insert) in every step.  Here a step
@@ -443,7 +473,7 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
         if (__ballot(t[r] >= bound) == 0ull) continue;
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
         const int cg = col0 + cl;
-        bool pred = real_query && (t[r] >= bound) && (cg < N);
+        bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
         if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
         const unsigned long long mask = __ballot(pred);
@@ -989,6 +1019,22 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
  if (tile < ntiles) gload(tile, 0);
         PHASE_MARK(2);
+        // largest threshold of this wavefront's 32 queries, from their bounds: thr = 2 (h_q - bound)
+        auto refresh_wave_thr = [&]() {
+            float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
+            t = fmaxf(t, __shfl_xor(t, 1));
+            t = fmaxf(t, __shfl_xor(t, 2));
+            t = fmaxf(t, __shfl_xor(t, 4));
+            t = fmaxf(t, __shfl_xor(t, 8));
+            t = fmaxf(t, __shfl_xor(t, 16));
+            // 2 (h_q - bound) reproduces the threshold up to a few ulps of h_q; widen it
+            wave_thr_max = t + 4.f * 1.1920929e-07f * fmaxf(fabsf(hqs[my_q_local]), t);
+            wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 1));
+            wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 2));
+            wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 4));
+            wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 8));
+            wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
+        };
         int step = 0;                      // multiplied tiles of this panel (buffer parity)
         while (tile < ntiles) {
             const int col0 = tile * BN;
@@ -1073,6 +1119,53 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 pick = seed_block<KL, MASKED>(acc[3], 3, pick, seed_tag, col0, tpar, N);
                 seed_resolve<KL, true>(pick, col0, Xq, Xc, p.c_id, d, k);
                 bound = bounds[my_q_local];
+                if (prune) refresh_wave_thr();     // the tile may leave no survivor to do it below
+            }
+            // ---- first tile of a pruned k-NN panel: fill the lists from its best candidates ----
+            if (PRUNE && !MASKED && k > 1 && step == 0) {
+                SeedRange range{__builtin_inff(), -__builtin_inff()};
+                range = seed_range(acc[0], range);
+                range = seed_range(acc[1], range);
+                range = seed_range(acc[2], range);
+                range = seed_range(acc[3], range);
+                const int want = (k >> 1) + 1;
+                for (int it = 0; it < 12; ++it) {
+                    const float mid = 0.5f * (range.lo + range.hi);
+                    const int reach = seed_count(acc[0], mid) + seed_count(acc[1], mid) +
+                                      seed_count(acc[2], mid) + seed_count(acc[3], mid);
+                    if (reach >= want) range.lo = mid; else range.hi = mid;
+                }
+                float provisional = range.lo;                       // +inf when the lane has no candidate
+                provisional = fminf(provisional, __shfl_xor(provisional, 32));
+                {
+                    // every pair that reaches the provisional bound, whatever the lists hold meanwhile
+                    // (the bound is not refreshed between blocks: the masking below relies on it)
+                    const int seed_tag = p.exclude_self ? my_qrow : -1;
+                    const float reach_bound = fmaxf(bound, provisional);
+                    int queued = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        int r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, queued);
+                        if (r < 0) {                                 // queue full: resolve, then this block alone
+                            survivors += (unsigned int)queued;
+                            resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
+                            r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, 0);
+                        }
+                        queued = r;
+                    }
+                    if (queued > 0) {
+                        survivors += (unsigned int)queued;
+                        resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
+                    }
+                    bound = bounds[my_q_local];
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[b][r] = (acc[b][r] >= provisional) ? -__builtin_inff() : acc[b][r];
+                }
+                refresh_wave_thr();
             }
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
             PHASE_MARK(3);
@@ -1131,22 +1224,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     bound = bounds[my_q_local];
                 }
                 __builtin_amdgcn_s_setprio(0);
-                if (prune) {
-                    // largest threshold of this wavefront's 32 queries: thr = 2 (h_q - bound)
-                    float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
-                    t = fmaxf(t, __shfl_xor(t, 1));
-                    t = fmaxf(t, __shfl_xor(t, 2));
-                    t = fmaxf(t, __shfl_xor(t, 4));
-                    t = fmaxf(t, __shfl_xor(t, 8));
-                    t = fmaxf(t, __shfl_xor(t, 16));
-                    // 2 (h_q - bound) reproduces the threshold up to a few ulps of h_q; widen it
-                    wave_thr_max = t + 4.f * 1.1920929e-07f * fmaxf(fabsf(hqs[my_q_local]), t);
-                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 1));
-                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 2));
-                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 4));
-                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 8));
-                    wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
-                }
+                if (prune) refresh_wave_thr();
             }
             if (shared_thr && flagged == 0) bound = own_bound;
             PHASE_MARK(6);
