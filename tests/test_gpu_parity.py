@@ -360,6 +360,25 @@ def test_pruned_knn_is_identical(lib, name, n):
     check_knn(X, k, i1.cpu().numpy()[rows], d1.cpu().numpy()[rows], rows=rows, min_exact=0.9)
 
 
+# Whatever path fills a list (the first tile's seeding pass, the batched queue, the deferred queue),
+# every neighbour appears once and the entries ascend in (distance, id): data with many exact
+# duplicates and equal distances, both modes, several k.
+@pytest.mark.parametrize("k", [2, 8, 33])
+def test_knn_lists_are_strictly_ordered(lib, k):
+    X, _, _ = gen.make("c5", n=20000)
+    print(f"list order c5 N={X.shape[0]} d={X.shape[1]} k={k}", flush=True)
+    Xd = torch.from_numpy(X).cuda()
+    for prune in (False, True):
+        idx, dist = lib.knn_graph(Xd, k, prune=prune)
+        torch.cuda.synchronize()
+        i, d = idx.cpu().numpy().astype(np.int64), dist.cpu().numpy()
+        assert (i >= 0).all() and (i < X.shape[0]).all()
+        assert (i != np.arange(X.shape[0])[:, None]).all()                  # self excluded
+        dd, di = np.diff(d, axis=1), np.diff(i, axis=1)
+        assert (dd >= 0).all()
+        assert ((dd > 0) | (di > 0)).all()                                  # strict (distance, id) order: no repeats
+
+
 def test_pruned_knn_lattice_and_ragged(lib):
     X = gen.integer_lattice(9, 3, seed=4)                      # ties everywhere
     Xd = torch.from_numpy(X).cuda()
