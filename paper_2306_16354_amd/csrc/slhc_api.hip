@@ -481,7 +481,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
 // (union by size, path halving) in which every set carries the dendrogram node created by its last
 // merge; merge i creates node N+i.  The edges arrive in weight order, so their end points are
 // scattered over the whole array: one 16-byte record per point keeps a find step to one cache
-// line, and the records of the edges a few iterations ahead are prefetched.
+// line, and the records of the edges a few iterations ahead, then their parents, are prefetched.
 void build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* children, int32_t* sizes)
 {
     struct PointSet { int32_t up, count, node, unused; };
@@ -494,11 +494,14 @@ void build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* 
         }
         return a;
     };
-    constexpr int64_t AHEAD = 8;
+    constexpr int64_t AHEAD = 16;
     for (int64_t i = 0; i < N - 1; ++i) {
         if (i + AHEAD < N - 1) {
             __builtin_prefetch(&set[(size_t)lo[i + AHEAD]]);
             __builtin_prefetch(&set[(size_t)hi[i + AHEAD]]);
+            // and, half way, the records those point to (their own have arrived by now)
+            __builtin_prefetch(&set[(size_t)set[(size_t)lo[i + AHEAD / 2]].up]);
+            __builtin_prefetch(&set[(size_t)set[(size_t)hi[i + AHEAD / 2]].up]);
         }
         int32_t ra = root(lo[i]), rb = root(hi[i]);
         const int32_t a = set[(size_t)ra].node, b = set[(size_t)rb].node;
