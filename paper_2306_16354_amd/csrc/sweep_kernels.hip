@@ -316,6 +316,7 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
 // tile then goes through the filter with the thresholds they leave.  The seeds are ordinary exact
 // candidates, so the result of the sweep does not depend on them.
 struct SeedPick { float v; int cl; };
+constexpr int SEED_AGAIN_LANES = 8;     // later tiles of a pruned 1-NN sweep are seeded too from this many passing lanes on
 
 template <int KL, bool MASKED>
 __device__ __attribute__((noinline)) SeedPick seed_block(v16f t, int b, SeedPick cur, int tag, int col0,
@@ -1121,57 +1122,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 bound = bounds[my_q_local];
                 if (prune) refresh_wave_thr();     // the tile may leave no survivor to do it below
             }
-            // ---- first tile of a pruned k-NN panel: fill the lists from its best candidates ----
-            if (PRUNE && !MASKED && k > 1 && step == 0) {
-                SeedRange range{__builtin_inff(), -__builtin_inff()};
-                range = seed_range(acc[0], range);
-                range = seed_range(acc[1], range);
-                range = seed_range(acc[2], range);
-                range = seed_range(acc[3], range);
-                const int want = (k >> 1) + 1;
-                for (int it = 0; it < 12; ++it) {
-                    const float mid = 0.5f * (range.lo + range.hi);
-                    const int reach = seed_count(acc[0], mid) + seed_count(acc[1], mid) +
-                                      seed_count(acc[2], mid) + seed_count(acc[3], mid);
-                    if (reach >= want) range.lo = mid; else range.hi = mid;
-                }
-                float provisional = range.lo;                       // +inf when the lane has no candidate
-                provisional = fminf(provisional, __shfl_xor(provisional, 32));
-                {
-                    // every pair that reaches the provisional bound, whatever the lists hold meanwhile
-                    // (the bound is not refreshed between blocks: the masking below relies on it)
-                    const int seed_tag = p.exclude_self ? my_qrow : -1;
-                    const float reach_bound = fmaxf(bound, provisional);
-                    int queued = 0;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        int r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, queued);
-                        if (r < 0) {                                 // queue full: resolve, then this block alone
-                            survivors += (unsigned int)queued;
-                            resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
-                            r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, 0);
-                        }
-                        queued = r;
-                    }
-                    if (queued > 0) {
-                        survivors += (unsigned int)queued;
-                        resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
-                    }
-                    bound = bounds[my_q_local];
-                }
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[b][r] = (acc[b][r] >= provisional) ? -__builtin_inff() : acc[b][r];
-                }
-                refresh_wave_thr();
-            }
             // ---- tile epilogue: filter (hot), then compact / re-evaluate / select (rare) ----
             PHASE_MARK(3);
             const float own_bound = bound;
             if (shared_thr) bound = fmaxf(bound, hqs[my_q_local] - 0.5f * thr_c);
             unsigned int flagged = 0;
+            int hits = 0;                  // pruned sweeps: lanes that hold a passing pair, over the four blocks
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 bool any = false;
@@ -1188,7 +1144,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 #pragma unroll
                     for (int r = 0; r < 16; ++r) any |= (acc[b][r] >= bound);
                 }
-                if (__any(any)) flagged |= 1u << b;
+                const unsigned long long hit = __ballot(any);
+                if (hit) flagged |= 1u << b;
+                if (PRUNE) hits += __popcll(hit);
             }
             PHASE_MARK(5);
             if (__builtin_expect(flagged != 0, 0)) {
@@ -1197,6 +1155,69 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 __builtin_amdgcn_s_setprio(1);
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
                 if (PRUNE) {
+                    // First tile of a k-NN panel (k > 1): fill the lists from its best candidates (see
+                    // seed_range).  Later tiles were tried too and gain nothing: what passes there are
+                    // mostly real list updates.
+                    if (!MASKED && k > 1 && step == 0) {
+                        SeedRange range{__builtin_inff(), -__builtin_inff()};
+                        range = seed_range(acc[0], range);
+                        range = seed_range(acc[1], range);
+                        range = seed_range(acc[2], range);
+                        range = seed_range(acc[3], range);
+                        const int want = (k >> 1) + 1;
+                        for (int it = 0; it < 12; ++it) {
+                            const float mid = 0.5f * (range.lo + range.hi);
+                            const int reach = seed_count(acc[0], mid) + seed_count(acc[1], mid) +
+                                              seed_count(acc[2], mid) + seed_count(acc[3], mid);
+                            if (reach >= want) range.lo = mid; else range.hi = mid;
+                        }
+                        float provisional = range.lo;                       // +inf when the lane has no candidate
+                        provisional = fminf(provisional, __shfl_xor(provisional, 32));
+                        {
+                            // every pair that reaches the provisional bound, whatever the lists hold meanwhile
+                            // (the bound is not refreshed between blocks: the masking below relies on it)
+                            const int seed_tag = p.exclude_self ? my_qrow : -1;
+                            const float reach_bound = fmaxf(bound, provisional);
+                            int queued = 0;
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) {
+                                int r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, queued);
+                                if (r < 0) {                                 // queue full: resolve, then this block alone
+                                    survivors += (unsigned int)queued;
+                                    resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
+                                    r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, 0);
+                                }
+                                queued = r;
+                            }
+                            if (queued > 0) {
+                                survivors += (unsigned int)queued;
+                                resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
+                            }
+                            bound = bounds[my_q_local];
+                        }
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                acc[b][r] = (acc[b][r] >= provisional) ? -__builtin_inff() : acc[b][r];
+                        }
+                        refresh_wave_thr();
+                    }
+                    // A pruned 1-NN sweep only multiplies near tiles, where a query can have dozens of
+                    // candidates below its threshold at once: evaluate the most promising one per lane
+                    // first (as in the first tile), so that the compaction below runs under the
+                    // threshold it leaves and only the close contenders are re-evaluated.
+                    if (k == 1 && step > 0 && hits >= SEED_AGAIN_LANES) {
+                        SeedPick pick{-__builtin_inff(), -1};
+                        pick = seed_block<KL, MASKED>(acc[0], 0, pick, my_tag, col0, tpar, N);
+                        pick = seed_block<KL, MASKED>(acc[1], 1, pick, my_tag, col0, tpar, N);
+                        pick = seed_block<KL, MASKED>(acc[2], 2, pick, my_tag, col0, tpar, N);
+                        pick = seed_block<KL, MASKED>(acc[3], 3, pick, my_tag, col0, tpar, N);
+                        if (!(pick.v >= bound)) pick.cl = -1;
+                        seed_resolve<KL, true>(pick, col0, Xq, Xc, p.c_id, d, k);
+                        bound = bounds[my_q_local];
+                        if (shared_thr) bound = fmaxf(bound, hqs[my_q_local] - 0.5f * thr_c);
+                    }
                     const int colbuf_ = tpar;
                     SLHC_SELECT_TILE(KL, MASKED, true);
                     if (shared_thr) bound = bounds[my_q_local];         // this query's own bound again
