@@ -182,6 +182,19 @@ __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32
     if (u >= 0) min_into(&f.best_w[c], __float_as_uint(w));
 }
 
+// slot of this lane among the lanes of `mask` behind *counter (one atomic per wavefront)
+__device__ inline int wave_append(unsigned long long mask, bool mine, int32_t* counter)
+{
+    if (!mask) return -1;
+    const int lane = threadIdx.x & 63;
+    const int leader = __builtin_ctzll(mask);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(counter, __popcll(mask));
+    base = __shfl(base, leader);
+    const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+    return mine ? base + pre : -1;
+}
+
 // Two-phase connection sweeps.  k_split_queries sends the listed rows whose 128-row panel in the row
 // order is a sampled one (every `stride`-th panel) to part A and the others to part B.  After the
 // sweep over part A has lowered best_w, k_still_needed keeps of part B only the rows whose bound still
@@ -192,26 +205,32 @@ __global__ void __launch_bounds__(TB) k_split_queries(ForestState f, const int32
                                                       int32_t* __restrict__ counts)
 {
     const int q = blockIdx.x * TB + threadIdx.x;
-    if (q >= n) return;
-    const int v = list[q];
-    if (!in_range(v, f.N)) { report(f, 10); return; }
-    const bool sampled = ((inv[v] >> 7) % stride) == 0;
-    const int slot = atomicAdd(&counts[sampled ? 0 : 1], 1);
-    if (!in_range(slot, f.N)) { report(f, 10); return; }
-    (sampled ? part_a : part_b)[slot] = v;
+    int v = -1;
+    if (q < n) {
+        v = list[q];
+        if (!in_range(v, f.N)) { report(f, 10); v = -1; }
+    }
+    const bool sampled = v >= 0 && ((inv[v] >> 7) % stride) == 0;
+    const bool other = v >= 0 && !sampled;
+    const int slot_a = wave_append(__ballot(sampled), sampled, &counts[0]);
+    const int slot_b = wave_append(__ballot(other), other, &counts[1]);
+    if (sampled) { if (in_range(slot_a, f.N)) part_a[slot_a] = v; else report(f, 10); }
+    if (other) { if (in_range(slot_b, f.N)) part_b[slot_b] = v; else report(f, 10); }
 }
 
 __global__ void __launch_bounds__(TB) k_still_needed(ForestState f, const int32_t* __restrict__ list, int n,
                                                      int32_t* __restrict__ out, int32_t* __restrict__ count)
 {
     const int q = blockIdx.x * TB + threadIdx.x;
-    if (q >= n) return;
-    const int v = list[q];
-    if (!in_range(v, f.N) || !in_range(f.colour[v], f.N)) { report(f, 11); return; }
-    if (__float_as_uint(f.cand_w[v]) > f.best_w[f.colour[v]]) return;
-    const int slot = atomicAdd(count, 1);
-    if (!in_range(slot, f.N)) { report(f, 11); return; }
-    out[slot] = v;
+    bool keep = false;
+    int v = -1;
+    if (q < n) {
+        v = list[q];
+        if (!in_range(v, f.N) || !in_range(f.colour[v], f.N)) report(f, 11);
+        else keep = __float_as_uint(f.cand_w[v]) <= f.best_w[f.colour[v]];
+    }
+    const int slot = wave_append(__ballot(keep), keep, count);
+    if (keep) { if (in_range(slot, f.N)) out[slot] = v; else report(f, 11); }
 }
 
 __global__ void __launch_bounds__(TB) k_select_edges(ForestState f)
