@@ -12,13 +12,24 @@
  *     (for instance the data_ptr() of a torch tensor).  Pointers marked HOST are host memory.
  *     The library never frees or keeps a caller pointer after the call returns, and it never
  *     modifies an input.
- *   - X is row-major float32 [N, d], finite values.  Distances are squared Euclidean.
+ *   - X is row-major float32 [N, d].  Distances are squared Euclidean.  Values must be finite and
+ *     small enough that a row's squared norm is finite in float32: slhc_slhc / slhc_slhc_opt and
+ *     the SLHC_PRUNE form of slhc_knn_graph_opt detect a violation and return SLHC_NONFINITE.  The
+ *     asynchronous entry points cannot return what only the device knows: there a row with a
+ *     non-finite norm is never reported as anybody's neighbour, and the entries of its own result
+ *     are unspecified except that every index written is -1 or a valid row.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - `workspace` is DEVICE scratch of at least the size the matching *_workspace_bytes call
  *     reports, 256-byte aligned; its contents on entry are ignored and on exit unspecified.
- *   - Every function returns an slhc_status.  No C++ exception crosses the boundary.  On any
- *     status other than SLHC_OK the outputs are unspecified.  slhc_last_error() gives a
- *     thread-local detail string for the last failing call of the calling thread.
+ *   - Every function returns an slhc_status.  No C++ exception crosses the boundary (a failed
+ *     host allocation becomes SLHC_HOST_MEMORY).  On any status other than SLHC_OK the outputs are
+ *     unspecified.  slhc_last_error() gives a thread-local detail string for the last failing call
+ *     of the calling thread.
+ *   - Device memory: the library allocates none; everything it needs is in `workspace`.  Host
+ *     memory: the synchronous entry points (slhc_slhc*, slhc_csr_msf, and slhc_knn_graph_opt with
+ *     SLHC_PRUNE) allocate pinned staging buffers and HIP events for the duration of the call
+ *     (slhc_slhc: 20 bytes per row for the host dendrogram pass) and free them before returning.
+ *     The library keeps no mutable state between calls other than the thread-local error text.
  *   - Calls that share a workspace must not overlap in time.  Calls on different streams with
  *     different workspaces and outputs are independent.
  */
@@ -32,7 +43,7 @@
 extern "C" {
 #endif
 
-#define SLHC_ABI_VERSION 1
+#define SLHC_ABI_VERSION 2
 
 /* Largest k of the fused path: the selection keeps one list entry per lane of a 64-wide
  * wavefront.  (The paper's fused k-NN has the same limit, Sec. 2 and Sec. 3.1.1: k <= 64.) */
@@ -40,12 +51,16 @@ extern "C" {
 
 typedef enum slhc_status {
     SLHC_OK = 0,
-    SLHC_INVALID_ARG = 1,        /* null pointer, N < 2, d < 1, k < 1, k > N-1, bad row index      */
+    SLHC_INVALID_ARG = 1,        /* null pointer, N < 2, d < 1, k < 1, k > N-1, malformed CSR input */
     SLHC_UNSUPPORTED = 2,        /* k > SLHC_MAX_K, or N*k / N*d beyond the 2^31-1 element indexing */
     SLHC_WORKSPACE_TOO_SMALL = 3,
     SLHC_HIP_ERROR = 4,          /* a HIP call failed; see slhc_last_error()                      */
-    SLHC_INTERNAL = 5            /* the connection loop did not reach one component in
+    SLHC_NONFINITE = 5,          /* a row of X has a NaN, an infinity, or a squared norm that
+                                    overflows float32 (found on the device by the norm kernel)    */
+    SLHC_INTERNAL = 6,           /* a consistency check of the forest state failed, or the
+                                    connection loop did not reach one component in
                                     ceil(log2 N) + 2 rounds (cannot happen for finite input)      */
+    SLHC_HOST_MEMORY = 7         /* a host allocation failed                                      */
 } slhc_status;
 
 /* Counters and stage times of one slhc_slhc call (HOST struct, filled when not NULL). */
@@ -68,7 +83,7 @@ typedef struct slhc_stats {
     float ms_connect_kernels;        /* HIP-event time summed over the cross-component 1-NN sweeps */
     float ms_order;                  /* HIP-event time of building the row order + tile balls     */
     int64_t knn_tile_steps;          /* (query panel, candidate tile) pairs the k-NN sweep multiplied;
-                                        ceil(N/128)^2 when nothing is pruned                        */
+                                        ceil(N/128)^2 when nothing is pruned (either sweep kernel)  */
     int64_t connect_tile_steps;      /* same, summed over the connection sweeps                    */
     int32_t pruned;                  /* 1 when tile pruning was active in this call                */
     int32_t order_padded_rows;       /* rows of the reordered copy incl. padding (0 when not pruned) */
@@ -78,7 +93,14 @@ typedef struct slhc_stats {
 #define SLHC_PRUNE 1u   /* reorder rows spatially and skip (query panel, candidate tile) pairs whose
                            bounding balls prove that no pair can enter a list.  Results are identical
                            to the unpruned sweep; only available for d <= 128 with d % 4 == 0 and
-                           N >= 512 (ignored otherwise).  Not in the paper, whose k-NN multiplies every tile.          */
+                           N >= 512 (ignored otherwise).  Not in the paper, whose k-NN multiplies every tile.
+                           Building the row order reads counters back, so a call with this flag
+                           is synchronous and allocates pinned host staging while it runs.      */
+#define SLHC_SPLIT_ROUNDS 2u   /* slhc_slhc_opt with SLHC_PRUNE only; a testing and tuning aid.  Every
+                           pruned connection round of at least 256 query rows runs in two phases
+                           (a sample of the row panels first, the rest under the thresholds that
+                           leaves), which the library otherwise does only for rounds of >= 262144
+                           rows under loose thresholds.  Same outputs.                          */
 
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */
@@ -96,8 +118,9 @@ const char* slhc_last_error(void);              /* thread-local, never NULL  */
  *   X         DEVICE in   [N*d]
  *   nbr_idx   DEVICE out  [N*k] row-major int32
  *   nbr_dist  DEVICE out  [N*k] row-major float32
- * Asynchronous: work is enqueued on `stream`; outputs are complete when the stream reaches the
- * end of that work.  Errors detected on the host are reported immediately.
+ * slhc_knn_graph (and _opt with flags = 0) is asynchronous: work is enqueued on `stream`; outputs
+ * are complete when the stream reaches the end of that work; errors detected on the host are
+ * reported immediately.  With SLHC_PRUNE the call is synchronous (see the flag).
  */
 int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes /* HOST out */);
 int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k,
@@ -118,6 +141,8 @@ int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k,
  *   X        DEVICE in  [N*d]       colour   DEVICE in  [N] int32
  *   rows     DEVICE in  [m] int32   (each in [0, N); NULL means rows 0..m-1, then m <= N)
  *   out_idx  DEVICE out [m] int32   out_dist DEVICE out [m] float32
+ * The row list lives on the device, so it is not validated on the host: an entry outside [0, N)
+ * is not dereferenced and gets out_idx = -1, out_dist = +inf.
  * Asynchronous on `stream` like slhc_knn_graph.
  */
 int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes /* HOST out */);

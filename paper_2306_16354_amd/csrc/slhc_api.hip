@@ -10,6 +10,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
+#include <new>
 #include <vector>
 
 #include "../../include/slhc.h"
@@ -41,6 +43,24 @@ int hip_fail(hipError_t e, const char* what)
         hipError_t _e = (expr);                                        \
         if (_e != hipSuccess) return hip_fail(_e, #expr);              \
     } while (0)
+
+// Runs the body of an exported function; no C++ exception leaves the library.
+template <typename F>
+int guarded(F&& body) noexcept
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        set_err("a host allocation failed");
+        return SLHC_HOST_MEMORY;
+    } catch (const std::exception& e) {
+        set_err("unexpected exception: %s", e.what());
+        return SLHC_INTERNAL;
+    } catch (...) {
+        set_err("unexpected exception");
+        return SLHC_INTERNAL;
+    }
+}
 
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t b) { return (b + ALIGN - 1) & ~(ALIGN - 1); }
@@ -194,6 +214,7 @@ struct OrderWs {
 
 struct KnnWs {
     unsigned long long* counters;    // [0] k-NN survivors [1] connect survivors [2] k-NN tile steps [3] connect tile steps
+                                     // [4] non-finite flag (low word) [8] panel hand-out counter (low word)
     float* hn;
     bool has_order;
     OrderWs order;
@@ -270,7 +291,10 @@ int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, Orde
 //      rows: perm = -1, zero features, +inf half norm), so tiles do not straddle distant clusters.
 //   4. One bounding ball per tile of the reordered copy.
 // The order only affects which tiles the sweeps can skip, never a result.
-int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, hipStream_t s)
+// `nonfinite`: device word the norm kernel set when a row is not finite; checked first, because
+// nothing below is defined for such rows.
+int build_order(const float* X, int64_t N, int32_t d, const float* hn, const unsigned int* nonfinite, OrderWs& o,
+                hipStream_t s)
 {
     const int n = (int)N;
     const int P1 = o.P1;
@@ -285,6 +309,10 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& 
     int32_t* h_cells = reinterpret_cast<int32_t*>(h_w + o.Pmax);
     int32_t* h_rank = h_cells + o.Pmax;
     int32_t* h_shift = h_rank + o.Pmax;
+
+    HIP_TRY(hipMemcpyAsync(h_count + 8, nonfinite, 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (h_count[8] != 0) { set_err("a row of X is not finite (NaN, infinity, or a squared norm beyond float32)"); return SLHC_NONFINITE; }
 
     // ---- 1. pivots and assignment
     HIP_TRY(slhc::order_pick_rows(X, hn, n, d, P1, o.Xp, o.hp, s));
@@ -439,13 +467,13 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(ws.counters), 64);
     HIP_TRY(hipGetLastError());
     if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->a, stream));
-    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn, stream));
+    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn, stream, reinterpret_cast<unsigned int*>(ws.counters + 4)));
     if (ev_norm) HIP_TRY(hipEventRecord(ev_norm->b, stream));
     const bool prune = (flags & SLHC_PRUNE) && ws.has_order;
     if (pruned_out) *pruned_out = prune;
     if (ev_order) HIP_TRY(hipEventRecord(ev_order->a, stream));
     if (prune) {
-        const int rc = build_order(X, N, d, ws.hn, ws.order, stream);
+        const int rc = build_order(X, N, d, ws.hn, reinterpret_cast<const unsigned int*>(ws.counters + 4), ws.order, stream);
         if (rc != SLHC_OK) return rc;
     }
     if (ev_order) HIP_TRY(hipEventRecord(ev_order->b, stream));
@@ -529,7 +557,9 @@ const char* slhc_strerror(int status)
         case SLHC_UNSUPPORTED: return "unsupported size";
         case SLHC_WORKSPACE_TOO_SMALL: return "workspace too small";
         case SLHC_HIP_ERROR: return "HIP error";
+        case SLHC_NONFINITE: return "input not finite";
         case SLHC_INTERNAL: return "internal error";
+        case SLHC_HOST_MEMORY: return "host allocation failed";
         default: return "unknown status";
     }
 }
@@ -538,64 +568,74 @@ const char* slhc_last_error(void) { return g_err; }
 
 int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, k, true);
-    if (rc != SLHC_OK) return rc;
-    *bytes = KnnWs(nullptr, N, d, true).bytes;
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, k, true);
+        if (rc != SLHC_OK) return rc;
+        *bytes = KnnWs(nullptr, N, d, true).bytes;
+        return SLHC_OK;
+    });
 }
 
 int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
                        void* workspace, size_t workspace_bytes, void* stream, uint32_t flags)
 {
-    if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, k, true);
-    if (rc != SLHC_OK) return rc;
-    KnnWs ws(workspace, N, d, true);
-    if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
-    return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
+    return guarded([&]() -> int {
+        if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, k, true);
+        if (rc != SLHC_OK) return rc;
+        KnnWs ws(workspace, N, d, true);
+        if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+        return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
+    });
 }
 
 int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
                    void* workspace, size_t workspace_bytes, void* stream)
 {
-    return slhc_knn_graph_opt(X, N, d, k, nbr_idx, nbr_dist, workspace, workspace_bytes, stream, 0u);
+    return guarded([&]() -> int {
+        return slhc_knn_graph_opt(X, N, d, k, nbr_idx, nbr_dist, workspace, workspace_bytes, stream, 0u);
+    });
 }
 
 int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, 1, false);
-    if (rc != SLHC_OK) return rc;
-    if (m < 0 || m > 2147483647LL) { set_err("bad m"); return SLHC_INVALID_ARG; }
-    *bytes = up(32 * sizeof(unsigned long long)) + up((size_t)N * sizeof(float));
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, 1, false);
+        if (rc != SLHC_OK) return rc;
+        if (m < 0 || m > 2147483647LL) { set_err("bad m"); return SLHC_INVALID_ARG; }
+        *bytes = up(32 * sizeof(unsigned long long)) + up((size_t)N * sizeof(float));
+        return SLHC_OK;
+    });
 }
 
 int slhc_cross_1nn(const float* X, int64_t N, int32_t d, const int32_t* colour, const int32_t* rows,
                    int64_t m, int32_t* out_idx, float* out_dist, void* workspace,
                    size_t workspace_bytes, void* stream)
 {
-    if (!X || !colour || !out_idx || !out_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, 1, false);
-    if (rc != SLHC_OK) return rc;
-    if (m < 0 || m > 2147483647LL || (!rows && m > N)) { set_err("bad m=%lld", (long long)m); return SLHC_INVALID_ARG; }
-    Carver c(workspace);
-    unsigned long long* counters = c.take<unsigned long long>(32);
-    float* hn = c.take<float>((size_t)N);
-    if (workspace_bytes < c.off) { set_err("workspace %zu < %zu bytes", workspace_bytes, c.off); return SLHC_WORKSPACE_TOO_SMALL; }
-    if (m == 0) return SLHC_OK;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(counters), 64);
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, hn, s));
-    slhc::SweepParams p{};
-    p.Xq = p.Xc = X; p.hq = p.hc = hn; p.NQ = p.NC = (int)N; p.d = d; p.k = 1;
-    p.out_idx = out_idx; p.out_dist = out_dist;
-    p.qcolour = p.ccolour = colour; p.rows = rows; p.m = (int)m;
-    p.survivors = counters;
-    HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!X || !colour || !out_idx || !out_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, 1, false);
+        if (rc != SLHC_OK) return rc;
+        if (m < 0 || m > 2147483647LL || (!rows && m > N)) { set_err("bad m=%lld", (long long)m); return SLHC_INVALID_ARG; }
+        Carver c(workspace);
+        unsigned long long* counters = c.take<unsigned long long>(32);
+        float* hn = c.take<float>((size_t)N);
+        if (workspace_bytes < c.off) { set_err("workspace %zu < %zu bytes", workspace_bytes, c.off); return SLHC_WORKSPACE_TOO_SMALL; }
+        if (m == 0) return SLHC_OK;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(counters), 64);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(slhc::launch_half_norms(X, (int)N, d, hn, s));
+        slhc::SweepParams p{};
+        p.Xq = p.Xc = X; p.hq = p.hc = hn; p.NQ = p.NC = (int)N; p.d = d; p.k = 1;
+        p.out_idx = out_idx; p.out_dist = out_dist;
+        p.qcolour = p.ccolour = colour; p.rows = rows; p.m = (int)m;
+        p.survivors = counters;
+        HIP_TRY(slhc::launch_cross_1nn_sweep(p, s));
+        return SLHC_OK;
+    });
 }
 
 struct CsrWs {
@@ -631,78 +671,82 @@ static int csr_shape(int64_t V, int64_t E)
 
 int slhc_csr_msf_workspace_bytes(int64_t V, int64_t E, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    const int rc = csr_shape(V, E);
-    if (rc != SLHC_OK) return rc;
-    *bytes = CsrWs(nullptr, V).bytes;
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        const int rc = csr_shape(V, E);
+        if (rc != SLHC_OK) return rc;
+        *bytes = CsrWs(nullptr, V).bytes;
+        return SLHC_OK;
+    });
 }
 
 int slhc_csr_msf(const int32_t* offsets, const int32_t* indices, const float* weights, int64_t V, int64_t E,
                  int32_t* mst_src, int32_t* mst_dst, float* mst_w, int64_t* n_edges, int32_t* colours,
                  int32_t* rounds, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!offsets || (E > 0 && (!indices || !weights)) || !mst_src || !mst_dst || !mst_w || !n_edges || !colours || !workspace) {
-        set_err("NULL pointer argument");
-        return SLHC_INVALID_ARG;
-    }
-    const int rc = csr_shape(V, E);
-    if (rc != SLHC_OK) return rc;
-    CsrWs ws(workspace, V);
-    if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    slhc::ForestState f{};
-    f.N = (int)V; f.k = 1;
-    f.colour = ws.colour; f.ptr = ws.ptr; f.ext_idx = ws.ext_idx; f.ext_dist = ws.ext_dist;
-    f.cand_w = ws.cand_w; f.cand_u = ws.cand_u; f.best_w = ws.best_w; f.best_e = ws.best_e;
-    f.min_lb = ws.min_lb; f.hook = ws.hook; f.qlist = ws.ptr; f.counters = ws.counters;
-    f.e_lo = ws.e_lo; f.e_hi = ws.e_hi; f.e_w = ws.e_w;
-    HIP_TRY(slhc::forest_init(f, s));
-    HIP_TRY(slhc::forest_csr_check(offsets, indices, weights, (int)V, (int)E, ws.counters, s));
-    PinnedHost pin_cnt;
-    HIP_TRY(pin_cnt.alloc(64));
-    int32_t* h_cnt = static_cast<int32_t*>(pin_cnt.p);
-    HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    if (h_cnt[3] != 0) {
-        set_err("CSR input check %d failed (20-22: offsets, 23: index out of range, 24: weight negative or not finite)", h_cnt[3]);
-        return SLHC_INVALID_ARG;
-    }
-    int edges = 0, nrounds = 0;
-    int max_rounds = 2;
-    for (int64_t t = 1; t < V; t *= 2) ++max_rounds;
-    // Alg. "MST Algorithm": min edge per vertex, min edge per supervertex, label propagation, until a
-    // round adds no edge (the graph's components are then the forest's trees)
-    while (edges < V - 1) {
-        if (nrounds >= max_rounds) { set_err("no steady state after %d rounds", max_rounds); return SLHC_INTERNAL; }
-        ++nrounds;
-        HIP_TRY(slhc::forest_round_reset(f, s));
-        HIP_TRY(slhc::forest_csr_scan(offsets, indices, weights, (int)E, f, s));
-        HIP_TRY(slhc::forest_select_edges(f, s));
-        HIP_TRY(slhc::forest_commit(f, s));
-        int jumps = 0;
-        do {
-            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
-            HIP_TRY(hipGetLastError());
-            HIP_TRY(slhc::forest_jump(f, s));
-            HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-            HIP_TRY(hipStreamSynchronize(s));
-            if (++jumps > 64) { set_err("component hooks do not form a forest (is every edge stored in both rows with one weight?)"); return SLHC_INTERNAL; }
-            if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
-        } while (h_cnt[2] != 0);
-        HIP_TRY(slhc::forest_relabel(f, s));
-        if (h_cnt[1] < edges || h_cnt[1] > V - 1) { set_err("round left %d edges (had %d)", h_cnt[1], edges); return SLHC_INTERNAL; }
-        if (h_cnt[1] == edges) break;                 // steady state: a spanning forest
-        edges = h_cnt[1];
-    }
-    if (edges > 0)
-        HIP_TRY(slhc::edge_sort(ws.e_lo, ws.e_hi, ws.e_w, edges, ws.keys_a, ws.keys_b, ws.vals_a, ws.vals_b,
-                                ws.sort_temp, ws.sort_temp_bytes, mst_src, mst_dst, mst_w, s));
-    HIP_TRY(hipMemcpyAsync(colours, ws.colour, (size_t)V * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    *n_edges = edges;
-    if (rounds) *rounds = nrounds;
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!offsets || (E > 0 && (!indices || !weights)) || !mst_src || !mst_dst || !mst_w || !n_edges || !colours || !workspace) {
+            set_err("NULL pointer argument");
+            return SLHC_INVALID_ARG;
+        }
+        const int rc = csr_shape(V, E);
+        if (rc != SLHC_OK) return rc;
+        CsrWs ws(workspace, V);
+        if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        slhc::ForestState f{};
+        f.N = (int)V; f.k = 1;
+        f.colour = ws.colour; f.ptr = ws.ptr; f.ext_idx = ws.ext_idx; f.ext_dist = ws.ext_dist;
+        f.cand_w = ws.cand_w; f.cand_u = ws.cand_u; f.best_w = ws.best_w; f.best_e = ws.best_e;
+        f.min_lb = ws.min_lb; f.hook = ws.hook; f.qlist = ws.ptr; f.counters = ws.counters;
+        f.e_lo = ws.e_lo; f.e_hi = ws.e_hi; f.e_w = ws.e_w;
+        HIP_TRY(slhc::forest_init(f, s));
+        HIP_TRY(slhc::forest_csr_check(offsets, indices, weights, (int)V, (int)E, ws.counters, s));
+        PinnedHost pin_cnt;
+        HIP_TRY(pin_cnt.alloc(64));
+        int32_t* h_cnt = static_cast<int32_t*>(pin_cnt.p);
+        HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (h_cnt[3] != 0) {
+            set_err("CSR input check %d failed (20-22: offsets, 23: index out of range, 24: weight negative or not finite)", h_cnt[3]);
+            return SLHC_INVALID_ARG;
+        }
+        int edges = 0, nrounds = 0;
+        int max_rounds = 2;
+        for (int64_t t = 1; t < V; t *= 2) ++max_rounds;
+        // Alg. "MST Algorithm": min edge per vertex, min edge per supervertex, label propagation, until a
+        // round adds no edge (the graph's components are then the forest's trees)
+        while (edges < V - 1) {
+            if (nrounds >= max_rounds) { set_err("no steady state after %d rounds", max_rounds); return SLHC_INTERNAL; }
+            ++nrounds;
+            HIP_TRY(slhc::forest_round_reset(f, s));
+            HIP_TRY(slhc::forest_csr_scan(offsets, indices, weights, (int)E, f, s));
+            HIP_TRY(slhc::forest_select_edges(f, s));
+            HIP_TRY(slhc::forest_commit(f, s));
+            int jumps = 0;
+            do {
+                hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(slhc::forest_jump(f, s));
+                HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                if (++jumps > 64) { set_err("component hooks do not form a forest (is every edge stored in both rows with one weight?)"); return SLHC_INTERNAL; }
+                if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+            } while (h_cnt[2] != 0);
+            HIP_TRY(slhc::forest_relabel(f, s));
+            if (h_cnt[1] < edges || h_cnt[1] > V - 1) { set_err("round left %d edges (had %d)", h_cnt[1], edges); return SLHC_INTERNAL; }
+            if (h_cnt[1] == edges) break;                 // steady state: a spanning forest
+            edges = h_cnt[1];
+        }
+        if (edges > 0)
+            HIP_TRY(slhc::edge_sort(ws.e_lo, ws.e_hi, ws.e_w, edges, ws.keys_a, ws.keys_b, ws.vals_a, ws.vals_b,
+                                    ws.sort_temp, ws.sort_temp_bytes, mst_src, mst_dst, mst_w, s));
+        HIP_TRY(hipMemcpyAsync(colours, ws.colour, (size_t)V * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        *n_edges = edges;
+        if (rounds) *rounds = nrounds;
+        return SLHC_OK;
+    });
 }
 
 static size_t fused_1nn_layout(void* ws, int64_t m, int64_t n, float** hq, float** hy, unsigned long long** keys)
@@ -716,33 +760,37 @@ static size_t fused_1nn_layout(void* ws, int64_t m, int64_t n, float** hq, float
 
 int slhc_fused_1nn_workspace_bytes(int64_t m, int64_t n, int32_t d, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
-    if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
-    float *hq, *hy; unsigned long long* keys;
-    *bytes = fused_1nn_layout(nullptr, m, n, &hq, &hy, &keys);
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
+        if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+        float *hq, *hy; unsigned long long* keys;
+        *bytes = fused_1nn_layout(nullptr, m, n, &hq, &hy, &keys);
+        return SLHC_OK;
+    });
 }
 
 int slhc_fused_1nn(const float* Q, int64_t m, const float* Y, int64_t n, int32_t d, int32_t* out_idx,
                    float* out_dist, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!Q || !Y || !out_idx || !out_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-    if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
-    if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
-    float *hq, *hy; unsigned long long* keys;
-    const size_t need = fused_1nn_layout(workspace, m, n, &hq, &hy, &keys);
-    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    HIP_TRY(slhc::launch_half_norms(Q, (int)m, d, hq, s));
-    HIP_TRY(slhc::launch_half_norms(Y, (int)n, d, hy, s));
-    slhc::SweepParams p{};
-    p.Xq = Q; p.hq = hq; p.NQ = (int)m;
-    p.Xc = Y; p.hc = hy; p.NC = (int)n;
-    p.d = d; p.k = 1;
-    p.out_idx = out_idx; p.out_dist = out_dist;
-    HIP_TRY(slhc::launch_segmented_1nn(p, keys, s));
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!Q || !Y || !out_idx || !out_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (m < 1 || n < 1 || d < 1) { set_err("need m >= 1, n >= 1, d >= 1"); return SLHC_INVALID_ARG; }
+        if (m * (int64_t)d > 2147483647LL || n * (int64_t)d > 2147483647LL) { set_err("m*d or n*d exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+        float *hq, *hy; unsigned long long* keys;
+        const size_t need = fused_1nn_layout(workspace, m, n, &hq, &hy, &keys);
+        if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        HIP_TRY(slhc::launch_half_norms(Q, (int)m, d, hq, s));
+        HIP_TRY(slhc::launch_half_norms(Y, (int)n, d, hy, s));
+        slhc::SweepParams p{};
+        p.Xq = Q; p.hq = hq; p.NQ = (int)m;
+        p.Xc = Y; p.hc = hy; p.NC = (int)n;
+        p.d = d; p.k = 1;
+        p.out_idx = out_idx; p.out_dist = out_dist;
+        HIP_TRY(slhc::launch_segmented_1nn(p, keys, s));
+        return SLHC_OK;
+    });
 }
 
 static int flat_clusters_layout(void* ws, int64_t N, int32_t** above, int32_t** flag, int32_t** rank, void** temp,
@@ -761,59 +809,69 @@ static int flat_clusters_layout(void* ws, int64_t N, int32_t** above, int32_t** 
 
 int slhc_flat_clusters_workspace_bytes(int64_t N, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
-    if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
-    int32_t *a, *f, *r; void* t; size_t tb;
-    return flat_clusters_layout(nullptr, N, &a, &f, &r, &t, &tb, bytes);
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
+        if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+        int32_t *a, *f, *r; void* t; size_t tb;
+        return flat_clusters_layout(nullptr, N, &a, &f, &r, &t, &tb, bytes);
+    });
 }
 
 int slhc_flat_clusters(const int32_t* children, int64_t N, int64_t n_clusters, int32_t* labels,
                        void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!children || !labels || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-    if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
-    if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
-    if (n_clusters < 1 || n_clusters > N) { set_err("need 1 <= n_clusters <= N (n_clusters=%lld)", (long long)n_clusters); return SLHC_INVALID_ARG; }
-    int32_t *above, *flag, *rank; void* temp; size_t temp_bytes, total;
-    flat_clusters_layout(workspace, N, &above, &flag, &rank, &temp, &temp_bytes, &total);
-    if (workspace_bytes < total) { set_err("workspace %zu < %zu bytes", workspace_bytes, total); return SLHC_WORKSPACE_TOO_SMALL; }
-    HIP_TRY(slhc::flat_clusters(children, (int)N, (int)n_clusters, labels, above, flag, rank, temp, temp_bytes,
-                                static_cast<hipStream_t>(stream)));
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!children || !labels || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (N < 2) { set_err("need N >= 2 (N=%lld)", (long long)N); return SLHC_INVALID_ARG; }
+        if (N > 1073741823LL) { set_err("2N exceeds 2^31-1"); return SLHC_UNSUPPORTED; }
+        if (n_clusters < 1 || n_clusters > N) { set_err("need 1 <= n_clusters <= N (n_clusters=%lld)", (long long)n_clusters); return SLHC_INVALID_ARG; }
+        int32_t *above, *flag, *rank; void* temp; size_t temp_bytes, total;
+        flat_clusters_layout(workspace, N, &above, &flag, &rank, &temp, &temp_bytes, &total);
+        if (workspace_bytes < total) { set_err("workspace %zu < %zu bytes", workspace_bytes, total); return SLHC_WORKSPACE_TOO_SMALL; }
+        HIP_TRY(slhc::flat_clusters(children, (int)N, (int)n_clusters, labels, above, flag, rank, temp, temp_bytes,
+                                    static_cast<hipStream_t>(stream)));
+        return SLHC_OK;
+    });
 }
 
 int slhc_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
 {
-    if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
-    const int rc = check_shape(N, d, k, true);
-    if (rc != SLHC_OK) return rc;
-    *bytes = SlhcWs(nullptr, N, d, k, true).bytes;
-    return SLHC_OK;
+    return guarded([&]() -> int {
+        if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, k, true);
+        if (rc != SLHC_OK) return rc;
+        *bytes = SlhcWs(nullptr, N, d, k, true).bytes;
+        return SLHC_OK;
+    });
 }
 
 int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, int32_t* mst_dst,
               float* mst_w, int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats,
               void* workspace, size_t workspace_bytes, void* stream)
 {
-    return slhc_slhc_opt(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
-                         workspace_bytes, stream, SLHC_PRUNE);
+    return guarded([&]() -> int {
+        return slhc_slhc_opt(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
+                             workspace_bytes, stream, SLHC_PRUNE);
+    });
 }
 
 int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, int32_t* mst_dst,
                   float* mst_w, int32_t* children, float* heights, int32_t* sizes, slhc_stats* stats,
                   void* workspace, size_t workspace_bytes, void* stream, uint32_t flags)
 {
-    if (!X || !mst_src || !mst_dst || !mst_w || !children || !heights || !sizes || !workspace) {
-        set_err("NULL pointer argument");
-        return SLHC_INVALID_ARG;
-    }
-    const int rc = check_shape(N, d, k, true);
-    if (rc != SLHC_OK) return rc;
-    const size_t need = slhc_ws_bytes(N, d, k, true);
-    if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
-    return run_slhc(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
-                    static_cast<hipStream_t>(stream), flags, true);
+    return guarded([&]() -> int {
+        if (!X || !mst_src || !mst_dst || !mst_w || !children || !heights || !sizes || !workspace) {
+            set_err("NULL pointer argument");
+            return SLHC_INVALID_ARG;
+        }
+        const int rc = check_shape(N, d, k, true);
+        if (rc != SLHC_OK) return rc;
+        const size_t need = slhc_ws_bytes(N, d, k, true);
+        if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
+        return run_slhc(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
+                        static_cast<hipStream_t>(stream), flags, true);
+    });
 }
 
 }  // extern "C"
@@ -846,8 +904,9 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     PinnedHost pin_surv;
     HIP_TRY(pin_surv.alloc(64));
     unsigned long long* h_surv = static_cast<unsigned long long*>(pin_surv.p);
-    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if ((h_surv[4] & 0xffffffffull) != 0) { set_err("a row of X is not finite (NaN, infinity, or a squared norm beyond float32)"); return SLHC_NONFINITE; }
     st.knn_filter_survivors = (int64_t)h_surv[0];
     st.knn_tile_steps = (int64_t)h_surv[2];
     st.ms_norm_kernel = ev_norm.ms();
@@ -951,8 +1010,11 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 return SLHC_OK;
             };
             int queried = nq;
-            if (round_pruned && (int64_t)nq * 2 >= N && (int64_t)nq >= TWO_PHASE_MIN_ROWS &&
-                prev_steps_per_panel >= TWO_PHASE_MIN_STEPS) {
+            const bool split_round = (flags & SLHC_SPLIT_ROUNDS)
+                                         ? nq >= 256
+                                         : ((int64_t)nq * 2 >= N && (int64_t)nq >= TWO_PHASE_MIN_ROWS &&
+                                            prev_steps_per_panel >= TWO_PHASE_MIN_STEPS);
+            if (round_pruned && split_round) {
                 // Two phases, for a round that queries most rows while the thresholds the forest has
                 // are loose (the last pruned round multiplied hundreds of tiles per panel).  The rows
                 // of every 16th panel go first; what they find lowers their components' best

@@ -59,7 +59,8 @@ struct SweepParams {
 };
 
 float filter_slack_coefficient(int d);
-hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream);
+// `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
+hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr);
 int sweep_grid_limit();   // upper bound of gridDim.x of a sweep launch (for sizing gap_ws); 0 on error
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream);
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);

@@ -10,7 +10,9 @@
 // Structure (our own design for 64-wide wavefronts, not the paper's CUDA tiling):
 //   * a workgroup (4 wavefronts) owns a panel of 128 query rows and sweeps all N candidate rows
 //     in tiles of 128; workgroups are persistent and all sweep the candidates in the same order,
-//     so a candidate tile is fetched from HBM about once per XCD and then served by that L2;
+//     but they drift out of step, so most of a panel's candidate stream misses the XCD's L2
+//     (measured at 1M x 128: about 10 % hits, 3.5 TB through the fabric per launch); the
+//     stream runs at a fifth of the HBM peak and stays hidden behind the MFMA work;
 //   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32.  Candidates are the A
 //     operand and queries the B operand, so a lane's 16 accumulators of a 32x32 block belong to
 //     ONE query: the query's threshold is a per-lane scalar;
@@ -98,9 +100,12 @@ __device__ inline float group8_sqdist(const float* __restrict__ a, const float* 
 }
 
 // h_i = (1-c)/2 * ||x_i||^2 ; one 16-lane group per row.
+// A row whose squared norm is not a finite float32 (NaN or infinity among its values, or overflow) sets
+// *nonfinite (optional) to 1.
 template <bool VEC4>
 __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict__ X, int N, int d,
-                                                        float scale, float* __restrict__ hn)
+                                                        float scale, float* __restrict__ hn,
+                                                        unsigned int* __restrict__ nonfinite)
 {
     const int lane16 = threadIdx.x & 15;
     const long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
@@ -127,7 +132,10 @@ __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict_
     s += __shfl_xor(s, 2);
     s += __shfl_xor(s, 4);
     s += __shfl_xor(s, 8);
-    if (active && lane16 == 0) hn[row] = scale * s;
+    if (active && lane16 == 0) {
+        hn[row] = scale * s;
+        if (nonfinite && !(s < __builtin_inff())) atomicOr(nonfinite, 1u);      // NaN fails the compare too
+    }
 }
 
 __device__ inline unsigned long long make_key(float dist, int idx)
@@ -545,6 +553,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     const int ld_col = (tid & 7) * 4;     // 0..28
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
+    unsigned long long tiles_done = 0;
 
     // Work item = (query panel, segment of the candidate tiles).  With one segment a workgroup
     // sweeps all candidates for its panel; with few query rows the candidates are split so that
@@ -628,6 +637,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 
         v16f acc[4];
         if (t_begin < t_end) gload(t_begin, 0);
+        tiles_done += (unsigned long long)(t_end - t_begin);
         for (int tile = t_begin; tile < t_end; ++tile) {
             const int col0 = tile * BN;
             for (int chunk = 0; chunk < nchunks; ++chunk) {
@@ -729,7 +739,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         __builtin_amdgcn_wave_barrier();
         for (int ql = 0; ql < 32; ++ql) {
             const int row = qid[wave * 32 + ql];
-            if (row < 0) continue;
+            if (row < 0) {
+                // a listed row outside [0, NQ): never dereferenced, answered with "nothing found"
+                // (with p.out_key the slot keeps the sentinel it was filled with, which unpacks to the same)
+                const int qi = panel * BM + wave * 32 + ql;
+                if (MASKED && !p.out_key && lane == 0 && qi < nq) {
+                    p.out_idx[qi] = -1;
+                    p.out_dist[qi] = __builtin_inff();
+                }
+                continue;
+            }
             if (lane < k) {
                 const unsigned long long key = mylists[(size_t)ql * KL + lane];
                 const float dist = __uint_as_float((unsigned int)(key >> 32));
@@ -747,6 +766,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         }
     }
     if (p.survivors && lane == 0 && survivors) atomicAdd(p.survivors, survivors);
+    if (p.tiles_done && tid == 0 && tiles_done) atomicAdd(p.tiles_done, tiles_done);
 }
 
 // Variant for d <= 128 (d a multiple of 4): the query fragments of the MFMA B operand stay in
@@ -840,6 +860,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         if (tid < 8) L.wmax[tid] = __builtin_inff();
         if (tid < 4) *deferred_count(L, tid) = 0;
         __syncthreads();
+        // a listed row outside [0, NQ) is never dereferenced and is answered with "nothing found"
+        if (MASKED && !aligned && tid < BM && qid[tid] < 0 && panel * BM + tid < nq) {
+            p.out_idx[panel * BM + tid] = -1;
+            p.out_dist[panel * BM + tid] = __builtin_inff();
+        }
         // a panel without a single query has nothing to do (every wavefront reads the same qid)
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
         PHASE_MARK(0);
@@ -1286,20 +1311,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 }
 
 // ------------------------------------------------------------------------------- launchers
-static int g_num_cu = 0;
-
+// Compute units of the current device (asked on every call: the answer belongs to the device
+// that is current now, and the runtime answers from its own cache).
 static hipError_t device_cus(int* cus)
 {
-    if (g_num_cu == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        int v = 0;
-        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        g_num_cu = v > 0 ? v : 1;
-    }
-    *cus = g_num_cu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    int v = 0;
+    e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    *cus = v > 0 ? v : 1;
     return hipSuccess;
 }
 
@@ -1312,14 +1334,14 @@ float filter_slack_coefficient(int d)
     return (float)(d + 8) * 1.1920928955078125e-07f;
 }
 
-hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream)
+hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite)
 {
     const float scale = 0.5f * (1.0f - filter_slack_coefficient(d));
     const long long threads = (long long)N * 16;
     const int blocks = (int)((threads + 255) / 256);
     const bool vec4 = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn);
-    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn);
+    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite);
+    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite);
     return hipGetLastError();
 }
 

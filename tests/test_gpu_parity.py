@@ -35,7 +35,7 @@ def pair_dist64(X, i, j):
     i, j = np.broadcast_arrays(np.asarray(i), np.asarray(j))
     out = np.empty(i.shape, dtype=np.float64)
     flat_i, flat_j, flat_o = i.reshape(-1), j.reshape(-1), out.reshape(-1)
-    step = 1 << 18
+    step = max(1024, (1 << 24) // max(1, X.shape[1]))          # ~128 MB of float64 per gathered operand
     for s in range(0, flat_i.size, step):
         diff = X[flat_i[s:s + step]].astype(np.float64) - X[flat_j[s:s + step]].astype(np.float64)
         flat_o[s:s + step] = np.einsum("nt,nt->n", diff, diff)
@@ -272,14 +272,102 @@ def check_slhc(X, out, tie_free):
         sig_g, sig_o = cluster_signatures(children, N), cluster_signatures(ref["children"], N)
         # band: a few float32 ulps, the accuracy of a directly summed squared distance
         iso_o, iso_g = isolated_heights(ref["heights"], 1e-6), isolated_heights(heights, 1e-6)
-        assert iso_o.mean() > 0.9
+        n_tied = int((~iso_o).sum())
+        # (how many heights have a neighbour within the band grows like N^2 x band on any continuous data:
+        # it says where clusters may legitimately differ, not how much the trees do; that is the edge
+        # comparison below, whose budget is absolute)
+        print(f"  merge heights with a neighbour within 1e-6 relative (oracle): {n_tied} of {N - 1}", flush=True)
         assert np.isin(sig_o[iso_o], sig_g).all(), "an oracle cluster is missing from the GPU hierarchy"
         assert np.isin(sig_g[iso_g], sig_o).all(), "a GPU cluster is missing from the oracle hierarchy"
         assert np.array_equal(np.sort(sizes[iso_g & iso_o]), np.sort(ref["sizes"][iso_g & iso_o]))
+        # Edge sets: the two trees may differ only by exchanging edges whose float64 weights agree
+        # within what float32 resolves (each exchanged pair closes a cycle in which both are the heaviest
+        # edge up to rounding), and only a handful of such exchanges can exist on tie-free data.
         eg = {(a, b) for a, b in zip(src.tolist(), dst.tolist())}
         eo = {(a, b) for a, b in zip(ref["src"].tolist(), ref["dst"].tolist())}
-        assert len(eg ^ eo) <= 2 * max(1, (~iso_o).sum()), "edge set differs from the oracle's beyond near-ties"
+        only_g, only_o = sorted(eg - eo), sorted(eo - eg)
+        print(f"  tree edges not shared with the oracle's tree: {len(only_g)}", flush=True)
+        assert len(only_g) == len(only_o) <= max(2, N // 20000)
+        if only_g:
+            wg = np.sort(pair_dist64(X, [a for a, _ in only_g], [b for _, b in only_g]))
+            wo = np.sort(pair_dist64(X, [a for a, _ in only_o], [b for _, b in only_o]))
+            assert close(wg, wo, 2e-6).all(), "trees differ by more than an exchange of equal-weight edges"
     return out["stats"]
+
+
+def check_tree_properties(X, k, gi, out, rng, n_nn=20_000, n_pairs=300, n_weights=300_000):
+    """Checks of a returned tree and dendrogram that hold at any size, for inputs the oracle cannot
+    finish: the edges span without a cycle (the sizes must be those of a union over the returned
+    children), sampled weights are the float64 distances of their pairs, the nearest neighbour of
+    every sampled vertex is a tree edge (the first Boruvka round is exact), and no sampled near pair
+    is closer than the merge height of its lowest common ancestor (the cycle property)."""
+    N = X.shape[0]
+    src, dst, w = (out[n].cpu().numpy() for n in ("mst_src", "mst_dst", "mst_w"))
+    children, heights, sizes = (out[n].cpu().numpy() for n in ("children", "heights", "sizes"))
+    assert (src < dst).all() and (np.diff(w.astype(np.float64)) >= 0).all()
+    es = rng.choice(N - 1, size=min(n_weights, N - 1), replace=False)
+    assert close(w[es], pair_dist64(X, src[es], dst[es]), RTOL_DIST).all()
+    assert np.array_equal(heights, w)
+    # every tree edge joins two different clusters of the dendrogram built so far: replay the merges
+    assert sizes[-1] == N
+    counts = np.bincount(children.ravel(), minlength=2 * N - 1)
+    assert (counts[:2 * N - 2] == 1).all() and counts[2 * N - 2] == 0
+    assert (children[:, 0] < children[:, 1]).all()
+    assert (children < (N + np.arange(N - 1))[:, None]).all()
+    parent = np.arange(2 * N - 1)
+    sz = np.ones(2 * N - 1, dtype=np.int64)
+    parent[children[:, 0]] = N + np.arange(N - 1)
+    parent[children[:, 1]] = N + np.arange(N - 1)
+    for i in range(N - 1):
+        sz[N + i] = sz[children[i, 0]] + sz[children[i, 1]]
+    assert np.array_equal(sz[N:], sizes.astype(np.int64))
+    # the dendrogram is the one of the returned edges: edge i must join the two children of merge i.
+    # Checked on a sample by walking up from both end points to the first node created at or after i.
+    def node_at(v, i):
+        x = int(v)
+        while parent[x] != x and parent[x] < N + i:
+            x = int(parent[x])
+        return x
+    for i in rng.choice(N - 1, size=min(2000, N - 1), replace=False).tolist():
+        a, b = node_at(src[i], i), node_at(dst[i], i)
+        assert {a, b} == {int(children[i, 0]), int(children[i, 1])}, f"merge {i} does not join the ends of edge {i}"
+    # distinct edges (with N-1 of them and the union replay above: a spanning tree)
+    assert np.unique(src.astype(np.int64) * N + dst).size == N - 1
+    # every vertex's nearest neighbour is a tree edge, unless another tree edge of the same weight
+    # may stand in for it (exact duplicates: zero-weight ties)
+    edge_keys = set((src.astype(np.int64) * N + dst).tolist())
+    vs = rng.choice(N, size=min(n_nn, N), replace=False)
+    nn = gi[vs, 0].astype(np.int64)
+    lo, hi = np.minimum(vs, nn), np.maximum(vs, nn)
+    missing = [(int(a), int(b)) for a, b in zip(lo, hi) if int(a) * N + int(b) not in edge_keys]
+    if missing:
+        # allowed only among ties: then v has a tree edge of exactly the same weight
+        tree_min = np.full(N, np.inf)
+        np.minimum.at(tree_min, src, w)
+        np.minimum.at(tree_min, dst, w)
+        for a, b in missing:
+            dab = float(pair_dist64(X, [a], [b])[0])
+            assert tree_min[a] <= dab * (1 + 1e-6) + ATOL0 and tree_min[b] <= dab * (1 + 1e-6) + ATOL0, \
+                f"nearest-neighbour pair ({a},{b}) at {dab} is not covered by the tree"
+    # cycle property on sampled near pairs: d(a,b) >= height of the lowest common ancestor
+    def lca_height(a, b):
+        seen = set()
+        x = int(a)
+        while True:
+            seen.add(x)
+            if parent[x] == x:
+                break
+            x = int(parent[x])
+        y = int(b)
+        while y not in seen:
+            y = int(parent[y])
+        return float(heights[y - N])
+
+    pa = rng.integers(0, N, size=n_pairs)
+    pb = gi[pa, rng.integers(0, k, size=n_pairs)]          # near pairs are the ones that could violate it
+    d_ab = pair_dist64(X, pa, pb)
+    for a, b, dab in zip(pa, pb, d_ab):
+        assert lca_height(a, b) <= dab * (1 + 1e-5) + ATOL0
 
 
 SLHC_CASES = [
@@ -675,6 +763,8 @@ def test_c5_full_size_pruned_equals_every_tile(lib):
     assert int(b["sizes"][-1]) == N
     # the 1 % exact copies give at least that many zero-weight tree edges
     assert int((w == 0.0).sum()) >= 15_000
+    print("c5 full: tree properties", flush=True)
+    check_tree_properties(X, k, gi, b, np.random.default_rng(57))
 
 
 # ----------------------------------------------------------------------------- full size (headline)
@@ -715,50 +805,189 @@ def test_headline_full_size_properties(lib):
     for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
         assert torch.equal(out[name_], brute[name_]), name_
     del brute
-    src, dst, w = (out[n].cpu().numpy() for n in ("mst_src", "mst_dst", "mst_w"))
-    children, heights, sizes = (out[n].cpu().numpy() for n in ("children", "heights", "sizes"))
-    assert (src < dst).all() and (np.diff(w.astype(np.float64)) >= 0).all()
-    es = rng.choice(N - 1, size=300_000, replace=False)
-    assert close(w[es], pair_dist64(X, src[es], dst[es]), RTOL_DIST).all()
-    assert np.array_equal(heights, w)
-    # spanning + linkage invariants through the returned dendrogram
-    assert sizes[-1] == N
-    counts = np.bincount(children.ravel(), minlength=2 * N - 1)
-    assert (counts[:2 * N - 2] == 1).all() and counts[2 * N - 2] == 0
-    assert (children[:, 0] < children[:, 1]).all()
-    assert (children < (N + np.arange(N - 1))[:, None]).all()
-    # the sizes must be those of the union-find over the returned edges (=> acyclic, spanning)
-    parent = np.arange(2 * N - 1)
-    sz = np.ones(2 * N - 1, dtype=np.int64)
-    parent[children[:, 0]] = N + np.arange(N - 1)
-    parent[children[:, 1]] = N + np.arange(N - 1)
-    for i in range(N - 1):
-        sz[N + i] = sz[children[i, 0]] + sz[children[i, 1]]
-    assert np.array_equal(sz[N:], sizes.astype(np.int64))
-    # every vertex's nearest neighbour is a tree edge (first Boruvka round is exact)
-    edge_keys = set((src.astype(np.int64) * N + dst).tolist())
-    vs = rng.choice(N, size=20_000, replace=False)
-    nn = gi[vs, 0].astype(np.int64)
-    lo, hi = np.minimum(vs, nn), np.maximum(vs, nn)
-    assert all(int(a) * N + int(b) in edge_keys for a, b in zip(lo, hi))
-    # cycle property on sampled pairs: d(a,b) >= height of the lowest common ancestor
-    up = parent
+    check_tree_properties(X, k, gi, out, rng)
 
-    def lca_height(a, b):
-        seen = set()
-        x = int(a)
-        while True:
-            seen.add(x)
-            if up[x] == x:
-                break
-            x = int(up[x])
-        y = int(b)
-        while y not in seen:
-            y = int(up[y])
-        return float(heights[y - N])
 
-    pa = rng.integers(0, N, size=300)
-    pb = gi[pa, rng.integers(0, k, size=300)]          # near pairs are the ones that could violate it
-    d_ab = pair_dist64(X, pa, pb)
-    for a, b, dab in zip(pa, pb, d_ab):
-        assert lca_height(a, b) <= dab * (1 + 1e-5)
+# ----------------------------------------------------------------------------- full size (c2, c4)
+def test_c2_full_size_tree_against_prim(lib):
+    """c2 at its full size (100k x 64, k=32): the whole tree and dendrogram against the oracle's dense
+    Prim (about a minute of host time), through both the pruned and the every-tile path."""
+    X, _, k = gen.make("c2")
+    Xd = torch.from_numpy(X).cuda()
+    print("c2 full: slhc on the GPU, then the oracle's Prim on the host", flush=True)
+    out = lib.slhc(Xd, k)
+    brute = lib.slhc(Xd, k, prune=False)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(out[name_], brute[name_]), name_
+    check_slhc(X, out, tie_free=True)
+
+
+def test_c4_full_size_properties(lib):
+    """c4 at its full size (250k x 784, k=16), the launch configuration of the streaming sweep kernel
+    with several panels per workgroup: sampled rows of the k-NN graph against the oracle, sampled
+    reported pairs recomputed, and the tree checked through the properties that hold at any size."""
+    X, _, k = gen.make("c4")
+    N = X.shape[0]
+    Xd = torch.from_numpy(X).cuda()
+    print("c4 full: knn", flush=True)
+    idx, dist = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    gi, gd = idx.cpu().numpy(), dist.cpu().numpy()
+    rng = np.random.default_rng(44)
+    rows = rng.choice(N, size=256, replace=False)
+    check_knn(X, k, gi[rows], gd[rows], rows=rows, min_exact=0.999)
+    pr = rng.integers(0, N, size=200_000)
+    pc = rng.integers(0, k, size=200_000)
+    assert close(gd[pr, pc], pair_dist64(X, pr, gi[pr, pc]), RTOL_DIST).all()
+    assert (np.diff(gd.astype(np.float64), axis=1) >= 0).all()
+    assert not (gi == np.arange(N)[:, None]).any()
+    assert gi.min() >= 0 and gi.max() < N
+    print("c4 full: slhc", flush=True)
+    out = lib.slhc(Xd, k)
+    print("stats", out["stats"], flush=True)
+    T = (N + 127) // 128
+    assert out["stats"]["knn_tile_steps"] == T * T          # the streaming kernel counts its tile steps too
+    check_tree_properties(X, k, gi, out, rng, n_weights=100_000)
+
+
+# ----------------------------------------------------------------------------- streaming kernel, many panels
+# More than 512 query panels (65 536 rows): every workgroup of the streaming sweep kernel (d > 128 or
+# d % 4 != 0) then loops over several work items.  All list widths of that kernel are instantiated.
+@pytest.mark.parametrize("N,d,k", [(70_000, 132, 16), (70_000, 132, 33), (66_500, 30, 20), (66_000, 30, 5),
+                                   (66_000, 130, 1)])
+def test_streaming_kernel_many_panels(lib, N, d, k):
+    print(f"streaming sweep N={N} d={d} k={k}", flush=True)
+    rng = np.random.default_rng(N + d + k)
+    centres = rng.uniform(-10, 10, size=(40, d))
+    X = (centres[rng.integers(0, 40, size=N)] + rng.standard_normal((N, d))).astype(np.float32)
+    gi, gd = gpu_knn(lib, X, k)
+    assert gi.min() >= 0 and gi.max() < N
+    step = 10_000
+    for s0 in range(0, N, step):                      # every reported pair, in float64
+        r = np.arange(s0, min(N, s0 + step))
+        assert close(gd[r], pair_dist64(X, r[:, None], gi[r]), RTOL_DIST).all()
+    assert (np.diff(gd.astype(np.float64), axis=1) >= 0).all()
+    rows = rng.choice(N, size=256, replace=False)
+    rows[:4] = [0, 65_535, 65_536, N - 1]             # first and last panels of the first and second pass
+    check_knn(X, k, gi[rows], gd[rows], rows=rows, min_exact=0.999)
+
+
+def test_streaming_1nn_many_query_panels(lib):
+    """The k = 1 variants of the streaming kernel with more than 512 query panels: the cross-colour 1-NN
+    over all rows and the two-matrix 1-NN, sampled rows against the oracle."""
+    N, d = 68_000, 132
+    rng = np.random.default_rng(5)
+    centres = rng.uniform(-10, 10, size=(30, d))
+    lab = rng.integers(0, 30, size=N)
+    X = (centres[lab] + rng.standard_normal((N, d))).astype(np.float32)
+    colour = (lab % 7).astype(np.int32)
+    print("streaming cross 1-NN, all rows", flush=True)
+    gi, gd = lib.cross_1nn(torch.from_numpy(X).cuda(), torch.from_numpy(colour).cuda())
+    torch.cuda.synchronize()
+    gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+    assert gi.min() >= 0 and gi.max() < N and (colour[gi] != colour).all()
+    assert close(gd, pair_dist64(X, np.arange(N), gi), RTOL_DIST).all()
+    rows = rng.choice(N, size=300, replace=False)
+    rows[:3] = [0, 65_536, N - 1]
+    oi, od = oracle.cross_1nn(X, colour, rows.astype(np.int64))
+    assert close(gd[rows], od, RTOL_DIST).all()
+    assert (gi[rows] == oi).mean() >= 0.99
+    print("streaming two-matrix 1-NN, 68 000 queries", flush=True)
+    Y = (centres[rng.integers(0, 30, size=3000)] + rng.standard_normal((3000, d))).astype(np.float32)
+    fi, fd = lib.fused_1nn(torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda())
+    torch.cuda.synchronize()
+    fi, fd = fi.cpu().numpy(), fd.cpu().numpy()
+    assert fi.min() >= 0 and fi.max() < 3000
+    XY = np.concatenate([X, Y])
+    assert close(fd, pair_dist64(XY, np.arange(N), fi + N), RTOL_DIST).all()
+    col2 = np.concatenate([np.zeros(N, np.int32), np.ones(3000, np.int32)])
+    oi, od = oracle.cross_1nn(XY, col2, rows.astype(np.int64))
+    assert close(fd[rows], od, RTOL_DIST).all()
+    assert (fi[rows] == oi - N).mean() >= 0.99
+
+
+# ----------------------------------------------------------------------------- two-phase connection rounds
+def test_split_connection_rounds_are_identical(lib):
+    """SLHC_SPLIT_ROUNDS runs every pruned connection round of 256 rows or more in two phases (a sample
+    of the row panels first, the other rows under the thresholds that leaves): the tree must equal the
+    every-tile path's bit for bit on seeded random shapes, and the oracle's on the small ones."""
+    rng = np.random.default_rng(777)
+    split_seen = 0
+    for case in range(20):
+        N = int(rng.integers(600, 25_000)) if case % 3 else int(rng.integers(600, 3000))
+        d = int(rng.choice([4, 8, 16, 32, 64, 100, 128]))
+        k = int(rng.integers(1, 33))
+        nb = int(rng.integers(2, 120))
+        spread = float(rng.choice([3.0, 20.0, 1000.0]))
+        sigma = float(rng.choice([0.05, 1.0, 3.0]))
+        centres = rng.uniform(-spread, spread, size=(nb, d))
+        X = (centres[rng.integers(0, nb, size=N)] + sigma * rng.standard_normal((N, d))).astype(np.float32)
+        ties = False
+        if rng.random() < 0.3:
+            m = N // 10
+            X[rng.integers(0, N, size=m)] = X[rng.integers(0, N, size=m)]
+            ties = True
+        print(f"split rounds case {case}: N={N} d={d} k={k} blobs={nb} spread={spread} sigma={sigma} ties={ties}", flush=True)
+        Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+        a = lib.slhc(Xd, k, prune=False)
+        b = lib.slhc(Xd, k, prune=True, split_rounds=True)
+        c = lib.slhc(Xd, k, prune=True)
+        for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+            assert torch.equal(a[name_], b[name_]), name_
+            assert torch.equal(a[name_], c[name_]), name_
+        # a split round drops the rows the first phase made unnecessary, so it queries fewer rows
+        if b["stats"]["connect_query_rows"] != c["stats"]["connect_query_rows"]:
+            split_seen += 1
+        if N <= 3000:
+            check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
+    print("cases in which the split changed the number of queried rows:", split_seen, flush=True)
+    assert split_seen >= 3
+
+
+# ----------------------------------------------------------------------------- non-finite input, bad rows
+@pytest.mark.parametrize("bad", [float("nan"), float("inf"), -float("inf"), 3e20])
+def test_nonfinite_rows(lib, bad):
+    """A row with a NaN, an infinity or a squared norm beyond float32: the synchronous entry points
+    return SLHC_NONFINITE (5); the asynchronous k-NN never writes an index outside -1 .. N-1, never
+    lists the bad row, and gives every other row the list it has without that row."""
+    X, _, k = gen.make("c1", n=3000)
+    N = X.shape[0]
+    Xb = X.copy()
+    Xb[1234, 3] = bad
+    Xd = torch.from_numpy(Xb).cuda()
+    for prune in (True, False):
+        with pytest.raises(lib.SlhcError) as e:
+            lib.slhc(Xd, k, prune=prune)
+        assert e.value.status == 5
+    with pytest.raises(lib.SlhcError) as e:
+        lib.knn_graph(Xd, k, prune=True)
+    assert e.value.status == 5
+    idx, dist = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    gi = idx.cpu().numpy()
+    assert gi.min() >= -1 and gi.max() < N
+    others = np.arange(N) != 1234
+    assert not (gi[others] == 1234).any()
+    Xf = X.copy()
+    Xf[1234] = 1e4                                     # far from everything: in nobody's list either
+    ri, rd = gpu_knn(lib, Xf, k)
+    assert np.array_equal(gi[others], ri[others])
+    assert np.array_equal(dist.cpu().numpy()[others], rd[others])
+    # the library is unharmed: the clean input still works
+    check_slhc(X, lib.slhc(torch.from_numpy(X).cuda(), k), tie_free=True)
+
+
+def test_cross_1nn_rows_out_of_range(lib):
+    """Entries of the device row list outside [0, N) are not dereferenced and are answered with -1, +inf;
+    the other rows are answered as usual (both sweep kernels)."""
+    for d in (16, 33):
+        X = np.random.default_rng(d).standard_normal((2000, d)).astype(np.float32)
+        colour = (np.arange(2000) % 5).astype(np.int32)
+        rows = np.array([5, -1, 1999, 2000, 17, 2**31 - 1, -2**31, 700] + list(range(300)), dtype=np.int32)
+        gi, gd = lib.cross_1nn(torch.from_numpy(X).cuda(), torch.from_numpy(colour).cuda(), torch.from_numpy(rows).cuda())
+        torch.cuda.synchronize()
+        gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+        ok = (rows >= 0) & (rows < 2000)
+        assert (gi[~ok] == -1).all() and np.isinf(gd[~ok]).all()
+        oi, od = oracle.cross_1nn(X, colour, rows[ok].astype(np.int64))
+        assert np.array_equal(gi[ok], oi) and close(gd[ok], od, RTOL_DIST).all()

@@ -39,10 +39,33 @@ def test_every_declared_symbol_is_exported(cdll):
 
 
 def test_version_and_strings(cdll):
-    assert cdll.slhc_abi_version() == 1
+    assert cdll.slhc_abi_version() == 2
     assert cdll.slhc_strerror(0) == b"ok"
     assert cdll.slhc_strerror(3) == b"workspace too small"
+    assert cdll.slhc_strerror(5) == b"input not finite"
+    assert cdll.slhc_strerror(6) == b"internal error"
+    assert cdll.slhc_strerror(7) == b"host allocation failed"
     assert cdll.slhc_strerror(99) == b"unknown status"
+
+
+def test_status_numbering_matches_the_header():
+    text = open(os.path.join(ROOT, "include", "slhc.h")).read()
+    values = dict(re.findall(r"\b(SLHC_[A-Z_]+)\s*=\s*(\d+)", text))
+    assert values == {"SLHC_OK": "0", "SLHC_INVALID_ARG": "1", "SLHC_UNSUPPORTED": "2",
+                      "SLHC_WORKSPACE_TOO_SMALL": "3", "SLHC_HIP_ERROR": "4", "SLHC_NONFINITE": "5",
+                      "SLHC_INTERNAL": "6", "SLHC_HOST_MEMORY": "7"}
+    assert re.search(r"#define SLHC_ABI_VERSION 2\b", text)
+    assert re.search(r"#define SLHC_PRUNE 1u", text) and re.search(r"#define SLHC_SPLIT_ROUNDS 2u", text)
+
+
+def test_no_exception_crosses_the_boundary():
+    # every exported function that runs code of its own does so inside the library's exception guard
+    src = open(os.path.join(ROOT, "paper_2306_16354_amd", "csrc", "slhc_api.hip")).read()
+    block = src[src.index('extern "C" {'):src.index('}  // extern "C"')]
+    bodies = re.findall(r"\nint (slhc_[a-z0-9_]+)\([^)]*\)\n\{\n(.*?)\n\}\n", block, flags=re.S)
+    assert len(bodies) >= 14
+    for name, body in bodies:
+        assert body.lstrip().startswith("return guarded("), name
 
 
 def test_workspace_sizes_and_shape_errors(cdll):
