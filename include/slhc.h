@@ -29,7 +29,8 @@
  *     memory: the synchronous entry points (slhc_slhc*, slhc_csr_msf, and slhc_knn_graph_opt with
  *     SLHC_PRUNE) allocate pinned staging buffers and HIP events for the duration of the call
  *     (slhc_slhc: 20 bytes per row for the host dendrogram pass) and free them before returning.
- *     The library keeps no mutable state between calls other than the thread-local error text.
+ *     The library keeps no mutable state between calls other than the thread-local error text
+ *     (and the fixed scratch array of slhc_knn_graph_static, see there).
  *   - Calls that share a workspace must not overlap in time.  Calls on different streams with
  *     different workspaces and outputs are independent.
  */
@@ -130,6 +131,22 @@ int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k,
 int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k,
                        int32_t* nbr_idx, float* nbr_dist,
                        void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
+ * slhc_knn_graph for callers that cannot allocate and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and the same
+ * result as slhc_knn_graph, bit for bit; the scratch they need (a block of counters and one
+ * float per row) is a fixed device array inside the library of 256 + 4 * SLHC_STATIC_MAX_ROWS
+ * bytes, which every GPU the library runs on holds until the process ends.  The call allocates
+ * and frees nothing, on the device or on the host (its first call on a device looks up the
+ * array's address).  N > SLHC_STATIC_MAX_ROWS is rejected with SLHC_UNSUPPORTED.
+ * All calls on one GPU share that array: two calls that overlap in time on one GPU (different
+ * streams or threads) race; calls in order on one stream are safe.  Asynchronous on `stream`.
+ * The counters are cleared by a kernel, not a memset node, so the call may be captured.
+ */
+#define SLHC_STATIC_MAX_ROWS 1048576
+int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k,
+                          int32_t* nbr_idx, float* nbr_dist, void* stream);
 
 /*
  * Cross-component 1-NN (paper Sec. 3.1.2, Alg. "Fused 1-NN", used by Alg. "connect_graph").

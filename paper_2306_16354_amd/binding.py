@@ -33,6 +33,7 @@ class _Stats(ctypes.Structure):
 
 SLHC_PRUNE = 1
 SLHC_SPLIT_ROUNDS = 2
+SLHC_STATIC_MAX_ROWS = 1048576
 
 
 def library_path():
@@ -55,6 +56,8 @@ def load_library():
     lib.slhc_knn_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
     lib.slhc_knn_graph.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp]
     lib.slhc_knn_graph_opt.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp, ctypes.c_uint32]
+    lib.slhc_knn_graph_static.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+    lib.slhc_knn_graph_static.restype = ctypes.c_int
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
     lib.slhc_cross_1nn.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
@@ -134,6 +137,16 @@ def knn_graph(X, k, out=None, workspace=None, prune=False):
     _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream(),
                                   SLHC_PRUNE if prune else 0))
+    return idx, dist
+
+
+def knn_graph_static(X, k, out):
+    """slhc_knn_graph_static: slhc_knn_graph on the library's fixed scratch array; the caller passes the
+    output tensors (idx int32 [N,k], dist float32 [N,k]) and nothing is allocated."""
+    X = _device_matrix(X)
+    N, d = X.shape
+    idx, dist = out
+    _check(load_library().slhc_knn_graph_static(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(), _stream()))
     return idx, dist
 
 

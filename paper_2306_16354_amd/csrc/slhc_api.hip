@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <exception>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -543,6 +544,34 @@ void build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* 
     }
 }
 
+// ---- scratch of slhc_knn_graph_static: the workspace of the unpruned k-NN path (counters + one
+// half norm per row) for up to SLHC_STATIC_MAX_ROWS rows, as a fixed device array.  Every GPU the
+// library runs on holds its own copy at its own address until the process ends; host code never
+// uses the array's name as an address, only what hipGetSymbolAddress returns for the current device.
+constexpr size_t STATIC_SCRATCH_BYTES = 256 + (size_t)SLHC_STATIC_MAX_ROWS * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) { set_err("device ordinal %d beyond %d", dev, MAX_DEVICES - 1); return SLHC_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) { set_err("hipGetSymbolAddress returned a null address"); return SLHC_HIP_ERROR; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLHC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -595,6 +624,27 @@ int slhc_knn_graph(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr
 {
     return guarded([&]() -> int {
         return slhc_knn_graph_opt(X, N, d, k, nbr_idx, nbr_dist, workspace, workspace_bytes, stream, 0u);
+    });
+}
+
+int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, float* nbr_dist,
+                          void* stream)
+{
+    return guarded([&]() -> int {
+        if (!X || !nbr_idx || !nbr_dist) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        const int rc = check_shape(N, d, k, true);
+        if (rc != SLHC_OK) return rc;
+        if (N > (int64_t)SLHC_STATIC_MAX_ROWS) {
+            set_err("N=%lld exceeds SLHC_STATIC_MAX_ROWS=%lld of the fixed scratch array; use slhc_knn_graph with a workspace",
+                    (long long)N, (long long)SLHC_STATIC_MAX_ROWS);
+            return SLHC_UNSUPPORTED;
+        }
+        void* ptr = nullptr;
+        const int rs = static_scratch(&ptr);
+        if (rs != SLHC_OK) return rs;
+        KnnWs ws(ptr, N, d, false);                 // counters (cleared by run_knn) + half norms (all N written)
+        if (ws.bytes > STATIC_SCRATCH_BYTES) { set_err("scratch layout %zu > %zu bytes", ws.bytes, STATIC_SCRATCH_BYTES); return SLHC_INTERNAL; }
+        return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), 0u);
     });
 }
 

@@ -29,7 +29,7 @@ def test_header_declares_the_expected_entry_points():
                  "slhc_knn_workspace_bytes", "slhc_last_error", "slhc_strerror", "slhc_abi_version",
                  "slhc_knn_graph_opt", "slhc_slhc_opt", "slhc_flat_clusters", "slhc_fused_1nn", "slhc_csr_msf",
                  "slhc_flat_clusters_workspace_bytes", "slhc_fused_1nn_workspace_bytes",
-                 "slhc_csr_msf_workspace_bytes"):
+                 "slhc_csr_msf_workspace_bytes", "slhc_knn_graph_static"):
         assert must in names
 
 
@@ -87,6 +87,7 @@ def test_workspace_sizes_and_shape_errors(cdll):
 def test_null_pointers_are_rejected_before_any_device_work(cdll):
     assert cdll.slhc_knn_graph(None, 10, 4, 2, None, None, None, 0, None) == 1
     assert cdll.slhc_slhc(None, 10, 4, 2, None, None, None, None, None, None, None, None, 0, None) == 1
+    assert cdll.slhc_knn_graph_static(None, 10, 4, 2, None, None, None) == 1
     assert cdll.slhc_cross_1nn(None, 10, 4, None, None, 5, None, None, None, 0, None) == 1
 
 
