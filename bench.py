@@ -8,8 +8,12 @@ already resident in HBM.  Prints ONE JSON line:
   value      fused k-NN distance pairs per second = N^2 / (norm kernel + k-NN sweep kernel time),
              kernel times taken with HIP events on the launch stream inside every timed step
   ms_per_step   wall time of the whole step (the end-to-end single-linkage seconds x 1000)
-  roofline   the fused k-NN sweep against the fp32 MFMA peak (2*d FLOP per ordered pair)
-  cpu_baseline  the CPU oracle's brute-force k-NN on a bounded sample of query rows
+  roofline   the fused k-NN sweep against the fp32 MFMA peak (2*d FLOP per ordered pair); also against
+             the rate a register-only fp32 MFMA loop sustains in the same run (empirical_peak)
+  roofline_connect / roofline_forest   the connection sweeps (MFMA) and the Boruvka rounds (HBM)
+  cpu_baseline  the CPU oracle's brute-force k-NN on a bounded sample of query rows, and its dense Prim +
+             dendrogram on the small workload and on a scaled-down copy of this one, next to the GPU
+             path's seconds on the same inputs
   pruned     the same workload through the default entry point (tile pruning on), outside the
              timed region: end-to-end seconds, stage times and the share of tile steps multiplied
 
@@ -115,6 +119,8 @@ def main():
     def mean(name):
         return float(np.mean([s[name] for s in stats]))
 
+    empirical_tflops = slhc.probe_fp32_mfma(dev)       # register-only MFMA loop, same process, right after the steps
+
     knn_kernel_ms = mean("ms_knn_kernel")
     knn_ms = knn_kernel_ms + mean("ms_norm_kernel")
     pairs = float(N) * float(N)
@@ -154,19 +160,34 @@ def main():
             "traffic": None,
             "launch_ms": knn_kernel_ms,
             "algorithmic_flop_per_launch": flops,
+            "empirical_peak": empirical_tflops,
+            "frac_of_empirical_peak": achieved_tflops / empirical_tflops,
+            "empirical_peak_note": "TFLOP/s of a register-only v_mfma_f32_32x32x2_f32 loop (4 accumulator blocks "
+                                   "per wavefront, 8 wavefronts per CU) measured in this run: what the chip "
+                                   "sustains at the clocks it holds under MFMA load",
         },
         "input_generation_s": gen_s,
     }
-    # HBM traffic of the sweep launch is not measurable from here; it comes from the committed
-    # rocprofv3 counter runs of this same workload (profiles/traffic.json), when there is one
+    # HBM traffic is not measurable from inside the run; it comes from the committed rocprofv3 counter runs
+    # of this same workload (profiles/traffic.json: one entry per kernel, keyed by workload and kernel name,
+    # FETCH_SIZE + WRITE_SIZE scaled by what the same counters read for a plain copy of known size)
+    traffic_table = {}
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
-            t = json.load(f).get(args.workload)
-        if t and t["N"] == N and t["d"] == d and t["k"] == k:
-            line["roofline"]["traffic"] = t["fetch_bytes_per_launch"] + t["write_bytes_per_launch"]
-            line["roofline"]["traffic_unit"] = "bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated)"
+            for ent in json.load(f).get("entries", []):
+                if ent.get("workload") == args.workload and ent["N"] == N and ent["d"] == d and ent["k"] == k:
+                    traffic_table[ent["role"]] = ent
     except (OSError, ValueError, KeyError):
         pass
+
+    def attach_traffic(obj, role):
+        ent = traffic_table.get(role)
+        if ent:
+            obj["traffic"] = ent["fetch_bytes"] + ent["write_bytes"]
+            obj["traffic_unit"] = ent["per"]
+            obj["traffic_kernel"] = ent["kernel"]
+
+    attach_traffic(line["roofline"], "knn_sweep")
     if not args.knn_only:
         line["stages_ms"] = {n: mean(n) for n in ("ms_knn", "ms_norm_kernel", "ms_knn_kernel", "ms_boruvka",
                                                   "ms_connect", "ms_connect_kernels", "ms_sort",
@@ -180,7 +201,9 @@ def main():
             ct = 2.0 * d * cq * N / (mean("ms_connect_kernels") * 1e-3) / 1e12
             line["roofline_connect"] = {"kernel": "sweep_kernel (cross-component 1-NN)", "bound": "mfma",
                                         "achieved": ct, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                                        "frac": ct / PEAK_FP32_MFMA_TFLOPS, "traffic": None}
+                                        "frac": ct / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                                        "frac_of_empirical_peak": ct / empirical_tflops}
+            attach_traffic(line["roofline_connect"], "connect_sweeps")
 
     if not args.knn_only:
         # graph / Boruvka stage against the HBM roofline: per round every list entry (4 B index) and the
@@ -195,6 +218,7 @@ def main():
                                        "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                        "frac": gbs / PEAK_HBM_GBS, "traffic": None,
                                        "algorithmic_bytes": forest_bytes, "ms": fms, "rounds": int(rounds)}
+            attach_traffic(line["roofline_forest"], "forest_rounds")
 
     if not args.knn_only and not args.no_pruned_leg:
         # the default entry point (tile pruning on) on the same input, outside the timed region
@@ -251,6 +275,31 @@ def main():
             "sample": f"fp64 brute-force k-NN of {rows.size} seeded query rows against all {N} rows "
                       f"of the same workload ({c1 - c0:.1f} s)",
         }
+        if not args.knn_only:
+            # the oracle's whole tree (dense Prim + sort + union-find dendrogram) beside the GPU path on the
+            # same inputs: the small workload in full, and this workload scaled down to what Prim
+            # finishes in a few seconds (its cost grows with N^2 d)
+            tree = []
+            scaled_rows = int(min(N, max(2000, (6.0e10 / d) ** 0.5)))
+            for wname, rows_ in (("c1", None), (args.workload, scaled_rows)):
+                Xs, _, ks = gen.make(wname, n=rows_)
+                if args.k is not None and wname == args.workload:
+                    ks = min(args.k, Xs.shape[0] - 1)
+                Xsd = torch.from_numpy(Xs).to(dev)
+                slhc.slhc(Xsd, ks)
+                torch.cuda.synchronize()
+                g0 = time.perf_counter()
+                slhc.slhc(Xsd, ks)
+                torch.cuda.synchronize()
+                g1 = time.perf_counter()
+                o0 = time.perf_counter()
+                oracle.slhc(Xs)
+                o1 = time.perf_counter()
+                tree.append({"workload": f"{wname}: N={Xs.shape[0]} d={Xs.shape[1]} k={ks}",
+                             "oracle_seconds": o1 - o0, "gpu_slhc_seconds": g1 - g0})
+            line["cpu_baseline"]["tree"] = tree
+            line["cpu_baseline"]["tree_note"] = ("oracle = dense Prim + sort + union-find on the host cores; the full "
+                                                 "workload would cost the oracle about (N / scaled N)^2 times its scaled time")
     print(json.dumps(line))
 
 

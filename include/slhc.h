@@ -149,6 +149,18 @@ int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k,
                           int32_t* nbr_idx, float* nbr_dist, void* stream);
 
 /*
+ * Measurement aid for the roofline report of the distance tiles (paper Sec. 3.1.1, the tile contraction
+ * of Alg. "Fused k-NN"): runs the MFMA instruction the sweep kernels use (v_mfma_f32_32x32x2_f32, four
+ * independent accumulator blocks per wavefront, two workgroups of four wavefronts per compute unit) on
+ * operands that stay in registers, for about 40 ms, and reports the rate it sustained.
+ *
+ *   tflops     HOST   out  10^12 floating-point operations per second
+ *   workspace  DEVICE      at least 256 bytes
+ * Synchronous.
+ */
+int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Cross-component 1-NN (paper Sec. 3.1.2, Alg. "Fused 1-NN", used by Alg. "connect_graph").
  *
  * For each query row rows[q], q < m: the row j with colour[j] != colour[rows[q]] that minimises

@@ -58,6 +58,8 @@ def load_library():
     lib.slhc_knn_graph_opt.argtypes = [vp, i64, i32, i32, vp, vp, vp, sz, vp, ctypes.c_uint32]
     lib.slhc_knn_graph_static.argtypes = [vp, i64, i32, i32, vp, vp, vp]
     lib.slhc_knn_graph_static.restype = ctypes.c_int
+    lib.slhc_probe_fp32_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp, sz, vp]
+    lib.slhc_probe_fp32_mfma.restype = ctypes.c_int
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
     lib.slhc_cross_1nn.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
@@ -148,6 +150,14 @@ def knn_graph_static(X, k, out):
     idx, dist = out
     _check(load_library().slhc_knn_graph_static(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(), _stream()))
     return idx, dist
+
+
+def probe_fp32_mfma(device="cuda"):
+    """slhc_probe_fp32_mfma: TFLOP/s a register-only fp32 MFMA loop sustains on the current device."""
+    ws = _workspace(256, device)
+    out = ctypes.c_double(0.0)
+    _check(load_library().slhc_probe_fp32_mfma(ctypes.byref(out), ws.data_ptr(), ws.numel(), _stream()))
+    return out.value
 
 
 def cross_1nn(X, colour, rows=None, m=None):

@@ -23,7 +23,8 @@ struct ForestState {
     uint32_t* min_lb;            // [N] per component: min lower-bound bits over unknown vertices
     int32_t* hook;               // [N] per component: component it attaches to this round
     int32_t* qlist;              // [N] rows sent to the cross-component 1-NN
-    int32_t* counters;           // [4]: 0 = queries this round, 1 = edges so far, 2 = jump flag,
+    int32_t* counters;           // [4]: 0 = queries this round, 1 = edges so far, 2 = hook chains not yet
+                                 //      followed to their end (cleared by forest_round_reset),
                                  //      3 = site of the first failed index check (0 = none)
     int32_t* e_lo;               // [N-1] committed edges
     int32_t* e_hi;
@@ -49,8 +50,11 @@ hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n,
                                hipStream_t s);
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
 hipError_t forest_commit(const ForestState& f, hipStream_t s);
-hipError_t forest_jump(const ForestState& f, hipStream_t s);       // one pointer-doubling step
-hipError_t forest_relabel(const ForestState& f, hipStream_t s);
+// Every component root follows the hooks up to `steps` components far and hooks itself there; with
+// `flag`, counters[2] is set when some root has not reached the end of its chain.
+hipError_t forest_jump(const ForestState& f, int steps, bool flag, hipStream_t s);
+// colour[v] = hook[colour[v]]; with only_if_converged the kernel does nothing while counters[2] != 0.
+hipError_t forest_relabel(const ForestState& f, bool only_if_converged, hipStream_t s);
 
 // CSR input (offsets [V+1], indices [E], weights [E]).  forest_csr_check flags malformed arrays or
 // weights that are negative / not finite in f.counters[3]; forest_csr_scan fills cand_w / cand_u with

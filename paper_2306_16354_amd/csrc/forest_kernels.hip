@@ -48,6 +48,57 @@ __device__ inline void min_into(unsigned long long* slot, unsigned long long v)
     if (v < *reinterpret_cast<volatile unsigned long long*>(slot)) atomicMin(slot, v);
 }
 
+// Minimum of `v` over the lanes that share a component, one atomic per component and wavefront.  In the
+// late rounds most vertices belong to a few large components, and one atomic per vertex on those few
+// words serialises (measured: 0.7 ms for one kernel at N = 1M).  The first two distinct colours of the
+// wavefront are reduced across lanes; lanes of any further colour fall back to their own atomic, so a
+// wavefront of 64 different colours (the first round) costs two short passes, not 64.
+__device__ inline void wave_min_into(uint32_t* slots, int c, uint32_t v, bool active)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned long long todo = __ballot(active);
+#pragma unroll 1
+    for (int pass = 0; pass < 2 && todo; ++pass) {
+        const int leader = __builtin_ctzll(todo);
+        const int c0 = __shfl(c, leader);
+        const bool mine = active && c == c0;
+        uint32_t m = mine ? v : 0xffffffffu;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint32_t other = (uint32_t)__shfl_xor((int)m, o);
+            m = other < m ? other : m;
+        }
+        if (lane == leader) min_into(&slots[c0], m);
+        const unsigned long long served = __ballot(mine);
+        todo &= ~served;
+        active = active && !mine;
+    }
+    if (active) min_into(&slots[c], v);
+}
+
+// Slot of this thread among the threads of the grid that pass `mine`, behind *counter: one atomic per
+// workgroup (per-vertex or per-wavefront atomics on the one counter word serialise: 15 600 of them took
+// 0.18 ms at N = 1M).  Every thread of the workgroup must call it.
+template <int THREADS>
+__device__ inline int block_append(bool mine, int32_t* counter)
+{
+    __shared__ int wave_count[THREADS / 64];
+    __shared__ int wave_base[THREADS / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long mask = __ballot(mine);
+    if (lane == 0) wave_count[wave] = __popcll(mask);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < THREADS / 64; ++w) { wave_base[w] = total; total += wave_count[w]; }
+        const int base = total > 0 ? atomicAdd(counter, total) : 0;
+        for (int w = 0; w < THREADS / 64; ++w) wave_base[w] += base;
+    }
+    __syncthreads();
+    const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+    return mine ? wave_base[wave] + pre : -1;
+}
+
 __global__ void __launch_bounds__(TB) k_forest_init(ForestState f)
 {
     const int v = blockIdx.x * TB + threadIdx.x;
@@ -66,81 +117,95 @@ __global__ void __launch_bounds__(TB) k_round_reset(ForestState f)
     f.best_w[v] = INF_BITS;
     f.best_e[v] = ~0ull;
     f.min_lb[v] = INF_BITS;
-    if (v == 0) f.counters[0] = 0;
+    if (v == 0) { f.counters[0] = 0; f.counters[2] = 0; }
 }
 
-// G lanes per vertex (G = power of two >= k): lane j looks at list entry j.
+// G lanes per vertex walk its list from ptr[v] on, G entries at a time, until an entry of another colour
+// turns up: the lists are ascending, so that entry is the vertex's lightest listed outgoing edge.  Most
+// vertices find it in their first step (in the first round entry 0 always is foreign), and ptr only moves
+// forward over the rounds, so the colour gathers summed over all rounds stay near N * (k + G * rounds)
+// instead of N * k * rounds with one lane per entry.
 template <int G>
 __global__ void __launch_bounds__(TB) k_scan_lists(ForestState f)
 {
+    // the scan for the next round is enqueued before the host knows that the tree is complete
+    if (f.counters[1] >= f.N - 1) return;
     const int gid = (int)(((long long)blockIdx.x * TB + threadIdx.x) / G);
     const int j = threadIdx.x & (G - 1);
     const int lane = threadIdx.x & 63;
     const bool live = gid < f.N;
     const int v = live ? gid : 0;
     const int c = f.colour[v];
-    const int p = f.ptr[v];
-    bool foreign = false;
-    if (live && j < f.k && j >= p) {
-        const int u = f.nbr_idx[(size_t)v * f.k + j];
-        if (in_range(u, f.N)) foreign = f.colour[u] != c;
-        else report(f, 1);
+    int found = -1;
+    for (int base = f.ptr[v];; base += G) {
+        const bool more = live && base < f.k && found < 0;        // the same for the G lanes of a vertex
+        if (!__any(more)) break;
+        bool foreign = false;
+        const int e = base + j;
+        if (more && e < f.k) {
+            const int u = f.nbr_idx[(size_t)v * f.k + e];
+            if (in_range(u, f.N)) foreign = f.colour[u] != c;
+            else report(f, 1);
+        }
+        unsigned long long mask = __ballot(foreign);
+        mask = (mask >> (lane & ~(G - 1))) & ((1ull << G) - 1ull);
+        if (more && mask) found = base + __builtin_ctzll(mask);
     }
-    unsigned long long mask = __ballot(foreign);
-    if constexpr (G < 64) mask = (mask >> (lane & ~(G - 1))) & ((1ull << G) - 1ull);
-    if (!live || j != 0) return;
-    if (!in_range(c, f.N)) { report(f, 2); return; }
-    if (mask) {
-        const int pn = __builtin_ctzll(mask);
-        const float w = f.nbr_dist[(size_t)v * f.k + pn];
-        f.ptr[v] = pn;
-        f.cand_w[v] = w;
-        f.cand_u[v] = f.nbr_idx[(size_t)v * f.k + pn];
-        min_into(&f.best_w[c], __float_as_uint(w));
-        return;
+    const bool head = live && j == 0;
+    bool exact = false, bounded = false;
+    uint32_t wbits = INF_BITS;
+    if (head && !in_range(c, f.N)) report(f, 2);
+    else if (head) {
+        if (found >= 0) {
+            const float w = f.nbr_dist[(size_t)v * f.k + found];
+            f.ptr[v] = found;
+            f.cand_w[v] = w;
+            f.cand_u[v] = f.nbr_idx[(size_t)v * f.k + found];
+            wbits = __float_as_uint(w);
+            exact = true;
+        } else {
+            f.ptr[v] = f.k;
+            const int eu = f.ext_idx[v];
+            const float ed = f.ext_dist[v];
+            if (eu >= f.N) report(f, 3);
+            else if (eu >= 0 && f.colour[eu] != c) {      // cached answer still leads out of the component
+                f.cand_w[v] = ed;
+                f.cand_u[v] = eu;
+                wbits = __float_as_uint(ed);
+                exact = true;
+            } else {
+                // lower bounds on v's nearest foreign point: its k-th list distance, and whatever the last
+                // cross-component query left in ext_dist (an exact answer that has since joined v's
+                // component, or the component threshold a truncated search was run under; 0 when never queried)
+                float lb = f.nbr_dist[(size_t)v * f.k + f.k - 1];
+                if (ed > lb) lb = ed;
+                f.cand_w[v] = lb;
+                f.cand_u[v] = -1;
+                wbits = __float_as_uint(lb);
+                bounded = true;
+            }
+        }
     }
-    f.ptr[v] = f.k;
-    const int eu = f.ext_idx[v];
-    const float ed = f.ext_dist[v];
-    if (eu >= f.N) { report(f, 3); return; }
-    if (eu >= 0 && f.colour[eu] != c) {          // cached answer still leads out of the component
-        f.cand_w[v] = ed;
-        f.cand_u[v] = eu;
-        min_into(&f.best_w[c], __float_as_uint(ed));
-        return;
-    }
-    // lower bounds on v's nearest foreign point: its k-th list distance, and whatever the last
-    // cross-component query left in ext_dist (an exact answer that has since joined v's component,
-    // or the component threshold a truncated search was run under; 0 when never queried)
-    float lb = f.nbr_dist[(size_t)v * f.k + f.k - 1];
-    if (ed > lb) lb = ed;
-    f.cand_w[v] = lb;
-    f.cand_u[v] = -1;
-    min_into(&f.min_lb[c], __float_as_uint(lb));
+    wave_min_into(f.best_w, c, wbits, exact);
+    wave_min_into(f.min_lb, c, wbits, bounded);
 }
 
 // Vertices that only know a lower bound and whose bound does not exceed their component's best
 // exact weight must be queried (<=, so that weight ties are resolved by the edge order).
-__global__ void __launch_bounds__(TB) k_classify(ForestState f)
+constexpr int TB_WIDE = 1024;
+__global__ void __launch_bounds__(TB_WIDE) k_classify(ForestState f)
 {
-    const int v = blockIdx.x * TB + threadIdx.x;
+    const int v = blockIdx.x * TB_WIDE + threadIdx.x;
     bool need = false;
+    if (f.counters[1] >= f.N - 1) return;                // tree complete (workgroup-uniform)
     if (v < f.N && f.cand_u[v] < 0) {
         const int c = f.colour[v];
         if (in_range(c, f.N)) need = __float_as_uint(f.cand_w[v]) <= f.best_w[c];
         else report(f, 4);
     }
-    const unsigned long long mask = __ballot(need);
-    if (!mask) return;
-    const int lane = threadIdx.x & 63;
-    const int leader = __builtin_ctzll(mask);
-    int base = 0;
-    if (lane == leader) base = atomicAdd(&f.counters[0], __popcll(mask));
-    base = __shfl(base, leader);
+    const int slot = block_append<TB_WIDE>(need, &f.counters[0]);
     if (need) {
-        const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
-                          __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
-        if (in_range(base + pre, f.N)) f.qlist[base + pre] = v;
+        if (in_range(slot, f.N)) f.qlist[slot] = v;
         else report(f, 5);
     }
 }
@@ -157,29 +222,39 @@ __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32
                                                       const uint32_t* __restrict__ thresholds)
 {
     const int q = blockIdx.x * TB + threadIdx.x;
-    if (q >= nq) return;
-    const int v = qrows[q];
-    const int u = q_idx[q];
-    const float w = q_dist[q];
-    if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) { report(f, 6); return; }
-    const int c = f.colour[v];
-    if (thresholds) {
-        const uint32_t fb = thresholds[c];
-        if (!(u >= 0 && __float_as_uint(w) <= fb)) {
-            const float F = __uint_as_float(fb);
-            const float old = f.ext_dist[v];
-            f.ext_idx[v] = -1;
-            f.ext_dist[v] = F > old ? F : old;
-            f.cand_u[v] = -1;
-            f.cand_w[v] = F;
-            return;
+    bool found = false;
+    int c = 0;
+    float w = 0.f;
+    if (q < nq) {
+        const int v = qrows[q];
+        const int u = q_idx[q];
+        w = q_dist[q];
+        if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) report(f, 6);
+        else {
+            c = f.colour[v];
+            bool exact = true;
+            if (thresholds) {
+                const uint32_t fb = thresholds[c];
+                if (!(u >= 0 && __float_as_uint(w) <= fb)) {
+                    const float F = __uint_as_float(fb);
+                    const float old = f.ext_dist[v];
+                    f.ext_idx[v] = -1;
+                    f.ext_dist[v] = F > old ? F : old;
+                    f.cand_u[v] = -1;
+                    f.cand_w[v] = F;
+                    exact = false;
+                }
+            }
+            if (exact) {
+                f.ext_idx[v] = u;
+                f.ext_dist[v] = w;
+                f.cand_u[v] = u;
+                f.cand_w[v] = w;
+                found = u >= 0;
+            }
         }
     }
-    f.ext_idx[v] = u;
-    f.ext_dist[v] = w;
-    f.cand_u[v] = u;
-    f.cand_w[v] = w;
-    if (u >= 0) min_into(&f.best_w[c], __float_as_uint(w));
+    wave_min_into(f.best_w, c, __float_as_uint(w), found);
 }
 
 // slot of this lane among the lanes of `mask` behind *counter (one atomic per wavefront)
@@ -249,48 +324,103 @@ __global__ void __launch_bounds__(TB) k_select_edges(ForestState f)
 // One thread per component root: append the component's edge (once per undirected edge) and
 // record which component it attaches to.  Two components that chose the same edge keep the
 // smaller root.
-__global__ void __launch_bounds__(TB) k_commit(ForestState f)
+constexpr int COMMIT_ITEMS = 8;        // vertices per thread: one atomic on the edge counter per 8192 vertices
+__global__ void __launch_bounds__(TB_WIDE) k_commit(ForestState f)
 {
-    const int v = blockIdx.x * TB + threadIdx.x;
-    if (v >= f.N || f.colour[v] != v) return;
-    const uint32_t wb = f.best_w[v];
-    if (wb == INF_BITS) { f.hook[v] = v; return; }
-    const unsigned long long e = f.best_e[v];
-    const int lo = (int)(e >> 32), hi = (int)(e & 0xffffffffull);
-    if (!in_range(lo, f.N) || !in_range(hi, f.N)) { report(f, 8); f.hook[v] = v; return; }
-    const int clo = f.colour[lo], chi = f.colour[hi];
-    const int other = (clo == v) ? chi : clo;
-    if (!in_range(other, f.N) || other == v || (clo != v && chi != v)) { report(f, 9); f.hook[v] = v; return; }
-    const bool mutual = (f.best_w[other] == wb) && (f.best_e[other] == e);
-    if (!mutual || v < other) {
-        const int slot = atomicAdd(&f.counters[1], 1);
-        if (slot < f.N - 1) {
-            f.e_lo[slot] = lo;
-            f.e_hi[slot] = hi;
-            f.e_w[slot] = __uint_as_float(wb);
+    __shared__ int wave_count[TB_WIDE / 64];
+    __shared__ int wave_base[TB_WIDE / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int lo[COMMIT_ITEMS], hi[COMMIT_ITEMS];
+    uint32_t wbits[COMMIT_ITEMS];
+    unsigned int adds = 0;             // bit i: vertex i of this thread appends its component's edge
+#pragma unroll
+    for (int i = 0; i < COMMIT_ITEMS; ++i) {
+        const long long vv = ((long long)blockIdx.x * COMMIT_ITEMS + i) * TB_WIDE + threadIdx.x;
+        lo[i] = hi[i] = 0;
+        wbits[i] = INF_BITS;
+        if (vv >= f.N) continue;
+        const int v = (int)vv;
+        if (f.colour[v] != v) continue;
+        const uint32_t wb = f.best_w[v];
+        int hook = v;
+        if (wb != INF_BITS) {
+            const unsigned long long e = f.best_e[v];
+            const int elo = (int)(e >> 32), ehi = (int)(e & 0xffffffffull);
+            if (!in_range(elo, f.N) || !in_range(ehi, f.N)) report(f, 8);
+            else {
+                const int clo = f.colour[elo], chi = f.colour[ehi];
+                const int other = (clo == v) ? chi : clo;
+                if (!in_range(other, f.N) || other == v || (clo != v && chi != v)) report(f, 9);
+                else {
+                    const bool mutual = (f.best_w[other] == wb) && (f.best_e[other] == e);
+                    if (!mutual || v < other) { adds |= 1u << i; lo[i] = elo; hi[i] = ehi; wbits[i] = wb; }
+                    hook = (mutual && v < other) ? v : other;
+                }
+            }
         }
+        f.hook[v] = hook;
     }
-    f.hook[v] = (mutual && v < other) ? v : other;
+    // exclusive prefix of the per-thread counts over the workgroup
+    const int mine = __popc(adds);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_count[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < TB_WIDE / 64; ++w) { wave_base[w] = total; total += wave_count[w]; }
+        const int base = total > 0 ? atomicAdd(&f.counters[1], total) : 0;
+        for (int w = 0; w < TB_WIDE / 64; ++w) wave_base[w] += base;
+    }
+    __syncthreads();
+    int slot = wave_base[wave] + incl - mine;
+#pragma unroll
+    for (int i = 0; i < COMMIT_ITEMS; ++i) {
+        if (!(adds & (1u << i))) continue;
+        if (slot < f.N - 1) {
+            f.e_lo[slot] = lo[i];
+            f.e_hi[slot] = hi[i];
+            f.e_w[slot] = __uint_as_float(wbits[i]);
+        }
+        ++slot;
+    }
 }
 
-__global__ void __launch_bounds__(TB) k_jump(ForestState f)
+// Every root follows the hooks up to `steps` components far and hooks itself to where it got; other
+// roots do the same at the same time, which is harmless: whatever a hook is replaced by is an ancestor
+// of what it held.  With `flag` a root that has not reached the end of its chain sets counters[2].
+// Two launches of 32 steps resolve chains of up to 1024 hooks; the host loops only beyond that.
+__global__ void __launch_bounds__(TB) k_jump(ForestState f, int steps, int flag)
 {
     const int v = blockIdx.x * TB + threadIdx.x;
     if (v >= f.N || f.colour[v] != v) return;
-    const int h = f.hook[v];
+    int h = f.hook[v];
     if (!in_range(h, f.N)) { report(f, 10); return; }
-    const int hh = f.hook[h];
-    if (!in_range(hh, f.N)) { report(f, 11); return; }
-    if (hh != h) {
-        f.hook[v] = hh;
-        f.counters[2] = 1;
+    bool at_root = false;
+    for (int i = 0; i < steps; ++i) {
+        const int hh = *reinterpret_cast<volatile int32_t*>(&f.hook[h]);
+        if (!in_range(hh, f.N)) { report(f, 11); return; }
+        if (hh == h) { at_root = true; break; }
+        h = hh;
+    }
+    f.hook[v] = h;
+    if (flag && !at_root) {
+        const int hh = *reinterpret_cast<volatile int32_t*>(&f.hook[h]);
+        if (hh != h) atomicOr(&f.counters[2], 1);
     }
 }
 
-__global__ void __launch_bounds__(TB) k_relabel(ForestState f)
+// With `only_if_converged` the kernel does nothing while counters[2] says that some hook chain has not
+// been followed to its end (the host then finishes the chains and launches it again).
+__global__ void __launch_bounds__(TB) k_relabel(ForestState f, int only_if_converged)
 {
     const int v = blockIdx.x * TB + threadIdx.x;
     if (v >= f.N) return;
+    if (only_if_converged && f.counters[2] != 0) return;
     const int c = f.colour[v];
     if (!in_range(c, f.N)) { report(f, 12); return; }
     const int r = f.hook[c];
@@ -332,6 +462,10 @@ __global__ void __launch_bounds__(TB) k_csr_scan(const int32_t* __restrict__ off
 {
     const int v = blockIdx.x * TB + threadIdx.x;
     if (v >= f.N) return;
+    // f.ptr[v] != 0: an earlier round found every neighbour of v in v's own component.  Components only
+    // grow, so v never has an outgoing edge again; its cand_u stays -1 and its row is not read any more
+    // (after a few rounds that is most vertices).
+    if (f.ptr[v] != 0) return;
     const int c = f.colour[v];
     if (!in_range(c, f.N)) { report(f, 25); return; }
     int o0 = offsets[v], o1 = offsets[v + 1];
@@ -350,6 +484,7 @@ __global__ void __launch_bounds__(TB) k_csr_scan(const int32_t* __restrict__ off
     f.cand_u[v] = bu;
     f.cand_w[v] = __uint_as_float(bw);
     if (bu >= 0) min_into(&f.best_w[c], bw);
+    else f.ptr[v] = 1;
 }
 
 #define LAUNCH1(kern, n, s, ...)                                                       \
@@ -363,13 +498,15 @@ hipError_t forest_round_reset(const ForestState& f, hipStream_t s) { LAUNCH1(k_r
 
 hipError_t forest_scan_lists(const ForestState& f, hipStream_t s)
 {
-    if (f.k <= 8) LAUNCH1(k_scan_lists<8>, (long long)f.N * 8, s, f);
-    if (f.k <= 16) LAUNCH1(k_scan_lists<16>, (long long)f.N * 16, s, f);
-    if (f.k <= 32) LAUNCH1(k_scan_lists<32>, (long long)f.N * 32, s, f);
-    LAUNCH1(k_scan_lists<64>, (long long)f.N * 64, s, f);
+    if (f.k <= 2) LAUNCH1(k_scan_lists<2>, (long long)f.N * 2, s, f);
+    LAUNCH1(k_scan_lists<4>, (long long)f.N * 4, s, f);
 }
 
-hipError_t forest_classify(const ForestState& f, hipStream_t s) { LAUNCH1(k_classify, f.N, s, f); }
+hipError_t forest_classify(const ForestState& f, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_classify, dim3((f.N + TB_WIDE - 1) / TB_WIDE), dim3(TB_WIDE), 0, s, f);
+    return hipGetLastError();
+}
 
 hipError_t forest_apply_queries(const ForestState& f, const int32_t* qrows, const int32_t* q_idx,
                                 const float* q_dist, int nq, const uint32_t* thresholds, hipStream_t s)
@@ -390,9 +527,14 @@ hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n,
 }
 
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }
-hipError_t forest_commit(const ForestState& f, hipStream_t s) { LAUNCH1(k_commit, f.N, s, f); }
-hipError_t forest_jump(const ForestState& f, hipStream_t s) { LAUNCH1(k_jump, f.N, s, f); }
-hipError_t forest_relabel(const ForestState& f, hipStream_t s) { LAUNCH1(k_relabel, f.N, s, f); }
+hipError_t forest_commit(const ForestState& f, hipStream_t s)
+{
+    const int per_block = TB_WIDE * COMMIT_ITEMS;
+    hipLaunchKernelGGL(k_commit, dim3((f.N + per_block - 1) / per_block), dim3(TB_WIDE), 0, s, f);
+    return hipGetLastError();
+}
+hipError_t forest_jump(const ForestState& f, int steps, bool flag, hipStream_t s) { LAUNCH1(k_jump, f.N, s, f, steps, flag ? 1 : 0); }
+hipError_t forest_relabel(const ForestState& f, bool only_if_converged, hipStream_t s) { LAUNCH1(k_relabel, f.N, s, f, only_if_converged ? 1 : 0); }
 
 hipError_t forest_csr_check(const int32_t* offsets, const int32_t* indices, const float* weights, int V, int E,
                             int32_t* counters, hipStream_t s)

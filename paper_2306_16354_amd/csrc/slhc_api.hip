@@ -648,6 +648,27 @@ int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k, int32
     });
 }
 
+int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return guarded([&]() -> int {
+        if (!tflops || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (workspace_bytes < 256) { set_err("workspace %zu < 256 bytes", workspace_bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        EventPair ev;
+        HIP_TRY(ev.create());
+        double flop = 0.0;
+        HIP_TRY(slhc::launch_mfma_probe(2000, static_cast<float*>(workspace), s, &flop));      // warm-up: clocks settle
+        HIP_TRY(hipEventRecord(ev.a, s));
+        HIP_TRY(slhc::launch_mfma_probe(40000, static_cast<float*>(workspace), s, &flop));     // ~40 ms
+        HIP_TRY(hipEventRecord(ev.b, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const float ms = ev.ms();
+        if (!(ms > 0.f)) { set_err("probe timing failed"); return SLHC_HIP_ERROR; }
+        *tflops = flop / (ms * 1e-3) / 1e12;
+        return SLHC_OK;
+    });
+}
+
 int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes)
 {
     return guarded([&]() -> int {
@@ -773,17 +794,25 @@ int slhc_csr_msf(const int32_t* offsets, const int32_t* indices, const float* we
             HIP_TRY(slhc::forest_csr_scan(offsets, indices, weights, (int)E, f, s));
             HIP_TRY(slhc::forest_select_edges(f, s));
             HIP_TRY(slhc::forest_commit(f, s));
-            int jumps = 0;
-            do {
-                hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
-                HIP_TRY(hipGetLastError());
-                HIP_TRY(slhc::forest_jump(f, s));
-                HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-                HIP_TRY(hipStreamSynchronize(s));
-                if (++jumps > 64) { set_err("component hooks do not form a forest (is every edge stored in both rows with one weight?)"); return SLHC_INTERNAL; }
-                if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
-            } while (h_cnt[2] != 0);
-            HIP_TRY(slhc::forest_relabel(f, s));
+            HIP_TRY(slhc::forest_jump(f, 32, false, s));
+            HIP_TRY(slhc::forest_jump(f, 32, true, s));
+            HIP_TRY(slhc::forest_relabel(f, true, s));
+            HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+            if (h_cnt[2] != 0) {
+                // hook chains longer than the two device passes cover: finish them with the host in the loop
+                for (int jumps = 0; h_cnt[2] != 0; ++jumps) {
+                    if (jumps > 64) { set_err("component hooks do not form a forest (is every edge stored in both rows with one weight?)"); return SLHC_INTERNAL; }
+                    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
+                    HIP_TRY(hipGetLastError());
+                    HIP_TRY(slhc::forest_jump(f, 32, true, s));
+                    HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+                    HIP_TRY(hipStreamSynchronize(s));
+                    if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+                }
+                HIP_TRY(slhc::forest_relabel(f, false, s));
+            }
             if (h_cnt[1] < edges || h_cnt[1] > V - 1) { set_err("round left %d edges (had %d)", h_cnt[1], edges); return SLHC_INTERNAL; }
             if (h_cnt[1] == edges) break;                 // steady state: a spanning forest
             edges = h_cnt[1];
@@ -993,14 +1022,50 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     unsigned long long conn_steps_seen = 0;
     double prev_steps_per_panel = 0.0;     // tile steps per query panel in the last pruned round
     st.components_after_knn = 1;
-    while (edges < N - 1) {
-        if (st.boruvka_rounds >= max_rounds) { set_err("no single component after %d rounds", max_rounds); return SLHC_INTERNAL; }
-        ++st.boruvka_rounds;
+    // One read-back per round: the scan of the lists for round r+1 is enqueued right behind the relabelling
+    // of round r, so the counters that come back carry the edges committed so far, whether the hook
+    // chains were followed to their end, and the number of rows the next round has to query.
+    auto enqueue_scan = [&]() -> int {
         HIP_TRY(slhc::forest_round_reset(f, s));
         HIP_TRY(slhc::forest_scan_lists(f, s));
         HIP_TRY(slhc::forest_classify(f, s));
+        return SLHC_OK;
+    };
+    auto read_counters = [&]() -> int {
         HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
+        if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+        return SLHC_OK;
+    };
+    rc = enqueue_scan();
+    if (rc != SLHC_OK) return rc;
+    for (;;) {
+        rc = read_counters();
+        if (rc != SLHC_OK) return rc;
+        if (st.boruvka_rounds > 0) {
+            if (h_cnt[2] != 0) {
+                // a hook chain longer than the two device passes cover (a path of > 1000 components): finish
+                // it with the host in the loop, relabel, and scan again under the final colours
+                for (int jumps = 0; h_cnt[2] != 0; ++jumps) {
+                    if (jumps > 64) { set_err("component hooks do not form a forest"); return SLHC_INTERNAL; }
+                    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
+                    HIP_TRY(hipGetLastError());
+                    HIP_TRY(slhc::forest_jump(f, 32, true, s));
+                    rc = read_counters();
+                    if (rc != SLHC_OK) return rc;
+                }
+                HIP_TRY(slhc::forest_relabel(f, false, s));
+                rc = enqueue_scan();
+                if (rc != SLHC_OK) return rc;
+                rc = read_counters();
+                if (rc != SLHC_OK) return rc;
+            }
+            if (h_cnt[1] <= edges || h_cnt[1] > N - 1) { set_err("round added %d edges (total %d)", h_cnt[1] - edges, h_cnt[1]); return SLHC_INTERNAL; }
+            edges = h_cnt[1];
+            if (edges == N - 1) break;
+        }
+        if (st.boruvka_rounds >= max_rounds) { set_err("no single component after %d rounds", max_rounds); return SLHC_INTERNAL; }
+        ++st.boruvka_rounds;
         const int nq = h_cnt[0];
         if (h_cnt[3] != 0 || nq < 0 || nq > N) { set_err("forest state check %d failed (nq=%d)", h_cnt[3], nq); return SLHC_INTERNAL; }
         if (nq > 0) {
@@ -1120,19 +1185,11 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
         }
         HIP_TRY(slhc::forest_select_edges(f, s));
         HIP_TRY(slhc::forest_commit(f, s));
-        int jumps = 0;
-        do {                                                  // pointer doubling to the new roots
-            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws.counters + 2), 1);
-            HIP_TRY(hipGetLastError());
-            HIP_TRY(slhc::forest_jump(f, s));
-            HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-            HIP_TRY(hipStreamSynchronize(s));
-            if (++jumps > 64) { set_err("component hooks do not form a forest"); return SLHC_INTERNAL; }
-            if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
-        } while (h_cnt[2] != 0);
-        HIP_TRY(slhc::forest_relabel(f, s));
-        if (h_cnt[1] <= edges || h_cnt[1] > N - 1) { set_err("round added %d edges (total %d)", h_cnt[1] - edges, h_cnt[1]); return SLHC_INTERNAL; }
-        edges = h_cnt[1];
+        HIP_TRY(slhc::forest_jump(f, 32, false, s));          // hooks -> new roots
+        HIP_TRY(slhc::forest_jump(f, 32, true, s));
+        HIP_TRY(slhc::forest_relabel(f, true, s));
+        rc = enqueue_scan();                                  // next round's scan; its counters are read at the top
+        if (rc != SLHC_OK) return rc;
     }
     HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));

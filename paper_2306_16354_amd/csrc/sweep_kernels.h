@@ -61,6 +61,9 @@ struct SweepParams {
 float filter_slack_coefficient(int d);
 // `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr);
+// Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
+// *flop receives the floating-point operations of the launch.  `sink`: one device float.
+hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);
 int sweep_grid_limit();   // upper bound of gridDim.x of a sweep launch (for sizing gap_ws); 0 on error
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream);
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);

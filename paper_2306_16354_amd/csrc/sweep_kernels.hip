@@ -1325,6 +1325,44 @@ static hipError_t device_cus(int* cus)
     return hipSuccess;
 }
 
+// Register-only fp32 MFMA loop: every wavefront chains v_mfma_f32_32x32x2_f32 on four independent
+// accumulator blocks (the instruction and the accumulator count of the sweep kernels) with operands that
+// never leave registers.  What it sustains is the rate the chip holds at its clocks under this load: the
+// practical ceiling of the distance tiles, next to the published peak.
+__global__ void __launch_bounds__(WG_THREADS, 2) mfma_probe_kernel(int iters, float seed, float* __restrict__ sink)
+{
+    v16f acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+    float a = seed + (float)(threadIdx.x & 7) * 1e-3f, c = seed * 0.5f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, c, acc[b], 0, 0, 0);
+        }
+    }
+    float total = 0.f;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) total += acc[b][r];
+    if (total == 123456.789f) sink[0] = total;          // keeps the chain alive; practically never taken
+}
+
+hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop)
+{
+    int cus = 0;
+    hipError_t e = device_cus(&cus);
+    if (e != hipSuccess) return e;
+    const int grid = 2 * cus;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(grid), dim3(WG_THREADS), 0, stream, iters, 1.0f, sink);
+    *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 2);
+    return hipGetLastError();
+}
+
 float filter_slack_coefficient(int d)
 {
     // The accumulator is a chain of d+1 round-to-nearest fused multiply-adds whose partial sums
