@@ -49,6 +49,9 @@ hipError_t forest_split_queries(const ForestState& f, const int32_t* list, int n
 hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n, int32_t* out, int32_t* count,
                                hipStream_t s);
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s);
+// sizes[c] += 1 for every entry c of colour[0..n) inside [0, bins); sizes zeroed by the caller.  One atomic
+// per colour and wavefront where neighbouring entries share their colour.
+hipError_t forest_component_sizes(const int32_t* colour, int n, int bins, int32_t* sizes, hipStream_t s);
 hipError_t forest_commit(const ForestState& f, hipStream_t s);
 // Every component root follows the hooks up to `steps` components far and hooks itself there; with
 // `flag`, counters[2] is set when some root has not reached the end of its chain.

@@ -210,12 +210,14 @@ __global__ void __launch_bounds__(TB_WIDE) k_classify(ForestState f)
     }
 }
 
-// `thresholds` (optional): the queries ran under their component's shared threshold
-// F = thresholds[colour], the lightest outgoing edge the lists already knew (a snapshot of best_w
-// taken before the sweep, so that the outcome does not depend on thread order).  An answer at distance <= F is the
-// query's exact nearest foreign row, because every candidate at most that far was examined.  Any
-// other query only learns that no foreign row is nearer than F: it keeps no candidate, and F becomes
-// its lower bound for the following rounds (components only grow).
+// `thresholds` (optional): the queries ran under their component's shared threshold, which started at the
+// lightest outgoing edge the lists already knew and which the sweep lowered whenever one of the
+// component's queries found a lighter one; thresholds[colour] is its value after the sweep, F.  A query's
+// tiles were filtered under values that were never below F, so every candidate at most F away was
+// examined: an answer at distance <= F is the query's exact nearest foreign row.  Any other query only
+// learns that no foreign row is nearer than F: it keeps no candidate, and F becomes its lower bound for the
+// following rounds (components only grow).  F = min(start value, lightest edge from a queried row of the
+// component to a foreign row) does not depend on the order in which the panels ran.
 __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32_t* __restrict__ qrows,
                                                       const int32_t* __restrict__ q_idx,
                                                       const float* __restrict__ q_dist, int nq,
@@ -428,6 +430,30 @@ __global__ void __launch_bounds__(TB) k_relabel(ForestState f, int only_if_conve
     f.colour[v] = r;
 }
 
+// Rows per component: sizes[c] += 1 for every row of colour c (entries outside [0, bins) are skipped;
+// sizes zeroed by the caller).  Meant for colours in a spatially coherent row order, where the lanes of a
+// wavefront share one or two colours: those are counted with one atomic each.
+__global__ void __launch_bounds__(TB) k_component_sizes(const int32_t* __restrict__ colour, int n, int bins,
+                                                        int32_t* __restrict__ sizes)
+{
+    const int i = blockIdx.x * TB + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int c = i < n ? colour[i] : -1;
+    bool active = (unsigned int)c < (unsigned int)bins;
+    unsigned long long todo = __ballot(active);
+#pragma unroll 1
+    for (int pass = 0; pass < 4 && todo; ++pass) {
+        const int leader = __builtin_ctzll(todo);
+        const int c0 = __shfl(c, leader);
+        const bool mine = active && c == c0;
+        const unsigned long long served = __ballot(mine);
+        if (lane == leader) atomicAdd(&sizes[c0], __popcll(served));
+        todo &= ~served;
+        active = active && !mine;
+    }
+    if (active) atomicAdd(&sizes[c], 1);
+}
+
 // ------------------------------------------------------------------------------- CSR graphs
 // Sec. 3.2 takes the graph in CSR form.  Input check: offsets monotone from 0 to E, indices in
 // range, weights finite and non-negative (the edge order compares weight bit patterns).  A failed
@@ -527,6 +553,10 @@ hipError_t forest_still_needed(const ForestState& f, const int32_t* list, int n,
 }
 
 hipError_t forest_select_edges(const ForestState& f, hipStream_t s) { LAUNCH1(k_select_edges, f.N, s, f); }
+hipError_t forest_component_sizes(const int32_t* colour, int n, int bins, int32_t* sizes, hipStream_t s)
+{
+    LAUNCH1(k_component_sizes, n, s, colour, n, bins, sizes);
+}
 hipError_t forest_commit(const ForestState& f, hipStream_t s)
 {
     const int per_block = TB_WIDE * COMMIT_ITEMS;

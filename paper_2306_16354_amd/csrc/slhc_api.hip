@@ -162,6 +162,16 @@ constexpr int64_t TWO_PHASE_MIN_ROWS = SLHC_TWO_PHASE_MIN_ROWS;
 #endif
 constexpr double TWO_PHASE_MIN_STEPS = SLHC_TWO_PHASE_MIN_STEPS;
 constexpr int TWO_PHASE_STRIDE = 16;
+// pruned connection sweeps lower a component's shared threshold to this multiple of the lightest edge its
+// queries have found so far (squared distance; see SweepParams::comp_lower_factor)
+#ifndef SLHC_LOWER_FACTOR
+#define SLHC_LOWER_FACTOR 1.0f
+#endif
+constexpr float LOWER_FACTOR = SLHC_LOWER_FACTOR;
+#ifndef SLHC_LOWER_MIN_ROWS
+#define SLHC_LOWER_MIN_ROWS 4096
+#endif
+constexpr int LOWER_MIN_ROWS = SLHC_LOWER_MIN_ROWS;
 constexpr int NESTED_K = 8;
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
 int first_level_pivots(int64_t N) { return (int)((N + 63) / 64); }
@@ -1078,6 +1088,10 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 const OrderWs& o = kws.order;
                 HIP_TRY(slhc::order_gather_i32(ws.colour, o.perm, o.Ns, (int)N, -1, o.colour_s, s));
                 HIP_TRY(slhc::order_tile_colours(o.colour_s, o.Ns, o.tile_colour, s));
+                // rows per component (vals_b is free until the edge sort): which components may lower
+                // their shared threshold during the sweep
+                HIP_TRY(slhc::order_fill_i32(reinterpret_cast<int32_t*>(ws.vals_b), (int)N, 0, s));
+                HIP_TRY(slhc::forest_component_sizes(o.colour_s, o.Ns, (int)N, reinterpret_cast<int32_t*>(ws.vals_b), s));
             }
             float ms_round_kernels = 0.f;
             // one cross-colour 1-NN sweep for `n` listed rows, and its answers applied to the forest
@@ -1100,9 +1114,16 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
                     p.tile_colour = o.tile_colour;
                     // thresholds shared by the queries of a component: what the forest already knows (a
-                    // snapshot, vals_a is free until the edge sort)
+                    // working copy that the sweep lowers further as its queries find lighter edges;
+                    // vals_a is free until the edge sort)
                     HIP_TRY(hipMemcpyAsync(ws.vals_a, ws.best_w, (size_t)N * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
                     p.comp_best = ws.vals_a;
+#ifndef SLHC_STUDY_NO_LOWERING
+                    p.comp_best_lower = ws.vals_a;      // lowered in place; forest_apply_queries reads the final values
+                    p.comp_lower_factor = LOWER_FACTOR;
+                    p.comp_size = reinterpret_cast<const int32_t*>(ws.vals_b);
+                    p.comp_lower_min_size = LOWER_MIN_ROWS;
+#endif
                     p.comp_count = (int)N;
                     p.panel_counter = reinterpret_cast<unsigned int*>(kws.counters + 8);
 #ifdef SLHC_PHASE_TIMERS

@@ -42,6 +42,24 @@ struct SweepParams {
     // foreign row is nearer than comp_best, which is all the caller may conclude.
     const unsigned int* comp_best;
     int comp_count;
+    // optional, the same array as comp_best: the sweep also lowers comp_best[c] (atomic minimum) whenever a
+    // query of colour c finds a foreign row nearer than it, and all queries of that colour run under the
+    // lowered value from then on.  The rule above then holds with the value the word has when the sweep has
+    // FINISHED: answers at distance <= that final value are exact, every other query only knows that no
+    // foreign row is nearer than it.  The final value is min(value at launch, lightest edge from any queried
+    // row of that colour to a foreign row), whatever the order in which the panels ran.
+    unsigned int* comp_best_lower;
+    // >= 1.  The word is lowered to comp_lower_factor times the lightest edge found, not to the edge itself:
+    // with factor 1 only the queries that tie with the component's lightest edge end with an exact answer,
+    // and all the others have to be asked again in a later round; a factor of 2 (in squared distance) keeps
+    // the answers of nearly all rows of a compact cluster exact while still cutting off everything beyond
+    // 1.4 times the distance to the nearest foreign row.
+    float comp_lower_factor;
+    // optional: comp_size[c] = rows of component c; only components of at least comp_lower_min_size rows
+    // lower their word.  A component that fits a few panels gains little from a falling threshold, and
+    // every row that ends without an exact answer has to be asked again in the next round.
+    const int32_t* comp_size;
+    int comp_lower_min_size;
     unsigned int* panel_counter;  // optional device word, zero at launch: panels are taken from it one at
                                   // a time instead of round-robin (use when panel costs differ widely)
     int own_tile_first;    // self-join in the same row order: start each panel at its own tile

