@@ -251,6 +251,11 @@ def main():
                                                         "ms_connect", "ms_connect_kernels", "ms_sort",
                                                         "ms_dendrogram", "ms_total")},
             }
+            for role in ("pruned_knn_sweep", "pruned_connect_sweeps"):
+                ent = traffic_table.get(role)
+                if ent:
+                    line["pruned"].setdefault("traffic", {})[role] = {
+                        "bytes": ent["fetch_bytes"] + ent["write_bytes"], "per": ent["per"], "kernel": ent["kernel"]}
 
     if not args.no_cpu_baseline:
         import oracle                                     # cpu_baseline leg only

@@ -174,7 +174,10 @@ constexpr float LOWER_FACTOR = SLHC_LOWER_FACTOR;
 constexpr int LOWER_MIN_ROWS = SLHC_LOWER_MIN_ROWS;
 constexpr int NESTED_K = 8;
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
-int first_level_pivots(int64_t N) { return (int)((N + 63) / 64); }
+#ifndef SLHC_PIVOT_STRIDE
+#define SLHC_PIVOT_STRIDE 64
+#endif
+int first_level_pivots(int64_t N) { return (int)((N + SLHC_PIVOT_STRIDE - 1) / SLHC_PIVOT_STRIDE); }
 // The reordered copy inserts padding rows so that well separated clusters start on a tile
 // boundary; padding is limited to N/2 rows.
 int64_t padded_rows_limit(int64_t N) { return N + N / 2 + 256; }
