@@ -48,46 +48,70 @@ __host__ __device__ inline size_t sweep_lds_bytes(int KL)
                     BM /*hq*/ + 8 /*wmax*/ + 8 /*next panel*/) * 4 + (size_t)BM * KL * 8 + (size_t)4 * QCAP * 2;
 }
 
+// Rows are read through pointers in the global address space: the re-evaluation runs in functions that
+// are real calls, where a plain pointer has lost its address space and every load would be a flat one.
+typedef const __attribute__((address_space(1))) float* global_floats;
+typedef const __attribute__((address_space(1))) int32_t* global_ints;
+
+// Features t .. t+3 of a row as one vector; features at or beyond d read as 0.  The address is clamped rather
+// than the load skipped, so that the loads of one round of group8_sqdist can all be in flight together.
+template <bool VEC4>
+__device__ inline v4f load_quad(global_floats row, int t, int d)
+{
+    v4f v;
+    if (VEC4) {
+        const bool live = t < d;
+        const v4f w = *reinterpret_cast<const __attribute__((address_space(1))) v4f*>(row + (live ? t : 0));
+        v = live ? w : v4f{0.f, 0.f, 0.f, 0.f};
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool live = t + e < d;
+            const float w = row[live ? t + e : 0];
+            v[e] = live ? w : 0.f;
+        }
+    }
+    return v;
+}
+
+__device__ inline float quad_sqdist(v4f va, v4f vb, float s)
+{
+    float e;
+    e = va[0] - vb[0]; s = __builtin_fmaf(e, e, s);
+    e = va[1] - vb[1]; s = __builtin_fmaf(e, e, s);
+    e = va[2] - vb[2]; s = __builtin_fmaf(e, e, s);
+    e = va[3] - vb[3]; s = __builtin_fmaf(e, e, s);
+    return s;
+}
+
 // sum_t (a_t - b_t)^2 over d features by a group of 8 adjacent lanes; every lane of the group returns
 // the total.  The features are cut into 64-wide slabs; lane g adds features 4g..4g+3 of every slab
 // into one accumulator and features 4(g+8)..4(g+8)+3 into a second one, in ascending t with fused
 // multiply-adds; each set of eight partial sums goes through an xor butterfly (1, 2, 4) and the two
 // totals are added last.  (a-b)^2 == (b-a)^2 exactly, so the result is symmetric in its arguments
 // bit for bit, and every code path that re-evaluates a pair uses this one order of additions.
+// (A feature beyond d contributes fma(0, 0, s) = s, so padding the last slab changes no bit.)
+// Two slabs are read per round, eight vector loads in flight at once: one memory round trip per 128
+// features.  Read one slab at a time, each waiting for its own data, a pair of 128-feature rows cost four
+// round trips in a row, and the rare path of every sweep was mostly that wait.
 template <bool VEC4>
-__device__ inline float group8_sqdist(const float* __restrict__ a, const float* __restrict__ b,
+__device__ inline float group8_sqdist(const float* __restrict__ a_, const float* __restrict__ b_,
                                       int d, int g, bool active)
 {
+    const global_floats a = (global_floats)a_;
+    const global_floats b = (global_floats)b_;
     float s0 = 0.f, s1 = 0.f;
     if (active) {
-        if (VEC4) {
-            for (int t = 4 * g; t < d; t += 64) {
-                const v4f va = *reinterpret_cast<const v4f*>(a + t);
-                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
-                float e;
-                e = va[0] - vb[0]; s0 = __builtin_fmaf(e, e, s0);
-                e = va[1] - vb[1]; s0 = __builtin_fmaf(e, e, s0);
-                e = va[2] - vb[2]; s0 = __builtin_fmaf(e, e, s0);
-                e = va[3] - vb[3]; s0 = __builtin_fmaf(e, e, s0);
-            }
-            for (int t = 4 * (g + 8); t < d; t += 64) {
-                const v4f va = *reinterpret_cast<const v4f*>(a + t);
-                const v4f vb = *reinterpret_cast<const v4f*>(b + t);
-                float e;
-                e = va[0] - vb[0]; s1 = __builtin_fmaf(e, e, s1);
-                e = va[1] - vb[1]; s1 = __builtin_fmaf(e, e, s1);
-                e = va[2] - vb[2]; s1 = __builtin_fmaf(e, e, s1);
-                e = va[3] - vb[3]; s1 = __builtin_fmaf(e, e, s1);
-            }
-        } else {
-            for (int t0 = 4 * g; t0 < d; t0 += 64) {
-                const int te = (t0 + 4 < d) ? t0 + 4 : d;
-                for (int t = t0; t < te; ++t) { const float e = a[t] - b[t]; s0 = __builtin_fmaf(e, e, s0); }
-            }
-            for (int t0 = 4 * (g + 8); t0 < d; t0 += 64) {
-                const int te = (t0 + 4 < d) ? t0 + 4 : d;
-                for (int t = t0; t < te; ++t) { const float e = a[t] - b[t]; s1 = __builtin_fmaf(e, e, s1); }
-            }
+        for (int base = 0; base < d; base += 128) {
+            const int t0 = base + 4 * g;
+            const v4f a00 = load_quad<VEC4>(a, t0, d), b00 = load_quad<VEC4>(b, t0, d);
+            const v4f a10 = load_quad<VEC4>(a, t0 + 32, d), b10 = load_quad<VEC4>(b, t0 + 32, d);
+            const v4f a01 = load_quad<VEC4>(a, t0 + 64, d), b01 = load_quad<VEC4>(b, t0 + 64, d);
+            const v4f a11 = load_quad<VEC4>(a, t0 + 96, d), b11 = load_quad<VEC4>(b, t0 + 96, d);
+            s0 = quad_sqdist(a00, b00, s0);
+            s0 = quad_sqdist(a01, b01, s0);
+            s1 = quad_sqdist(a10, b10, s1);
+            s1 = quad_sqdist(a11, b11, s1);
         }
     }
     s0 += __shfl_xor(s0, 1);
@@ -294,7 +318,7 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
         const int qrow = L.qid[wave * 32 + ql];
         const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
         const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
-        const int cid = (c_id && valid) ? c_id[cg] : cg;          // id that orders ties and is reported
+        const int cid = (c_id && valid) ? ((global_ints)c_id)[cg] : cg;   // id that orders ties and is reported
         const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
         const unsigned long long key = make_key(dist, cid);
         // a stale k-th entry is only larger than the current one, so this test never drops a
@@ -437,7 +461,7 @@ __device__ __attribute__((noinline)) void resolve_deferred(int qcount, const flo
         const int qrow = L.qid[wave * 32 + ql];
         const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
         const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
-        const int cid = (c_id && valid) ? c_id[cg] : cg;
+        const int cid = (c_id && valid) ? ((global_ints)c_id)[cg] : cg;
         const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
         const unsigned long long key = make_key(dist, cid);
         if constexpr (KL == 1) {
