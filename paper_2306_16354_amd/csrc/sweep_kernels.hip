@@ -196,8 +196,8 @@ extern __shared__ __align__(16) unsigned char sweep_smem[];
 // wavefront's queue (entry = query lane << 8 | candidate row within the tile).  `t` holds the
 // block's accumulators, `tag` the lane's query row (k-NN self-join: to skip itself; -1 when nothing
 // is to be skipped) or the lane's query colour (cross-colour 1-NN: to skip its own component).
-// Returns the new queue length, or -1 (nothing written) when the block does not fit: the caller
-// then resolves the queue and calls again.
+// Returns the new queue length, or -1 (nothing written) when the block might not fit: the caller then
+// resolves the queue and calls again with an empty one.
 template <int KL, bool MASKED>
 __device__ __attribute__((noinline)) int compact_block(v16f t, int b, float bound, int tag, int col0,
                                                        int colbuf, int N, int qcount)
@@ -210,87 +210,99 @@ __device__ __attribute__((noinline)) int compact_block(v16f t, int b, float boun
     const int lhalf = lane >> 5;
     unsigned short* myq = L.queues + wave * QCAP;
     const bool real_query = L.qid[wave * 32 + l32] >= 0;    // padding rows of the last panel
-    unsigned long long masks[16];
-    int total = 0;
+    // A wavefront instruction costs four cycles of the SIMD whatever it does, and this routine runs for every
+    // flagged block, so it is written for instruction count.  First one compare per accumulator row, whose
+    // ballots also bound the number of entries (if the bound fits the queue, nothing below can overflow; if it
+    // does not, the caller resolves the queue and calls again with an empty one, which always fits).  Then
+    // only the rows that hold a passing accumulator pay for the full test and the write.
+    unsigned long long rough[16];
+    int upper = 0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
+        rough[r] = __ballot(t[r] >= bound);
+        upper += __popcll(rough[r]);
+    }
+    if (qcount + upper > QCAP) return -1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (rough[r] == 0ull) continue;
         const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
         const int cg = col0 + cl;
         // candidates past the end or padding rows carry h = +inf, i.e. an accumulator of -inf
         bool pred = real_query && (t[r] >= bound) && (t[r] > -__builtin_inff()) && (cg < N);
         if (MASKED) pred = pred && (ccol[cl] != tag);
         else pred = pred && (cg != tag);
-        masks[r] = __ballot(pred);
-        total += __popcll(masks[r]);
-    }
-    if (qcount + total > QCAP) return -1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const unsigned long long mask = masks[r];
-        if (mask) {
-            const int cl = b * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-            const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
-                              __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
-            if ((mask >> lane) & 1ull) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
-            qcount += __popcll(mask);
-        }
+        const unsigned long long mask = __ballot(pred);
+        const int pre = __builtin_amdgcn_mbcnt_hi((unsigned int)(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo((unsigned int)mask, 0u));
+        if (pred) myq[qcount + pre] = (unsigned short)((l32 << 8) | cl);
+        qcount += __popcll(mask);
     }
     return qcount;
 }
 
-// group_list_insert: inserts the keys held by the lanes of `todo` (one bit per lane that holds an
-// accepted key and its query lane `ql`) into their queries' lists, 64/KL lists at a time: lane group
-// g = lane / KL serves the g-th pending key, one lane per list entry, so that a pass costs one LDS read,
-// one ballot and the shifted write whatever the number of lists.  Two pending keys of one query go to
-// different passes.  Per list: the key goes in front of the first entry that is not smaller, the
-// entries behind it move down by one and the last one drops out; nothing changes when the key does
-// not precede the last entry.  On change the query's filter bound is refreshed from the new k-th
-// entry: bound = h_q - worst/2.
-template <int KL>
-__device__ inline void group_list_insert(unsigned long long todo, unsigned long long key, int ql,
-                                         unsigned long long* mylists, int k, const float* hqs,
-                                         float* bounds, int lane)
+// group8_list_insert: the eight 8-lane groups of a wavefront each hold one re-evaluated pair (`key`, and the
+// query lane `ql` it belongs to, the same in all lanes of a group; `want`: the pair beat its query's k-th
+// entry when it was tested).  All eight keys go into their queries' sorted lists in one round: a group's
+// lane g holds entries g*E .. g*E+E-1 of the list (E = KL/8), counts how many of them precede the key, the
+// counts of the group give the key's position (E ballots, no reduction tree), every lane rebuilds its E
+// entries (the one before its first comes from the lane below through a DPP row shift) and writes them back;
+// the last entry drops out.  Two keys of one query cannot share a round: the higher group waits for the
+// next one, so a round costs one LDS read and one write per lane whatever the number of lists.  On change
+// the query's filter bound is refreshed from the new k-th entry: bound = h_q - worst/2.
+// (One lane per list entry and 64/KL lists per round, as this routine did before, needs four rounds for
+// eight keys at k = 32; the rounds, not the re-evaluation, were most of the rare path.)
+__device__ inline unsigned long long dpp_from_lane_below(unsigned long long v)
 {
-    constexpr int NG = 64 / KL;
-    const int g = lane / KL, l = lane % KL;
-    while (todo) {
-        unsigned long long rest = todo;
-        int picked_q[NG];
-        int mysrc = -1;
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned int)v, 0x111, 0xf, 0xf, false);          // row_shr:1
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned int)(v >> 32), 0x111, 0xf, 0xf, false);
+    return ((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo;
+}
+
+template <int KL>
+__device__ inline void group8_list_insert(bool want, unsigned long long key, int ql, unsigned long long* mylists,
+                                          int k, const float* hqs, float* bounds, int lane)
+{
+    static_assert(KL % 8 == 0, "one list is spread over the eight lanes of a group");
+    constexpr int E = KL / 8;
+    const int grp = lane >> 3, g8 = lane & 7;
+    unsigned long long pending = __ballot(want && g8 == 0);              // bit 8*grp: group grp still has its key
+    while (pending) {
+        // lane g of every group compares the group's query with group g's
+        const int other_q = __shfl(ql, g8 * 8);
+        const bool clash = g8 < grp && ((pending >> (g8 * 8)) & 1ull) && other_q == ql;
+        const unsigned long long clashes = __ballot(clash);
+        const bool go = ((pending >> (grp * 8)) & 1ull) && (((clashes >> (grp * 8)) & 0xffull) == 0ull);
+        unsigned long long* lst = mylists + (size_t)ql * KL + g8 * E;
+        unsigned long long old[E];
+        int cnt = 0;
 #pragma unroll
-        for (int j = 0; j < NG; ++j) {
-            picked_q[j] = -1;
-            if (rest) {
-                const int src = __builtin_ctzll(rest);
-                rest &= rest - 1;
-                const int q = __builtin_amdgcn_readlane(ql, src);
-                bool clash = false;
-#pragma unroll
-                for (int i = 0; i < j; ++i) clash = clash || (picked_q[i] == q);
-                if (!clash) {
-                    picked_q[j] = q;
-                    todo &= ~(1ull << src);
-                    if (g == j) mysrc = src;
-                }
-            }
+        for (int e = 0; e < E; ++e) {
+            old[e] = go ? lst[e] : ~0ull;
+            cnt += (g8 * E + e < k && old[e] < key) ? 1 : 0;
         }
-        const bool act = mysrc >= 0;
-        const int from = act ? mysrc : lane;
-        const unsigned int klo = (unsigned int)__shfl((int)(unsigned int)key, from);
-        const unsigned int khi = (unsigned int)__shfl((int)(unsigned int)(key >> 32), from);
-        const int myq = __shfl(ql, from);
-        const unsigned long long mykey = ((unsigned long long)khi << 32) | klo;
-        unsigned long long* lst = mylists + (size_t)myq * KL;
-        const unsigned long long old = (act && l < k) ? lst[l] : ~0ull;
-        const bool less = act && (l < k) && (old < mykey);
-        const unsigned long long m = __ballot(less);
-        const unsigned long long gm = (KL == 64) ? m : ((m >> (g * KL)) & ((1ull << (KL & 63)) - 1ull));
-        const int pos = __popcll(gm);
-        const bool ins = act && pos < k;                       // the key beats the k-th entry
-        if (ins && l >= pos && l < k - 1) lst[l + 1] = old;
-        if (ins && l == pos) lst[pos] = mykey;
-        if (ins && pos == k - 1 && l == k - 1) bounds[myq] = hqs[myq] - 0.5f * __uint_as_float(khi);
-        if (ins && pos < k - 1 && l == k - 2) bounds[myq] = hqs[myq] - 0.5f * __uint_as_float((unsigned int)(old >> 32));
+        // the list ascends, so the entries that precede the key are a prefix: its length is the key's position
+        int pos = 0;
+#pragma unroll
+        for (int c = 1; c <= E; ++c) {
+            const unsigned long long m = __ballot(go && cnt >= c);
+            pos += __popcll((m >> (grp * 8)) & 0xffull);
+        }
+        const bool ins = go && pos < k;                                   // the key still beats the k-th entry
+        const unsigned long long below = dpp_from_lane_below(old[E - 1]);
+        unsigned long long now[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = g8 * E + e;
+            const unsigned long long moved = e == 0 ? below : old[e > 0 ? e - 1 : 0];
+            now[e] = (i < pos || i >= k) ? old[e] : (i == pos ? key : moved);
+            if (ins && i == k - 1) bounds[ql] = hqs[ql] - 0.5f * __uint_as_float((unsigned int)(now[e] >> 32));
+        }
+        if (ins && g8 * E + E > pos && g8 * E < k) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) lst[e] = now[e];
+        }
+        pending &= ~__ballot(go && g8 == 0);
     }
 }
 
@@ -319,22 +331,28 @@ __device__ __attribute__((noinline)) void resolve_queue(int qcount, int col0, co
         const float* xa = Xq + (size_t)(valid ? qrow : 0) * d;
         const float* xb = Xc + (size_t)(valid ? cg : 0) * d;
         const int cid = (c_id && valid) ? ((global_ints)c_id)[cg] : cg;   // id that orders ties and is reported
+#ifdef SLHC_STUDY_DOUBLE_EVAL
+        const float dist = fmaxf(group8_sqdist<VEC4>(xa, xb, d, g8, valid), group8_sqdist<VEC4>(xb, xa, d, g8, valid));
+#else
         const float dist = group8_sqdist<VEC4>(xa, xb, d, g8, valid);
+#endif
         const unsigned long long key = make_key(dist, cid);
         // a stale k-th entry is only larger than the current one, so this test never drops a
-        // pair that belongs in the list; group_list_insert tests again
+        // pair that belongs in the list; group8_list_insert tests again
         if constexpr (KL == 1) {
             // k = 1: a list is one key, so the eight group leaders update their queries at once
             // (64-bit LDS minimum; two pairs of one query in the same pass are ordered by it) and
-            // then refresh the bounds from what the lists hold, as group_list_insert would
+            // then refresh the bounds from what the lists hold, as group8_list_insert would
             if (valid && g8 == 0) atomicMin(&mylists[ql], key);
             __builtin_amdgcn_wave_barrier();
             if (valid && g8 == 0)
                 L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
             continue;
         }
-        const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
-        if constexpr (KL > 1) group_list_insert<KL>(__ballot(accept), key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
+        if constexpr (KL > 1) {
+            const bool want = valid && key < mylists[(size_t)ql * KL + k - 1];
+            group8_list_insert<KL>(want, key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
+        }
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -471,8 +489,10 @@ __device__ __attribute__((noinline)) void resolve_deferred(int qcount, const flo
                 L.bounds[wave * 32 + ql] = L.hqs[wave * 32 + ql] - 0.5f * __uint_as_float((unsigned int)(mylists[ql] >> 32));
             continue;
         }
-        const bool accept = valid && g8 == 0 && key < mylists[(size_t)ql * KL + k - 1];
-        if constexpr (KL > 1) group_list_insert<KL>(__ballot(accept), key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
+        if constexpr (KL > 1) {
+            const bool want = valid && key < mylists[(size_t)ql * KL + k - 1];
+            group8_list_insert<KL>(want, key, ql, mylists, k, L.hqs + wave * 32, L.bounds + wave * 32, lane);
+        }
     }
     __builtin_amdgcn_wave_barrier();
     if (lane == 0) *deferred_count(L, wave) = 0;
@@ -529,12 +549,20 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
 // Tile epilogue after the hot filter flagged blocks `flagged` of this wavefront: all blocks go
 // through one queue, so the exact re-evaluation runs once per tile step.  Expands at its call site
 // with static block indices (a dynamic index into the accumulators would spill them).
+#define FINE_MARK(i) do { } while (0)      // redefined for study builds where the phase timers exist
+#ifdef SLHC_STUDY_DOUBLE_COMPACT
+#define STUDY_AGAIN(...) __VA_ARGS__
+#else
+#define STUDY_AGAIN(...) do { } while (0)
+#endif
 #define SLHC_SELECT_TILE(KL_, MASKED_, VEC4_)                                                               \
     do {                                                                                                    \
         int qn_ = 0;                                                                                        \
+        FINE_MARK(6);                                                                                       \
         _Pragma("unroll") for (int b_ = 0; b_ < 4; ++b_) {                                                  \
             if (flagged & (1u << b_)) {                                                                     \
                 int r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_);    \
+                STUDY_AGAIN(r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_)); \
                 if (r_ < 0) {                                                                               \
                     survivors += (unsigned int)qn_;                                                         \
                     resolve_queue<KL_, VEC4_>(qn_, col0, Xq, Xc, p.c_id, d, k);                             \
@@ -544,11 +572,13 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
                 qn_ = r_;                                                                                   \
             }                                                                                               \
         }                                                                                                   \
+        FINE_MARK(0);                                                                                       \
         if (qn_ > 0) {                                                                                      \
             survivors += (unsigned int)qn_;                                                                 \
             resolve_queue<KL_, VEC4_>(qn_, col0, Xq, Xc, p.c_id, d, k);                                     \
             bound = bounds[my_q_local];                                                                     \
         }                                                                                                   \
+        FINE_MARK(2);                                                                                       \
     } while (0)
 
 template <int KL, bool MASKED, bool VEC4>
@@ -822,6 +852,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     } while (0)
 #else
 #define PHASE_MARK(i) do { } while (0)
+#endif
+// study builds: compaction goes to phase slot 0 and the queue's resolution to slot 2 (both otherwise tiny)
+#if defined(SLHC_PHASE_TIMERS) && defined(SLHC_PHASE_TIMERS_FINE)
+#undef FINE_MARK
+#define FINE_MARK(i) PHASE_MARK(i)
 #endif
 
 template <int KL, bool MASKED, int DCH, bool PRUNE>
