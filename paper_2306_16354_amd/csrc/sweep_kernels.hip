@@ -1118,6 +1118,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             tile = tile_of(first);
             scan_from = first + 1;
         }
+        float ahead_gap = __builtin_nanf("");          // lower bound of scan position scan_from + lane (NaN: none)
+        if (prune) ahead_gap = scan_from + lane < nscan ? gap[scan_tile(scan_from + lane)] : __builtin_nanf("");
  if (tile < ntiles) gload(tile, 0);
         PHASE_MARK(2);
         // largest threshold of this wavefront's 32 queries, from their bounds: thr = 2 (h_q - bound)
@@ -1183,10 +1185,19 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                                                        __HIP_MEMORY_SCOPE_AGENT);
                     }
                     if (shared_thr) thr_max = fminf(thr_max, thr_c0);
-                    const int nxt = next_scan(scan_from, thr_max);
+                    // the lower bounds of the next 64 scan positions were read a step ago (ahead_gap): when
+                    // one of them is admissible, as it nearly always is, the choice costs no memory wait
+                    int nxt;
+                    if (prune) {
+                        const unsigned long long ok = __ballot(scan_from + lane < nscan && ahead_gap <= thr_max);
+                        nxt = ok ? scan_from + __builtin_ctzll(ok) : next_scan(scan_from + 64, thr_max);
+                    } else {
+                        nxt = next_scan(scan_from, thr_max);
+                    }
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
                     if (tile_after < ntiles) gload(tile_after, 0);
+                    if (prune) ahead_gap = scan_from + lane < nscan ? gap[scan_tile(scan_from + lane)] : __builtin_nanf("");
                     __builtin_amdgcn_sched_barrier(0);
                     PHASE_MARK(4);
                 }
@@ -1246,8 +1257,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             int hits = 0;                  // pruned sweeps: lanes that hold a passing pair, over the four blocks
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
+                // Every-tile sweeps: one fused test (a tile of random rows nearly always holds near rows of
+                // the query's own component, so a distance-only pre-test would rarely save the colour
+                // test).  Pruned sweeps skip the tiles of the panel's own colour, and what is left is
+                // mostly far: distances first, colours only in a block where some accumulator passes.
                 bool any = false;
-                if (MASKED) {
+                if (MASKED && !PRUNE) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int4 cc = *reinterpret_cast<const int4*>(ccol + b * 32 + 8 * g + 4 * lhalf);
@@ -1259,6 +1274,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 } else {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) any |= (acc[b][r] >= bound);
+                    if (MASKED && __any(any)) {
+                        any = false;
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int4 cc = *reinterpret_cast<const int4*>(ccol + b * 32 + 8 * g + 4 * lhalf);
+                            any |= (acc[b][4 * g + 0] >= bound) & (cc.x != my_qcol);
+                            any |= (acc[b][4 * g + 1] >= bound) & (cc.y != my_qcol);
+                            any |= (acc[b][4 * g + 2] >= bound) & (cc.z != my_qcol);
+                            any |= (acc[b][4 * g + 3] >= bound) & (cc.w != my_qcol);
+                        }
+                    }
                 }
                 const unsigned long long hit = __ballot(any);
                 if (hit) flagged |= 1u << b;
