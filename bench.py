@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--no-pruned-leg", action="store_true", help="skip the extra runs with tile pruning")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy three times and exit (reference for HBM counters)")
+    ap.add_argument("--loop-study", action="store_true",
+                    help="run the panel-loop probe (multiplies with the loop's ingredients added one by one) and exit")
     ap.add_argument("--cpu-sample-rows", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -77,6 +79,18 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": a.numel() * 4, "bytes_written": a.numel() * 4, "repeats": 3}))
+        return
+
+    if args.loop_study:
+        ws_probe = torch.zeros(1 << 27, dtype=torch.float32, device=dev)        # 512 MB to stream from
+        names = ["operands in registers", "+ barrier per chunk, A operands from LDS",
+                 "+ next chunk: global loads, LDS stores", "+ filter compares per tile"]
+        out_rows = []
+        for rep in range(2):                                                    # second pass reported
+            out_rows = [{"steps": st, "what": names[st], "tflops": slhc.probe_panel_loop(st, ws_probe)} for st in range(4)]
+        for r in out_rows:
+            r["frac_of_peak"] = r["tflops"] / PEAK_FP32_MFMA_TFLOPS
+        print(json.dumps({"loop_study": out_rows, "peak": PEAK_FP32_MFMA_TFLOPS}))
         return
 
     t0 = time.time()
@@ -285,7 +299,7 @@ def main():
             # same inputs: the small workload in full, and this workload scaled down to what Prim
             # finishes in a few seconds (its cost grows with N^2 d)
             tree = []
-            scaled_rows = int(min(N, max(2000, (6.0e10 / d) ** 0.5)))
+            scaled_rows = int(min(N, max(2000, (2.5e11 / d) ** 0.5)))
             for wname, rows_ in (("c1", None), (args.workload, scaled_rows)):
                 Xs, _, ks = gen.make(wname, n=rows_)
                 if args.k is not None and wname == args.workload:

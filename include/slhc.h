@@ -161,6 +161,21 @@ int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k,
 int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid like slhc_probe_fp32_mfma, for the panel loop of the sweeps (paper Sec. 3.1.1, the
+ * `gemm_nt_loop` of Alg. "Fused k-NN"): the same multiplies with the loop's ingredients added one by one,
+ * so that a run shows which of them costs MFMA rate.
+ *   steps = 0  operands in registers (what slhc_probe_fp32_mfma runs)
+ *           1  + one workgroup barrier per chunk of 64 multiplies, A operands read from LDS
+ *           2  + the next chunk of a 128-row tile loaded from the workspace and stored to LDS
+ *           3  + the filter: 16 compares and a ballot per accumulator block and tile
+ *   tflops     HOST   out
+ *   workspace  DEVICE      at least 131 328 bytes, contents irrelevant but finite floats; steps >= 2
+ *                          stream their tiles from it (the more, the less of the stream hits in L2)
+ * Synchronous.
+ */
+int slhc_probe_panel_loop(int32_t steps, double* tflops, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Cross-component 1-NN (paper Sec. 3.1.2, Alg. "Fused 1-NN", used by Alg. "connect_graph").
  *
  * For each query row rows[q], q < m: the row j with colour[j] != colour[rows[q]] that minimises

@@ -60,6 +60,8 @@ def load_library():
     lib.slhc_knn_graph_static.restype = ctypes.c_int
     lib.slhc_probe_fp32_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     lib.slhc_probe_fp32_mfma.restype = ctypes.c_int
+    lib.slhc_probe_panel_loop.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
+    lib.slhc_probe_panel_loop.restype = ctypes.c_int
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
     lib.slhc_cross_1nn.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.slhc_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(sz)]
@@ -157,6 +159,15 @@ def probe_fp32_mfma(device="cuda"):
     ws = _workspace(256, device)
     out = ctypes.c_double(0.0)
     _check(load_library().slhc_probe_fp32_mfma(ctypes.byref(out), ws.data_ptr(), ws.numel(), _stream()))
+    return out.value
+
+
+def probe_panel_loop(steps, workspace):
+    """slhc_probe_panel_loop: TFLOP/s of the multiplies with the panel loop's ingredients 0..steps.
+    `workspace`: a CUDA tensor of finite float32 values to stream tiles from."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().slhc_probe_panel_loop(int(steps), ctypes.byref(out), workspace.data_ptr(),
+                                                workspace.numel() * workspace.element_size(), _stream()))
     return out.value
 
 

@@ -682,6 +682,33 @@ int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes
     });
 }
 
+int slhc_probe_panel_loop(int32_t steps, double* tflops, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return guarded([&]() -> int {
+        if (!tflops || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (steps < 0 || steps > 3) { set_err("steps must be 0..3 (steps=%d)", steps); return SLHC_INVALID_ARG; }
+        // a sink word, then the rows to stream from: the largest power of two of 512-byte rows that fits
+        if (workspace_bytes < 256 + 512 * 256) { set_err("workspace %zu < %d bytes", workspace_bytes, 256 + 512 * 256); return SLHC_WORKSPACE_TOO_SMALL; }
+        int rows = 256;
+        while ((size_t)rows * 2 * 512 + 256 <= workspace_bytes && rows < (1 << 22)) rows *= 2;
+        float* sink = static_cast<float*>(workspace);
+        const float* rows_ptr = reinterpret_cast<const float*>(static_cast<unsigned char*>(workspace) + 256);
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        EventPair ev;
+        HIP_TRY(ev.create());
+        double flop = 0.0;
+        HIP_TRY(slhc::launch_loop_probe(steps, 500, rows_ptr, rows, sink, s, &flop));           // warm-up: clocks settle
+        HIP_TRY(hipEventRecord(ev.a, s));
+        HIP_TRY(slhc::launch_loop_probe(steps, 10000, rows_ptr, rows, sink, s, &flop));         // ~40 ms
+        HIP_TRY(hipEventRecord(ev.b, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const float ms = ev.ms();
+        if (!(ms > 0.f)) { set_err("probe timing failed"); return SLHC_HIP_ERROR; }
+        *tflops = flop / (ms * 1e-3) / 1e12;
+        return SLHC_OK;
+    });
+}
+
 int slhc_cross_1nn_workspace_bytes(int64_t N, int32_t d, int64_t m, size_t* bytes)
 {
     return guarded([&]() -> int {

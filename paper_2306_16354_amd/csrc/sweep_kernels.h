@@ -82,6 +82,10 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
 // Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
 // *flop receives the floating-point operations of the launch.  `sink`: one device float.
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);
+// The multiplies of launch_mfma_probe with the panel loop's ingredients added (steps 0..3, see the kernel);
+// `stream_rows`: [rows, 128] floats to stream from (steps >= 2; rows a power of two), iters chunks of 64 multiplies.
+hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int rows, float* sink, hipStream_t stream,
+                             double* flop);
 int sweep_grid_limit();   // upper bound of gridDim.x of a sweep launch (for sizing gap_ws); 0 on error
 hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream);
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream);

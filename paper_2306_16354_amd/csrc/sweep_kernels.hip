@@ -1519,6 +1519,107 @@ hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double*
     return hipGetLastError();
 }
 
+// The same multiplies with the ingredients of the sweep's panel loop added one by one (a measurement aid:
+// which ingredient costs MFMA rate).  STEPS: 1 = a workgroup barrier per chunk of 64 multiplies and the A
+// operands read from LDS (16 ds_read_b128 per chunk); 2 = also the next chunk of a 128-row candidate tile
+// loaded from `stream` (rows of 128 floats, `rows` a power of two) into registers and stored to LDS, double
+// buffered as in the sweep; 3 = also 16 compares and a ballot per accumulator block after every fourth
+// chunk.  Nothing it computes means anything.
+template <int STEPS>
+__global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, const float* __restrict__ stream,
+                                                                   int rows, float* __restrict__ sink)
+{
+    extern __shared__ __align__(16) unsigned char probe_smem[];
+    float* buf0 = reinterpret_cast<float*>(probe_smem);
+    float* buf1 = buf0 + BN * LDK;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhalf = lane >> 5;
+    const int ld_row = tid >> 3, ld_col = (tid & 7) * 4;
+    for (int i = tid; i < 2 * BN * LDK; i += WG_THREADS) buf0[i] = 1e-3f * (float)(i & 15);
+    __syncthreads();
+    v16f acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+    v4f q[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) q[kk] = v4f{1.f + lane * 1e-3f, 0.5f, 0.25f, 0.125f};
+    v4f creg[4];
+    unsigned int row = ((unsigned int)blockIdx.x * BN + ld_row) & (unsigned int)(rows - 1);
+    unsigned int flagged = 0;
+    const float bound = 1e30f;
+    if (STEPS >= 2) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            creg[i] = *reinterpret_cast<const v4f*>(stream + (size_t)((row + 32 * i) & (rows - 1)) * 128 + ld_col);
+    }
+    for (int it = 0; it < iters; ++it) {
+        float* Cb = (it & 1) ? buf1 : buf0;
+        if (STEPS >= 2) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDK + ld_col) = creg[i];
+        }
+        __syncthreads();
+        if (STEPS >= 2) {
+            row = (row + BN) & (unsigned int)(rows - 1);
+            const int col = ((it + 1) & 3) * KC + ld_col;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                creg[i] = *reinterpret_cast<const v4f*>(stream + (size_t)((row + 32 * i) & (rows - 1)) * 128 + col);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            v4f cf[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) cf[b] = *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + kk * 8 + 4 * lhalf);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(cf[b][e], q[kk][e], acc[b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (STEPS >= 3 && (it & 3) == 3) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                bool any = false;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) any |= acc[b][r] >= bound;
+                if (__any(any)) flagged |= 1u << b;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[b][r] = -1.0f;
+            }
+        }
+    }
+    float total = (float)flagged;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) total += acc[b][r];
+    if (total == 123456.789f) sink[0] = total;
+}
+
+hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int rows, float* sink, hipStream_t stream,
+                             double* flop)
+{
+    if (steps <= 0) return launch_mfma_probe(iters * 4, sink, stream, flop);     // 16 multiplies per iteration there
+    int cus = 0;
+    hipError_t e = device_cus(&cus);
+    if (e != hipSuccess) return e;
+    const int grid = 2 * cus;
+    const size_t lds = 80000;              // the two chunk buffers need 36 864 B; this size admits two workgroups per CU, like the sweep
+    auto run = [&](auto kernel) -> hipError_t {
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e2 != hipSuccess) return e2;
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(WG_THREADS), lds, stream, iters, stream_rows, rows, sink);
+        return hipGetLastError();
+    };
+    *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 64.0 * (2.0 * 32 * 32 * 2);
+    if (steps == 1) return run(&loop_probe_kernel<1>);
+    if (steps == 2) return run(&loop_probe_kernel<2>);
+    return run(&loop_probe_kernel<3>);
+}
+
 float filter_slack_coefficient(int d)
 {
     // The accumulator is a chain of d+1 round-to-nearest fused multiply-adds whose partial sums
