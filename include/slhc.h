@@ -168,6 +168,8 @@ int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes
  *           1  + one workgroup barrier per chunk of 64 multiplies, A operands read from LDS
  *           2  + the next chunk of a 128-row tile loaded from the workspace and stored to LDS
  *           3  + the filter: 16 compares and a ballot per accumulator block and tile
+ *           4  as 2, the chunk loaded from global memory straight into LDS (no register staging)
+ *           5  as 3, likewise
  *   tflops     HOST   out
  *   workspace  DEVICE      at least 131 328 bytes, contents irrelevant but finite floats; steps >= 2
  *                          stream their tiles from it (the more, the less of the stream hits in L2)

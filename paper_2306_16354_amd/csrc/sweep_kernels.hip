@@ -651,18 +651,42 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         v4f qreg[4], creg[4];
         float hreg = 0.f;
         int colreg = 0;
+        // VEC4: a chunk is loaded from a wavefront-uniform base (the chunk's first column) plus per-lane element
+        // offsets that change once per panel (queries) and once per tile (candidates, rows clamped to N - 1), so
+        // a chunk costs little address arithmetic.  Only the last chunk can reach past column d: there the dead
+        // lanes take the chunk's first quad instead and their values are zeroed when they are staged.
+        const bool last_has_dead = d < nchunks * KC;
+        const bool dead_lane = (nchunks - 1) * KC + ld_col >= d;           // in the last chunk
+        unsigned int qlo[4], clo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { qlo[i] = qoff[i] + (unsigned int)ld_col; clo[i] = 0u; }
         auto gload = [&](int tile, int chunk) {
             const int col = chunk * KC + ld_col;
             const int crow0 = tile * BN + ld_row;
             if (VEC4) {
-                const bool live = col < d;
-                const unsigned int c0 = live ? (unsigned int)col : 0u;
+                if (chunk == 0) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    int crow = crow0 + 32 * i;
-                    crow = crow < N ? crow : N - 1;
-                    qreg[i] = *reinterpret_cast<const v4f*>(Xq + (qoff[i] + c0));
-                    creg[i] = *reinterpret_cast<const v4f*>(Xc + ((unsigned int)crow * (unsigned int)d + c0));
+                    for (int i = 0; i < 4; ++i) {
+                        int crow = crow0 + 32 * i;
+                        crow = crow < N ? crow : N - 1;
+                        clo[i] = (unsigned int)crow * (unsigned int)d + (unsigned int)ld_col;
+                    }
+                }
+                const float* qb = Xq + chunk * KC;
+                const float* cb = Xc + chunk * KC;
+                if (chunk == nchunks - 1 && last_has_dead) {
+                    const unsigned int back = dead_lane ? (unsigned int)ld_col : 0u;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        qreg[i] = *reinterpret_cast<const v4f*>(qb + (qlo[i] - back));
+                        creg[i] = *reinterpret_cast<const v4f*>(cb + (clo[i] - back));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        qreg[i] = *reinterpret_cast<const v4f*>(qb + qlo[i]);
+                        creg[i] = *reinterpret_cast<const v4f*>(cb + clo[i]);
+                    }
                 }
             } else {
 #pragma unroll
@@ -696,23 +720,31 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
             const int col0 = tile * BN;
             for (int chunk = 0; chunk < nchunks; ++chunk) {
                 __syncthreads();                       // everyone is done reading the staged step
-                // values staged past the last feature column are loaded from a clamped address
-                // and zeroed here, at the point of use, so the loads stay in flight until now
+                // values staged past the last feature column were loaded from a valid address and are zeroed
+                // here, at the point of use, so the loads stay in flight until now; only the last chunk has any
+                if (!VEC4 || (chunk == nchunks - 1 && last_has_dead)) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    v4f q = qreg[i], c = creg[i];
+                    for (int i = 0; i < 4; ++i) {
+                        v4f q = qreg[i], c = creg[i];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool live = chunk * KC + ld_col + (VEC4 ? 0 : e) < d;
-                        q[e] = live ? q[e] : 0.f;
-                        c[e] = live ? c[e] : 0.f;
+                        for (int e = 0; e < 4; ++e) {
+                            const bool live = chunk * KC + ld_col + (VEC4 ? 0 : e) < d;
+                            q[e] = live ? q[e] : 0.f;
+                            c[e] = live ? c[e] : 0.f;
+                        }
+                        *reinterpret_cast<v4f*>(Qs + (ld_row + 32 * i) * LDK + ld_col) = q;
+                        *reinterpret_cast<v4f*>(Cs + (ld_row + 32 * i) * LDK + ld_col) = c;
                     }
-                    *reinterpret_cast<v4f*>(Qs + (ld_row + 32 * i) * LDK + ld_col) = q;
-                    *reinterpret_cast<v4f*>(Cs + (ld_row + 32 * i) * LDK + ld_col) = c;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        *reinterpret_cast<v4f*>(Qs + (ld_row + 32 * i) * LDK + ld_col) = qreg[i];
+                        *reinterpret_cast<v4f*>(Cs + (ld_row + 32 * i) * LDK + ld_col) = creg[i];
+                    }
                 }
                 if (chunk == 0 && tid < BN) {
                     const bool in_range = tile * BN + tid < N;
-                    hcs[tid] = in_range ? hreg : __builtin_inff();
+                    hcs[tid] = in_range ? -hreg : -__builtin_inff();     // negated here: the accumulators start from it as it is
                     if (MASKED) ccol[tid] = in_range ? colreg : -1;
                 }
                 __syncthreads();
@@ -728,10 +760,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             const v4f h = *reinterpret_cast<const v4f*>(hcs + b * 32 + 8 * g + 4 * lhalf);
-                            acc[b][4 * g + 0] = -h[0];
-                            acc[b][4 * g + 1] = -h[1];
-                            acc[b][4 * g + 2] = -h[2];
-                            acc[b][4 * g + 3] = -h[3];
+                            acc[b][4 * g + 0] = h[0];
+                            acc[b][4 * g + 1] = h[1];
+                            acc[b][4 * g + 2] = h[2];
+                            acc[b][4 * g + 3] = h[3];
                         }
                     }
                 }
@@ -1092,15 +1124,33 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         v4f creg[4];
         float hreg = 0.f;
         int colreg = 0;
-        auto gload = [&](int tile, int chunk) {
-            const int col = chunk * KC + ld_col;
-            const unsigned int c0 = col < d ? (unsigned int)col : 0u;
-            const int crow0 = tile * BN + ld_row;
+        // A chunk is loaded from a wavefront-uniform base (tile, chunk) plus four per-lane offsets, one per staged
+        // row, that stay the same from tile to tile: a chunk costs no address arithmetic in the vector unit.
+        // Only a tile that reaches past row N has other offsets (its rows are clamped to N - 1): they are
+        // rewritten when such a tile comes and when the next full one follows.  Only the last chunk can reach
+        // past column d: lanes that would take the first quad of that chunk instead (finite values of the same
+        // row, multiplied by query fragments that are zero).
+        unsigned int row_off[4];
+        bool row_off_clamped;
+        auto set_row_off = [&](int tile) {
+            const int last = N - 1 - tile * BN;                 // last valid row of the tile, >= 0
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                int crow = crow0 + 32 * i;
-                crow = crow < N ? crow : N - 1;
-                creg[i] = *reinterpret_cast<const v4f*>(Xc + ((unsigned int)crow * (unsigned int)d + c0));
+                const int r = ld_row + 32 * i;
+                row_off[i] = (unsigned int)(r < last ? r : last) * (unsigned int)d + (unsigned int)ld_col;
+            }
+        };
+        set_row_off(0);
+        row_off_clamped = BN > N;
+        const unsigned int dead_adj = (DCH - 1) * KC + ld_col < d ? 0u : (unsigned int)ld_col;
+        auto gload = [&](int tile, int chunk) {
+            const bool clamped = (tile + 1) * BN > N;
+            if (clamped != row_off_clamped) { set_row_off(tile); row_off_clamped = clamped; }
+            const float* base = Xc + ((size_t)tile * BN * (size_t)d + (size_t)(chunk * KC));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned int off = (chunk == DCH - 1 && d < DCH * KC) ? row_off[i] - dead_adj : row_off[i];
+                creg[i] = *reinterpret_cast<const v4f*>(base + off);
             }
             if (chunk == 0 && tid < BN) {
                 const int crow = tile * BN + tid;
@@ -1149,17 +1199,13 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             for (int chunk = 0; chunk < DCH; ++chunk) {
                 // candidate buffer of this step: steps alternate between the two LDS buffers
                 float* Cb = (((DCH & 1) ? (step + chunk) : chunk) & 1) ? L.Qs : L.Cs;
-                {
-                    const bool live = chunk * KC + ld_col < d;
+                // columns past d are staged as they were loaded (finite values of column 0): the query fragments
+                // are zero there, so they add nothing
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const v4f c = live ? creg[i] : v4f{0.f, 0.f, 0.f, 0.f};
-                        *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDK + ld_col) = c;
-                    }
-                }
+                for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDK + ld_col) = creg[i];
                 if (chunk == 0 && tid < BN) {
                     const bool in_range = col0 + tid < N;
-                    hcs[tid] = in_range ? hreg : __builtin_inff();
+                    hcs[tid] = in_range ? -hreg : -__builtin_inff();     // negated here: the accumulators start from it as it is
                     if (MASKED) ccol[tid] = in_range ? colreg : -1;
                 }
                 __syncthreads();
@@ -1207,10 +1253,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 #pragma unroll
                         for (int g = 0; g < 4; ++g) {
                             const v4f h = *reinterpret_cast<const v4f*>(hcs + b * 32 + 8 * g + 4 * lhalf);
-                            acc[b][4 * g + 0] = -h[0];
-                            acc[b][4 * g + 1] = -h[1];
-                            acc[b][4 * g + 2] = -h[2];
-                            acc[b][4 * g + 3] = -h[3];
+                            acc[b][4 * g + 0] = h[0];
+                            acc[b][4 * g + 1] = h[1];
+                            acc[b][4 * g + 2] = h[2];
+                            acc[b][4 * g + 3] = h[3];
                         }
                     }
                 }
@@ -1525,16 +1571,27 @@ hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double*
 // loaded from `stream` (rows of 128 floats, `rows` a power of two) into registers and stored to LDS, double
 // buffered as in the sweep; 3 = also 16 compares and a ballot per accumulator block after every fourth
 // chunk.  Nothing it computes means anything.
-template <int STEPS>
+template <int STEPS, bool DIRECT, bool ASYM = false>
 __global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, const float* __restrict__ stream,
                                                                    int rows, float* __restrict__ sink)
 {
+    // ASYM: the two wavefronts that share a SIMD (one of each resident workgroup) run at different priorities,
+    // chosen by the parity of the wavefront's slot number on its SIMD (HW_ID bits 3:0)
+    if (ASYM) {
+        if (__builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 4) & 1) __builtin_amdgcn_s_setprio(2);
+    }
+    // DIRECT: the candidate chunk goes from global memory straight into LDS (global_load_lds_dwordx4: lane l of a
+    // wavefront fills the 16 bytes at base + 16 l), rows of 32 floats without padding, the 16-byte quads of row r
+    // stored at position quad ^ (r & 7) so that the operand reads of 8 consecutive rows fall into different banks.
+    constexpr int LDR = DIRECT ? KC : LDK;
     extern __shared__ __align__(16) unsigned char probe_smem[];
     float* buf0 = reinterpret_cast<float*>(probe_smem);
-    float* buf1 = buf0 + BN * LDK;
-    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lhalf = lane >> 5;
-    const int ld_row = tid >> 3, ld_col = (tid & 7) * 4;
-    for (int i = tid; i < 2 * BN * LDK; i += WG_THREADS) buf0[i] = 1e-3f * (float)(i & 15);
+    float* buf1 = buf0 + BN * LDR;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, lhalf = lane >> 5;
+    const int ld_row = DIRECT ? wave * 32 + (lane >> 3) : tid >> 3;
+    const int ld_step = DIRECT ? 8 : 32;
+    const int ld_col = DIRECT ? ((lane & 7) ^ (lane >> 3)) * 4 : (tid & 7) * 4;
+    for (int i = tid; i < 2 * BN * LDR; i += WG_THREADS) buf0[i] = 1e-3f * (float)(i & 15);
     __syncthreads();
     v16f acc[4];
 #pragma unroll
@@ -1548,31 +1605,40 @@ __global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, co
     unsigned int row = ((unsigned int)blockIdx.x * BN + ld_row) & (unsigned int)(rows - 1);
     unsigned int flagged = 0;
     const float bound = 1e30f;
-    if (STEPS >= 2) {
+    auto stage = [&](float* dst, int col) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            creg[i] = *reinterpret_cast<const v4f*>(stream + (size_t)((row + 32 * i) & (rows - 1)) * 128 + ld_col);
-    }
+        for (int i = 0; i < 4; ++i) {
+            const float* src = stream + (size_t)((row + ld_step * i) & (rows - 1)) * 128 + col;
+            if (DIRECT)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                                 (__attribute__((address_space(3))) void*)(dst + (wave * 32 + 8 * i) * LDR),
+                                                 16, 0, 0);
+            else
+                creg[i] = *reinterpret_cast<const v4f*>(src);
+        }
+    };
+    if (STEPS >= 2) stage(buf0, ld_col);
     for (int it = 0; it < iters; ++it) {
         float* Cb = (it & 1) ? buf1 : buf0;
-        if (STEPS >= 2) {
+        if (STEPS >= 2 && !DIRECT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDK + ld_col) = creg[i];
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(Cb + (ld_row + 32 * i) * LDR + ld_col) = creg[i];
         }
+        if (STEPS >= 2 && DIRECT) __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wavefront's part of the chunk is in LDS
         __syncthreads();
         if (STEPS >= 2) {
             row = (row + BN) & (unsigned int)(rows - 1);
-            const int col = ((it + 1) & 3) * KC + ld_col;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                creg[i] = *reinterpret_cast<const v4f*>(stream + (size_t)((row + 32 * i) & (rows - 1)) * 128 + col);
+            stage((it & 1) ? buf0 : buf1, ((it + 1) & 3) * KC + ld_col);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             v4f cf[4];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) cf[b] = *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + kk * 8 + 4 * lhalf);
+            for (int b = 0; b < 4; ++b) {
+                const int quad = kk * 2 + lhalf;
+                cf[b] = *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDR + (DIRECT ? (quad ^ (l32 & 7)) * 4 : quad * 4));
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -1591,6 +1657,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, co
             }
         }
     }
+    if (STEPS >= 2 && DIRECT) __builtin_amdgcn_s_waitcnt(0x0f70);
     float total = (float)flagged;
 #pragma unroll
     for (int b = 0; b < 4; ++b)
@@ -1615,9 +1682,13 @@ hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int
         return hipGetLastError();
     };
     *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 64.0 * (2.0 * 32 * 32 * 2);
-    if (steps == 1) return run(&loop_probe_kernel<1>);
-    if (steps == 2) return run(&loop_probe_kernel<2>);
-    return run(&loop_probe_kernel<3>);
+    if (steps == 1) return run(&loop_probe_kernel<1, false>);
+    if (steps == 2) return run(&loop_probe_kernel<2, false>);
+    if (steps == 3) return run(&loop_probe_kernel<3, false>);
+    if (steps == 4) return run(&loop_probe_kernel<2, true>);      // 2 and 3 with the chunk loaded straight into LDS
+    if (steps == 5) return run(&loop_probe_kernel<3, true>);
+    if (steps == 6) return run(&loop_probe_kernel<2, false, true>);   // 2 and 3 with unequal wavefront priorities
+    return run(&loop_probe_kernel<3, false, true>);
 }
 
 float filter_slack_coefficient(int d)
