@@ -85,10 +85,11 @@ def main():
         ws_probe = torch.zeros(1 << 27, dtype=torch.float32, device=dev)        # 512 MB to stream from
         names = ["operands in registers", "+ barrier per chunk, A operands from LDS",
                  "+ next chunk: global loads, LDS stores", "+ filter compares per tile",
-                 "as 2, chunk loaded straight into LDS", "as 3, chunk loaded straight into LDS"]
+                 "as 2, chunk loaded straight into LDS", "as 3, chunk loaded straight into LDS",
+                 "as 2, unequal wavefront priorities", "as 3, unequal wavefront priorities"]
         out_rows = []
         for rep in range(2):                                                    # second pass reported
-            out_rows = [{"steps": st, "what": names[st], "tflops": slhc.probe_panel_loop(st, ws_probe)} for st in range(6)]
+            out_rows = [{"steps": st, "what": names[st], "tflops": slhc.probe_panel_loop(st, ws_probe)} for st in range(8)]
         for r in out_rows:
             r["frac_of_peak"] = r["tflops"] / PEAK_FP32_MFMA_TFLOPS
         print(json.dumps({"loop_study": out_rows, "peak": PEAK_FP32_MFMA_TFLOPS}))

@@ -170,6 +170,8 @@ int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes
  *           3  + the filter: 16 compares and a ballot per accumulator block and tile
  *           4  as 2, the chunk loaded from global memory straight into LDS (no register staging)
  *           5  as 3, likewise
+ *           6  as 2, the two wavefronts that share a SIMD run at different priorities
+ *           7  as 3, likewise
  *   tflops     HOST   out
  *   workspace  DEVICE      at least 131 328 bytes, contents irrelevant but finite floats; steps >= 2
  *                          stream their tiles from it (the more, the less of the stream hits in L2)
