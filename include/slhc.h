@@ -28,7 +28,8 @@
  *   - Device memory: the library allocates none; everything it needs is in `workspace`.  Host
  *     memory: the synchronous entry points (slhc_slhc*, slhc_csr_msf, and slhc_knn_graph_opt with
  *     SLHC_PRUNE) allocate pinned staging buffers and HIP events for the duration of the call
- *     (slhc_slhc: 20 bytes per row for the host dendrogram pass) and free them before returning.
+ *     (slhc_slhc: up to 28 bytes per row of pinned memory and 16 bytes per row of pageable memory for
+ *     the host dendrogram pass) and free them before returning.
  *     The library keeps no mutable state between calls other than the thread-local error text
  *     (and the fixed scratch array of slhc_knn_graph_static, see there).
  *   - Calls that share a workspace must not overlap in time.  Calls on different streams with
@@ -239,7 +240,9 @@ int slhc_fused_1nn(const float* Q, int64_t m, const float* Y, int64_t n, int32_t
  *   sizes     DEVICE out  [N-1] int32 rows under node N+i
  *   stats     HOST   out  optional
  * Synchronous: returns after the outputs are complete (the dendrogram pass runs on the host, as
- * in the paper, so the call has to wait for the device anyway).
+ * in the paper, so the call has to wait for the device anyway).  From 200 000 rows on that pass starts
+ * host threads of its own, at most 16 and at most the number of hardware threads; SLHC_HOST_THREADS in
+ * the environment sets another number (1: none).  The result does not depend on it.
  */
 int slhc_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes /* HOST out */);
 int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k,

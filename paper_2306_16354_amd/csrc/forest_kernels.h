@@ -75,6 +75,22 @@ hipError_t edge_sort(const int32_t* lo, const int32_t* hi, const float* w, int E
                      uint32_t* vals_a, uint32_t* vals_b, void* temp, size_t temp_bytes,
                      int32_t* out_lo, int32_t* out_hi, float* out_w, hipStream_t s);
 
+// Components of the forest made of edges 0..R-1 of a tree's edge list (lo, hi < N): one pass hooks every
+// edge's larger root under the smaller and flattens the labels; `first` initialises label[v] = v.  The
+// caller clears *changed before a pass and repeats passes until one leaves it 0; label[v] is then the
+// smallest vertex id of v's component.  prefix_forest_keys: key[e] = label[lo[e]], val[e] = e for e < R.
+hipError_t prefix_forest_pass(const int32_t* lo, const int32_t* hi, int R, int N, int32_t* label, int32_t* changed,
+                              bool first, hipStream_t s);
+hipError_t prefix_forest_keys(const int32_t* lo, const int32_t* label, int R, int N, uint32_t* key, uint32_t* val,
+                              hipStream_t s);
+
+// glo[j] = lo[listed[j]], ghi[j] = hi[listed[j]] for j < R (-1 where listed[j] is not below R), and the way
+// back: children[2 listed[j] ..] = cj[2 j ..], sizes[listed[j]] = sj[j].
+hipError_t prefix_forest_gather(const int32_t* lo, const int32_t* hi, const uint32_t* listed, int R, int32_t* glo,
+                                int32_t* ghi, hipStream_t s);
+hipError_t prefix_forest_scatter(const uint32_t* listed, const int32_t* cj, const int32_t* sj, int R, int32_t* children,
+                                 int32_t* sizes, hipStream_t s);
+
 // Stable sort of n (key, value) pairs of 32-bit words by key (keys below 2^key_bits).
 size_t pair_sort_temp_bytes(int n);
 hipError_t pair_sort_u32(const uint32_t* keys_in, uint32_t* keys_out, const uint32_t* vals_in,

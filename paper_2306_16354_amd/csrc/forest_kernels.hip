@@ -603,6 +603,114 @@ __global__ void __launch_bounds__(TB) k_unpack_edges(const unsigned long long* _
     w[i] = __uint_as_float(wbits[i]);
 }
 
+// ---- components of the forest made of the first R edges of a weight-sorted tree (for the dendrogram) ----
+// label[v] ends as the smallest vertex id of v's component.  Labels only ever decrease and label[x] <= x,
+// so every chain of labels descends strictly and every walk below ends.
+__global__ void __launch_bounds__(256) k_prefix_init(int32_t* __restrict__ label, int N)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v < N) label[v] = v;
+}
+
+__device__ __forceinline__ int prefix_root(const int32_t* label, int v)
+{
+    for (;;) {
+        const int up = __hip_atomic_load(label + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (up == v) return v;
+        v = up;
+    }
+}
+
+// every edge hooks the larger of its two roots under the smaller one; *changed is set when any edge still
+// joined two different roots (the hook may lose against a smaller one: the next pass sees to it)
+__global__ void __launch_bounds__(256) k_prefix_hook(const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
+                                                     int R, int N, int32_t* __restrict__ label,
+                                                     int32_t* __restrict__ changed)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= R) return;
+    const int a = lo[e], b = hi[e];
+    if ((unsigned int)a >= (unsigned int)N || (unsigned int)b >= (unsigned int)N) return;
+    const int ra = prefix_root(label, a), rb = prefix_root(label, b);
+    if (ra == rb) return;
+    atomicMin(label + (ra > rb ? ra : rb), ra > rb ? rb : ra);
+    *changed = 1;
+}
+
+__global__ void __launch_bounds__(256) k_prefix_flatten(int32_t* __restrict__ label, int N)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v < N) label[v] = prefix_root(label, v);
+}
+
+// key[e] = label of edge e's component, val[e] = e
+__global__ void __launch_bounds__(256) k_prefix_keys(const int32_t* __restrict__ lo, const int32_t* __restrict__ label,
+                                                     int R, int N, uint32_t* __restrict__ key, uint32_t* __restrict__ val)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= R) return;
+    const int a = lo[e];
+    key[e] = (unsigned int)a < (unsigned int)N ? (uint32_t)label[a] : 0u;
+    val[e] = (uint32_t)e;
+}
+
+// end points of the grouped edges in list order
+__global__ void __launch_bounds__(256) k_prefix_gather(const int32_t* __restrict__ lo, const int32_t* __restrict__ hi,
+                                                       const uint32_t* __restrict__ listed, int R,
+                                                       int32_t* __restrict__ glo, int32_t* __restrict__ ghi)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= R) return;
+    const uint32_t e = listed[j];
+    const bool ok = e < (uint32_t)R;
+    glo[j] = ok ? lo[e] : -1;
+    ghi[j] = ok ? hi[e] : -1;
+}
+
+// children / sizes computed in list order back to edge order
+__global__ void __launch_bounds__(256) k_prefix_scatter(const uint32_t* __restrict__ listed, const int32_t* __restrict__ cj,
+                                                        const int32_t* __restrict__ sj, int R,
+                                                        int32_t* __restrict__ children, int32_t* __restrict__ sizes)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= R) return;
+    const uint32_t e = listed[j];
+    if (e >= (uint32_t)R) return;
+    children[2 * (size_t)e] = cj[2 * (size_t)j];
+    children[2 * (size_t)e + 1] = cj[2 * (size_t)j + 1];
+    sizes[e] = sj[j];
+}
+
+hipError_t prefix_forest_gather(const int32_t* lo, const int32_t* hi, const uint32_t* listed, int R, int32_t* glo,
+                                int32_t* ghi, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_prefix_gather, dim3((R + 255) / 256), dim3(256), 0, s, lo, hi, listed, R, glo, ghi);
+    return hipGetLastError();
+}
+
+hipError_t prefix_forest_scatter(const uint32_t* listed, const int32_t* cj, const int32_t* sj, int R, int32_t* children,
+                                 int32_t* sizes, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_prefix_scatter, dim3((R + 255) / 256), dim3(256), 0, s, listed, cj, sj, R, children, sizes);
+    return hipGetLastError();
+}
+
+hipError_t prefix_forest_pass(const int32_t* lo, const int32_t* hi, int R, int N, int32_t* label, int32_t* changed,
+                              bool first, hipStream_t s)
+{
+    if (first) hipLaunchKernelGGL(k_prefix_init, dim3((N + 255) / 256), dim3(256), 0, s, label, N);
+    hipLaunchKernelGGL(k_prefix_hook, dim3((R + 255) / 256), dim3(256), 0, s, lo, hi, R, N, label, changed);
+    hipLaunchKernelGGL(k_prefix_flatten, dim3((N + 255) / 256), dim3(256), 0, s, label, N);
+    return hipGetLastError();
+}
+
+hipError_t prefix_forest_keys(const int32_t* lo, const int32_t* label, int R, int N, uint32_t* key, uint32_t* val,
+                              hipStream_t s)
+{
+    hipLaunchKernelGGL(k_prefix_keys, dim3((R + 255) / 256), dim3(256), 0, s, lo, label, R, N, key, val);
+    return hipGetLastError();
+}
+
 size_t edge_sort_temp_bytes(int E)
 {
     size_t a = 0, b = 0;

@@ -12,7 +12,9 @@
 #include <cstring>
 #include <exception>
 #include <mutex>
+#include <memory>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "../../include/slhc.h"
@@ -173,6 +175,11 @@ constexpr float LOWER_FACTOR = SLHC_LOWER_FACTOR;
 #endif
 constexpr int LOWER_MIN_ROWS = SLHC_LOWER_MIN_ROWS;
 constexpr int NESTED_K = 8;
+// dendrogram: from this many rows on, host threads share the light edges (see build_dendrogram_parallel)
+#ifndef SLHC_DENDROGRAM_THREADS_MIN_ROWS
+#define SLHC_DENDROGRAM_THREADS_MIN_ROWS 200000
+#endif
+constexpr int64_t DENDROGRAM_THREADS_MIN_ROWS = SLHC_DENDROGRAM_THREADS_MIN_ROWS;
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
 #ifndef SLHC_PIVOT_STRIDE
 #define SLHC_PIVOT_STRIDE 64
@@ -268,7 +275,7 @@ struct SlhcWs {
         best_w = c.take<uint32_t>(n); min_lb = c.take<uint32_t>(n);
         vals_a = c.take<uint32_t>(n); vals_b = c.take<uint32_t>(n);
         best_e = c.take<unsigned long long>(n); keys_a = c.take<unsigned long long>(n); keys_b = c.take<unsigned long long>(n);
-        sort_temp_bytes = slhc::edge_sort_temp_bytes((int)(N - 1));
+        sort_temp_bytes = std::max(slhc::edge_sort_temp_bytes((int)(N - 1)), slhc::pair_sort_temp_bytes((int)N));   // the second: grouping the dendrogram's edges
         sort_temp = c.take<unsigned char>(sort_temp_bytes);
         bytes = c.off;
     }
@@ -524,37 +531,107 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
 // merge; merge i creates node N+i.  The edges arrive in weight order, so their end points are
 // scattered over the whole array: one 16-byte record per point keeps a find step to one cache
 // line, and the records of the edges a few iterations ahead, then their parents, are prefetched.
-void build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* children, int32_t* sizes)
-{
+//
+// Merges inside different components of the forest made of the first R edges do not see each other, so
+// those components can be worked through by different threads, each in edge order, on one shared array (no
+// two of them touch the same record); the edges from R on follow on one thread.  `listed`: those first R
+// edge indices grouped by component, ascending inside a component.
+struct DendrogramBuilder {
     struct PointSet { int32_t up, count, node, unused; };
-    std::vector<PointSet> set((size_t)N);
-    for (int64_t v = 0; v < N; ++v) set[(size_t)v] = PointSet{(int32_t)v, 1, (int32_t)v, 0};
-    auto root = [&](int32_t a) {
+    std::unique_ptr<PointSet[]> set;
+    int64_t N;
+    static constexpr int64_t AHEAD = 16;
+
+    explicit DendrogramBuilder(int64_t N_) : set(new PointSet[(size_t)N_]), N(N_) {}
+    void init(int64_t v0, int64_t v1) { for (int64_t v = v0; v < v1; ++v) set[(size_t)v] = PointSet{(int32_t)v, 1, (int32_t)v, 0}; }
+    int32_t root(int32_t a)
+    {
         while (set[(size_t)a].up != a) {
             set[(size_t)a].up = set[(size_t)set[(size_t)a].up].up;
             a = set[(size_t)a].up;
         }
         return a;
-    };
-    constexpr int64_t AHEAD = 16;
-    for (int64_t i = 0; i < N - 1; ++i) {
-        if (i + AHEAD < N - 1) {
-            __builtin_prefetch(&set[(size_t)lo[i + AHEAD]]);
-            __builtin_prefetch(&set[(size_t)hi[i + AHEAD]]);
-            // and, half way, the records those point to (their own have arrived by now)
-            __builtin_prefetch(&set[(size_t)set[(size_t)lo[i + AHEAD / 2]].up]);
-            __builtin_prefetch(&set[(size_t)set[(size_t)hi[i + AHEAD / 2]].up]);
-        }
-        int32_t ra = root(lo[i]), rb = root(hi[i]);
-        const int32_t a = set[(size_t)ra].node, b = set[(size_t)rb].node;
-        children[2 * i] = a < b ? a : b;
-        children[2 * i + 1] = a < b ? b : a;
-        if (set[(size_t)ra].count < set[(size_t)rb].count) std::swap(ra, rb);
-        set[(size_t)rb].up = ra;
-        set[(size_t)ra].count += set[(size_t)rb].count;
-        set[(size_t)ra].node = (int32_t)(N + i);
-        sizes[i] = set[(size_t)ra].count;
     }
+    // Edges j0 .. j1-1 of the streams lo / hi, in order; edge j is merge `first_merge + j`, or merge ids[j]
+    // when `ids` is given; its children go to children[2 j ..], its size to sizes[j].  End points outside
+    // [0, N) (never produced by a correct caller) are skipped and reported by `false`.
+    bool run(const int32_t* lo, const int32_t* hi, const uint32_t* ids, int64_t first_merge, int64_t j0, int64_t j1,
+             int32_t* children, int32_t* sizes)
+    {
+        bool good = true;
+        const uint32_t n = (uint32_t)N;
+        for (int64_t j = j0; j < j1; ++j) {
+            if (j + AHEAD < j1 && (uint32_t)lo[j + AHEAD] < n && (uint32_t)hi[j + AHEAD] < n) {
+                __builtin_prefetch(&set[(size_t)lo[j + AHEAD]]);
+                __builtin_prefetch(&set[(size_t)hi[j + AHEAD]]);
+                // and, half way, the records those point to (their own have arrived by now)
+                __builtin_prefetch(&set[(size_t)set[(size_t)lo[j + AHEAD / 2]].up]);
+                __builtin_prefetch(&set[(size_t)set[(size_t)hi[j + AHEAD / 2]].up]);
+            }
+            if ((uint32_t)lo[j] >= n || (uint32_t)hi[j] >= n) { good = false; continue; }
+            int32_t ra = root(lo[j]), rb = root(hi[j]);
+            const int32_t a = set[(size_t)ra].node, b = set[(size_t)rb].node;
+            children[2 * j] = a < b ? a : b;
+            children[2 * j + 1] = a < b ? b : a;
+            if (set[(size_t)ra].count < set[(size_t)rb].count) std::swap(ra, rb);
+            set[(size_t)rb].up = ra;
+            set[(size_t)ra].count += set[(size_t)rb].count;
+            set[(size_t)ra].node = (int32_t)(N + (ids ? (int64_t)ids[j] : first_merge + j));
+            sizes[j] = set[(size_t)ra].count;
+        }
+        return good;
+    }
+};
+
+bool build_dendrogram(const int32_t* lo, const int32_t* hi, int64_t N, int32_t* children, int32_t* sizes)
+{
+    DendrogramBuilder b(N);
+    b.init(0, N);
+    return b.run(lo, hi, nullptr, 0, 0, N - 1, children, sizes);
+}
+
+// The same with `threads` host threads for the first R merges.  Those come grouped by component (`key`,
+// equal keys adjacent) and in merge order inside a group: glo / ghi / ids [R] are their end points and merge
+// numbers in that order, and their children and sizes are written in that order too (cj [2R], sj [R]).
+// Thread t takes the t-th share of the list, moved forward at both ends to the next group boundary.
+// The merges from R on follow on one thread: tlo / thi are their end points, tc / ts their output.
+bool build_dendrogram_parallel(int64_t N, int64_t R, const uint32_t* key, const int32_t* glo, const int32_t* ghi,
+                               const uint32_t* ids, int32_t* cj, int32_t* sj, const int32_t* tlo, const int32_t* thi,
+                               int32_t* tc, int32_t* ts, int threads)
+{
+    // joins what was started even when starting another thread throws
+    struct Pool {
+        std::vector<std::thread> v;
+        void join() { for (auto& th : v) if (th.joinable()) th.join(); }
+        ~Pool() { join(); }
+    };
+    DendrogramBuilder b(N);
+    {
+        Pool pool;
+        for (int t = 0; t < threads; ++t)
+            pool.v.emplace_back([&b, N, t, threads] { b.init(N * t / threads, N * (t + 1) / threads); });
+        pool.join();
+    }
+    {
+        auto boundary = [&](int64_t j) { while (j > 0 && j < R && key[j] == key[j - 1]) ++j; return j; };
+        std::vector<char> good((size_t)threads, 1);
+        Pool pool;
+        for (int t = 0; t < threads; ++t) {
+            const int64_t j0 = boundary(R * t / threads), j1 = t + 1 == threads ? R : boundary(R * (t + 1) / threads);
+            char* mine = &good[(size_t)t];
+            pool.v.emplace_back([&b, glo, ghi, ids, cj, sj, j0, j1, mine] { *mine = b.run(glo, ghi, ids, 0, j0, j1, cj, sj) ? 1 : 0; });
+        }
+        pool.join();
+        for (char g : good) if (!g) return false;
+    }
+    return b.run(tlo, thi, nullptr, R, 0, N - 1 - R, tc, ts);
+}
+
+int host_threads()
+{
+    int t = (int)std::thread::hardware_concurrency();
+    if (const char* e = std::getenv("SLHC_HOST_THREADS")) { const int v = std::atoi(e); if (v >= 1) t = v; }
+    return t < 1 ? 1 : (t > 16 ? 16 : t);
 }
 
 // ---- scratch of slhc_knn_graph_static: the workspace of the unpruned k-NN path (counters + one
@@ -1272,20 +1349,74 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     st.ms_sort = (float)(t_sort - t_forest);
 
     const size_t E = (size_t)(N - 1);
+    // Large trees: all but the heaviest sixteenth of the edges are grouped by the component they lie in when
+    // only those edges are there (labels on the device, a stable sort by label), and host threads share the
+    // groups; see build_dendrogram_parallel.  The arrays of the forest rounds are free by now.
+    const int threads = host_threads();
+    int64_t R = 0;
+    uint32_t* key_sorted = reinterpret_cast<uint32_t*>(ws.ptr);
+    uint32_t* listed = reinterpret_cast<uint32_t*>(ws.hook);
+    int32_t* glo = ws.qlist;
+    int32_t* ghi = ws.cand_u;
+    if (N >= DENDROGRAM_THREADS_MIN_ROWS && threads >= 2) {
+        const int64_t heavy = (int64_t)E / 16 > 4096 ? (int64_t)E / 16 : 4096;
+        R = (int64_t)E - heavy;
+        int32_t* changed = ws.counters + 8;
+        int32_t* h_changed = reinterpret_cast<int32_t*>(h_surv + 7);      // last word of the 64-byte staging buffer
+        bool settled = false;
+        for (int pass = 0; pass < 64 && !settled; ++pass) {
+            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(changed), 1);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(slhc::prefix_forest_pass(mst_src, mst_dst, (int)R, (int)N, ws.colour, changed, pass == 0, s));
+            HIP_TRY(hipMemcpyAsync(h_changed, changed, 4, hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            settled = *h_changed == 0;
+        }
+        if (settled) {
+            HIP_TRY(slhc::prefix_forest_keys(mst_src, ws.colour, (int)R, (int)N, ws.vals_a, ws.vals_b, s));
+            HIP_TRY(slhc::pair_sort_u32(ws.vals_a, key_sorted, ws.vals_b, listed, (int)R, bits_for(N), ws.sort_temp,
+                                        ws.sort_temp_bytes, s));
+            HIP_TRY(slhc::prefix_forest_gather(mst_src, mst_dst, listed, (int)R, glo, ghi, s));
+        } else {
+            R = 0;
+        }
+    }
+    // host staging: end points (grouped part in list order, then the rest in edge order), keys and merge numbers
+    // of the grouped part, children and sizes in the same two parts
+    const size_t Rz = (size_t)R, Tz = E - Rz;
     PinnedHost pin_edges;
-    HIP_TRY(pin_edges.alloc(E * 5 * sizeof(int32_t)));
-    int32_t* h_lo = static_cast<int32_t*>(pin_edges.p);
+    HIP_TRY(pin_edges.alloc((5 * E + 2 * Rz + 16) * sizeof(int32_t)));
+    int32_t* h_lo = static_cast<int32_t*>(pin_edges.p);     // [R] grouped, [E - R] rest
     int32_t* h_hi = h_lo + E;
-    int32_t* h_children = h_hi + E;          // 2E entries
+    int32_t* h_children = h_hi + E;                         // 2E entries, same two parts
     int32_t* h_sizes = h_children + 2 * E;
-    HIP_TRY(hipMemcpyAsync(h_lo, mst_src, E * 4, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(h_hi, mst_dst, E * 4, hipMemcpyDeviceToHost, s));
+    uint32_t* h_key = reinterpret_cast<uint32_t*>(h_sizes + E);
+    uint32_t* h_ids = h_key + Rz;
+    if (Rz) {
+        HIP_TRY(hipMemcpyAsync(h_lo, glo, Rz * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_hi, ghi, Rz * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_key, key_sorted, Rz * 4, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipMemcpyAsync(h_ids, listed, Rz * 4, hipMemcpyDeviceToHost, s));
+    }
+    HIP_TRY(hipMemcpyAsync(h_lo + Rz, mst_src + Rz, Tz * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_hi + Rz, mst_dst + Rz, Tz * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    log.mark("dendrogram: %zu edges staged on the host", E);
-    build_dendrogram(h_lo, h_hi, N, h_children, h_sizes);
+    log.mark("dendrogram: %zu edges staged on the host (%lld grouped for %d threads)", E, (long long)R, threads);
+    const bool good = Rz ? build_dendrogram_parallel(N, R, h_key, h_lo, h_hi, h_ids, h_children, h_sizes, h_lo + Rz, h_hi + Rz,
+                                                     h_children + 2 * Rz, h_sizes + Rz, threads)
+                         : build_dendrogram(h_lo, h_hi, N, h_children, h_sizes);
+    if (!good) { set_err("dendrogram: an edge of the sorted tree has an end point outside [0, N)"); return SLHC_INTERNAL; }
     log.mark("dendrogram: union-find");
-    HIP_TRY(hipMemcpyAsync(children, h_children, E * 8, hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(sizes, h_sizes, E * 4, hipMemcpyHostToDevice, s));
+    if (Rz) {
+        // the grouped part goes back to edge order on the device (the sort's scratch arrays are free again)
+        int32_t* cj = reinterpret_cast<int32_t*>(ws.keys_a);            // 2R words of the N 64-bit words
+        int32_t* sj = reinterpret_cast<int32_t*>(ws.vals_a);
+        HIP_TRY(hipMemcpyAsync(cj, h_children, Rz * 8, hipMemcpyHostToDevice, s));
+        HIP_TRY(hipMemcpyAsync(sj, h_sizes, Rz * 4, hipMemcpyHostToDevice, s));
+        HIP_TRY(slhc::prefix_forest_scatter(listed, cj, sj, (int)R, children, sizes, s));
+    }
+    HIP_TRY(hipMemcpyAsync(children + 2 * Rz, h_children + 2 * Rz, Tz * 8, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(sizes + Rz, h_sizes + Rz, Tz * 4, hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));
     const double t_end = now_ms();
     st.ms_dendrogram = (float)(t_end - t_sort);

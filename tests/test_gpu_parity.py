@@ -907,6 +907,32 @@ def test_streaming_1nn_many_query_panels(lib):
     assert (fi[rows] == oi - N).mean() >= 0.99
 
 
+# ----------------------------------------------------------------------------- dendrogram on several host threads
+def test_threaded_dendrogram_equals_oracle(lib):
+    """From 200 000 rows on the library groups all but the heaviest sixteenth of the tree edges by the
+    component they lie in without the heavy ones, and host threads work through the groups side by side.
+    The result must be the sequential relabelling of the same sorted edges (paper Sec. 3.3.1), which is
+    what the oracle computes: many blobs (many groups), one blob (one giant group), duplicates (ties)."""
+    rng = np.random.default_rng(4242)
+    cases = [dict(N=300_000, d=8, k=4, nb=500, spread=50.0, sigma=1.0, dup=0),
+             dict(N=250_000, d=4, k=4, nb=1, spread=0.0, sigma=1.0, dup=0),
+             dict(N=220_000, d=16, k=6, nb=40, spread=30.0, sigma=1.0, dup=30_000)]
+    for c in cases:
+        N, d, k = c["N"], c["d"], c["k"]
+        centres = rng.uniform(-c["spread"], c["spread"], size=(c["nb"], d)) if c["nb"] > 1 else np.zeros((1, d))
+        X = (centres[rng.integers(0, c["nb"], size=N)] + c["sigma"] * rng.standard_normal((N, d))).astype(np.float32)
+        if c["dup"]:
+            X[rng.integers(0, N, size=c["dup"])] = X[rng.integers(0, N, size=c["dup"])]
+        print(f"threaded dendrogram: N={N} d={d} k={k} blobs={c['nb']} duplicates={c['dup']}", flush=True)
+        out = lib.slhc(torch.from_numpy(np.ascontiguousarray(X)).cuda(), k)
+        src, dst, w = (out[n].cpu().numpy() for n in ("mst_src", "mst_dst", "mst_w"))
+        ref = oracle.dendrogram(src, dst, w.astype(np.float64), N)
+        assert np.array_equal(ref["src"], src) and np.array_equal(ref["dst"], dst), "edge order differs from (w, lo, hi)"
+        assert np.array_equal(out["children"].cpu().numpy(), ref["children"])
+        assert np.array_equal(out["sizes"].cpu().numpy(), ref["sizes"])
+        assert np.array_equal(out["heights"].cpu().numpy(), w)
+
+
 # ----------------------------------------------------------------------------- two-phase connection rounds
 def test_split_connection_rounds_are_identical(lib):
     """SLHC_SPLIT_ROUNDS runs every pruned connection round of 256 rows or more in two phases (a sample
