@@ -180,6 +180,60 @@ __global__ void __launch_bounds__(TB) k_tile_balls(const float* __restrict__ Xs,
     if (threadIdx.x == 0) tile_r[t] = cnt > 0 ? __uint_as_float(*rbits) : -3.0e38f;
 }
 
+// Lower bounds between all pairs of tile balls: gaps[p * T + t] = max(0, |c_p - c_t| - r_p - r_t)^2, rounded
+// towards zero (the centre distance may come out 2e-5 too large, the radii 2e-5 too small), NaN where tile t
+// has no valid row (r_t < 0): the table a pruned sweep otherwise computes for every query panel.
+// One workgroup per patch of 64 x 64 pairs; feature columns pass through LDS 32 at a time.
+__global__ void __launch_bounds__(TB) k_tile_gaps(const float* __restrict__ tile_c, const float* __restrict__ tile_r,
+                                                  int T, int d, float* __restrict__ gaps)
+{
+    __shared__ float P[64][33];
+    __shared__ float Q[64][33];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;        // 16 x 16 threads, 4 x 4 pairs each
+    const int p0 = blockIdx.y * 64, t0 = blockIdx.x * 64;
+    float s2[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s2[i][j] = 0.f;
+    for (int c0 = 0; c0 < d; c0 += 32) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < 64 * 32; e += TB) {
+            const int r = e >> 5, c = e & 31;
+            const bool live = c0 + c < d;
+            P[r][c] = (live && p0 + r < T) ? tile_c[(size_t)(p0 + r) * d + c0 + c] : 0.f;
+            Q[r][c] = (live && t0 + r < T) ? tile_c[(size_t)(t0 + r) * d + c0 + c] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 0; c < 32; ++c) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = P[ty + 16 * i][c]; b[i] = Q[tx + 16 * i][c]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { const float e = a[i] - b[j]; s2[i][j] = __builtin_fmaf(e, e, s2[i][j]); }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int pr = p0 + ty + 16 * i;
+        if (pr >= T) continue;
+        const float rp = tile_r[pr];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int tc = t0 + tx + 16 * j;
+            if (tc >= T) continue;
+            const float rt = tile_r[tc];
+            const float g = __builtin_sqrtf(s2[i][j]) * (1.f - 2e-5f) - (rp + rt) * (1.f + 2e-5f);
+            float lb = g > 0.f ? g * g * (1.f - 1e-5f) : 0.f;
+            if (rt < 0.f || rp < 0.f) lb = __builtin_nanf("");
+            gaps[(size_t)pr * T + tc] = lb;
+        }
+    }
+}
+
 static bool vec4_ok(const void* a, const void* b, int d)
 {
     return d % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0;
@@ -353,6 +407,14 @@ hipError_t order_adopt_pivots(const uint32_t* list, int m, int N, const int32_t*
 {
     hipLaunchKernelGGL(k_adopt_pivots, dim3(blocks_for(m)), dim3(TB), 0, s, list, m, N, new_idx, new_dist, base, count,
                        pid, pdist);
+    return hipGetLastError();
+}
+
+hipError_t order_tile_gaps(const float* tile_c, const float* tile_r, int T, int d, float* gaps, hipStream_t s)
+{
+    if (T < 1) return hipSuccess;
+    const int patches = (T + 63) / 64;
+    hipLaunchKernelGGL(k_tile_gaps, dim3(patches, patches), dim3(TB), 0, s, tile_c, tile_r, T, d, gaps);
     return hipGetLastError();
 }
 

@@ -175,6 +175,12 @@ constexpr float LOWER_FACTOR = SLHC_LOWER_FACTOR;
 #endif
 constexpr int LOWER_MIN_ROWS = SLHC_LOWER_MIN_ROWS;
 constexpr int NESTED_K = 8;
+// up to this many tiles of the reordered copy the lower bounds between all pairs of tiles are tabulated once
+// (T x T floats: 4 GiB at the limit) instead of being computed for every query panel of every pruned sweep
+#ifndef SLHC_TILE_GAP_MAX_TILES
+#define SLHC_TILE_GAP_MAX_TILES 32768
+#endif
+constexpr int TILE_GAP_MAX_TILES = SLHC_TILE_GAP_MAX_TILES;
 // dendrogram: from this many rows on, host threads share the light edges (see build_dendrogram_parallel)
 #ifndef SLHC_DENDROGRAM_THREADS_MIN_ROWS
 #define SLHC_DENDROGRAM_THREADS_MIN_ROWS 200000
@@ -193,7 +199,7 @@ size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {
-    float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *n_w, *n_heights;
+    float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *tile_gap, *n_w, *n_heights;
     int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
     uint32_t *tmp_a, *tmp_b, *tmp_c;
@@ -219,6 +225,8 @@ struct OrderWs {
         int grid = slhc::sweep_grid_limit();
         if (grid < 1) grid = 512;
         gap_ws = c.take<float>((size_t)grid * Tmax);
+        // lower bounds between all pairs of tiles (order_tile_gaps), as long as the table stays moderate
+        tile_gap = Tmax <= TILE_GAP_MAX_TILES ? c.take<float>((size_t)Tmax * Tmax) : nullptr;
         pid = c.take<int32_t>(n); perm = c.take<int32_t>(nm); inv = c.take<int32_t>(n); colour_s = c.take<int32_t>(nm);
         qslot = c.take<int32_t>(nm); tile_colour = c.take<int32_t>((size_t)Tmax);
         counts = c.take<int32_t>(pm); rank = c.take<int32_t>(pm); shift = c.take<int32_t>(pm); far_count = c.take<int32_t>(64);
@@ -476,6 +484,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, const uns
     HIP_TRY(slhc::order_scatter(o.tmp_b, o.tmp_c, o.shift, n, P, o.Ns, o.perm, o.inv, s));
     HIP_TRY(slhc::order_gather_padded(X, hn, o.perm, o.Ns, n, d, o.Xs, o.hs, s));
     HIP_TRY(slhc::order_tile_balls(o.Xs, o.perm, o.Ns, d, o.tile_c, o.tile_r, s));
+    if (o.tile_gap) HIP_TRY(slhc::order_tile_gaps(o.tile_c, o.tile_r, (o.Ns + 127) / 128, d, o.tile_gap, s));
     HIP_TRY(hipStreamSynchronize(s));        // the pinned staging buffer is released on return
     log.mark("row order: %d rows placed in %d (tau %.4g, padding above %.4g), tile balls", n, o.Ns, (double)tau, (double)tau_pad);
     return SLHC_OK;
@@ -510,6 +519,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
         p.q_out_row = o.perm; p.c_id = o.perm;
         p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
+        p.tile_gap = o.tile_gap;
         p.own_tile_first = 1;
         p.panel_counter = reinterpret_cast<unsigned int*>(ws.counters + 8);     // zeroed above
 #ifdef SLHC_PHASE_TIMERS
@@ -1219,6 +1229,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.qslot = o.qslot;
                     p.c_id = o.perm;
                     p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
+                    p.tile_gap = o.tile_gap;
                     p.tile_colour = o.tile_colour;
                     // thresholds shared by the queries of a component: what the forest already knows (a
                     // working copy that the sweep lowers further as its queries find lighter edges;
@@ -1243,12 +1254,30 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.qcolour = p.ccolour = ws.colour;
                     p.rows = rows;
                 }
+#ifdef SLHC_STUDY_PANEL_STEPS
+                int* study_steps = reinterpret_cast<int*>(ws.keys_b);
+                const int study_panels = (kws.order.Ns + 127) / 128;
+                if (round_pruned) { HIP_TRY(hipMemsetAsync(study_steps, 0, (size_t)study_panels * 8, s)); p.panel_steps = study_steps; }
+#endif
                 HIP_TRY(hipEventRecord(ev_conn.a, s));
                 // keys_a is free until the edge sort (the two-phase split above uses it in pruned rounds only)
                 HIP_TRY(slhc::launch_segmented_cross_1nn(p, round_pruned ? nullptr : ws.keys_a, s));
                 HIP_TRY(hipEventRecord(ev_conn.b, s));
                 HIP_TRY(slhc::forest_apply_queries(f, rows, ws.q_idx, ws.q_dist, n, round_pruned ? ws.vals_a : nullptr, s));
                 HIP_TRY(hipStreamSynchronize(s));
+#ifdef SLHC_STUDY_PANEL_STEPS
+                if (round_pruned) {
+                    std::vector<int> hs((size_t)study_panels * 2);
+                    HIP_TRY(hipMemcpy(hs.data(), study_steps, hs.size() * 4, hipMemcpyDeviceToHost));
+                    std::vector<int> order_((size_t)study_panels);
+                    for (int i = 0; i < study_panels; ++i) order_[(size_t)i] = i;
+                    std::sort(order_.begin(), order_.end(), [&](int a, int b) { return hs[(size_t)study_panels + a] > hs[(size_t)study_panels + b]; });
+                    long long tot_steps = 0, tot_cyc = 0; int used = 0;
+                    for (int i = 0; i < study_panels; ++i) { tot_steps += hs[(size_t)i]; tot_cyc += hs[(size_t)study_panels + i]; used += hs[(size_t)study_panels + i] > 0; }
+                    std::fprintf(stderr, "[study] %d rows, %d panels used, steps %lld, kcycles %lld (per WG slot %.0f), kernel %.2f ms\n", n, used, tot_steps, tot_cyc, tot_cyc / 512.0, ev_conn.ms());
+                    for (int r = 0; r < 12; ++r) { const int i = order_[(size_t)r]; std::fprintf(stderr, "[study]   panel %d: steps %d kcycles %d\n", i, hs[(size_t)i], hs[(size_t)study_panels + i]); }
+                }
+#endif
                 ms_round_kernels += ev_conn.ms();
                 return SLHC_OK;
             };

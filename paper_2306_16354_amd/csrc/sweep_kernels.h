@@ -33,6 +33,11 @@ struct SweepParams {
     const float* tile_c;
     const float* tile_r;
     float* gap_ws;
+    // optional [T, T] (order_tile_gaps): the lower bounds between all pairs of tile balls.  A panel whose query
+    // rows are (a subset of) the rows of candidate tile `panel` - a self-join in the same row order with
+    // own_tile_first, or the slot map `qslot` - then reads its row of this table instead of computing a ball
+    // of its own and T lower bounds (for a subset the table's bounds are a little looser, never wrong).
+    const float* tile_gap;
     const int32_t* tile_colour;   // cross 1-NN only, optional [T]: the colour all valid rows of a tile
                                   // share, or -1; a tile in the colour of all the panel's queries is skipped
     // cross 1-NN with pruning, optional: comp_best[c] (c < comp_count) is the lightest edge weight already
@@ -73,6 +78,9 @@ struct SweepParams {
     unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
 #ifdef SLHC_PHASE_TIMERS
     unsigned long long* phase_cycles;   // study builds: [8] cycles per phase of the panel loop
+#endif
+#ifdef SLHC_STUDY_PANEL_STEPS
+    int* panel_steps;                   // study builds: [npanels] multiplied tiles and [npanels] cycles per panel
 #endif
 };
 

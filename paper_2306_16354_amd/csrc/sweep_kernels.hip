@@ -916,7 +916,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     const int ld_row = tid >> 3;          // 0..31 (+32 i)
     const int ld_col = (tid & 7) * 4;     // 0..28
     constexpr bool prune = PRUNE;         // p.tile_c, p.tile_r and p.gap_ws are given
-    float* __restrict__ gap = prune ? p.gap_ws + (size_t)blockIdx.x * ntiles : nullptr;
+    float* __restrict__ gap_own = prune ? p.gap_ws + (size_t)blockIdx.x * ntiles : nullptr;
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
     unsigned long long tiles_done = 0;
@@ -936,6 +936,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             panel = *next_panel;
         }
         if (panel >= npanels) break;
+#ifdef SLHC_STUDY_PANEL_STEPS
+        const long long study_t0 = clock64();
+#endif
         if (tid < BM) {
             const int qi = panel * BM + tid;
             int row = -1;
@@ -961,6 +964,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         PHASE_MARK(0);
 
         int panel_colour = -2;       // the colour all queries of the panel share (-2: they differ / unknown)
+        // lower bounds of this panel against every candidate tile: its row of the table of all tile pairs when
+        // the panel's rows lie in candidate tile `panel`, else computed here from a ball of the panel's own
+        const bool table_row = prune && p.tile_gap != nullptr && panel < ntiles &&
+                               (MASKED ? aligned : (p.own_tile_first != 0));
+        const float* __restrict__ gap = table_row ? p.tile_gap + (size_t)panel * ntiles : gap_own;
         if (prune) {
             // ---- bounding ball of the panel's query rows (L.Cs is free here: d <= 128 floats)
             float* qc = L.Cs;                       // centre
@@ -968,7 +976,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             int* col_lo = reinterpret_cast<int*>(L.Cs + 257);
             int* col_hi = reinterpret_cast<int*>(L.Cs + 258);
             if (tid == 0) { *rq_bits = 0u; *col_lo = 0x7fffffff; *col_hi = -0x7fffffff - 1; }
-            {
+            if (!table_row) {
                 // partial column sums by groups of rows (fixed assignment and order: the centre is
                 // the same in every run), then one thread per column adds the partial sums
                 float* part = L.Cs + 512;           // [groups][d]
@@ -994,10 +1002,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
             __syncthreads();
             if (tid < BM && qid[tid] >= 0) {
-                const float* x = Xq + (size_t)qid[tid] * d;
-                float s2 = 0.f;
-                for (int t = 0; t < d; ++t) { const float e = x[t] - qc[t]; s2 = __builtin_fmaf(e, e, s2); }
-                atomicMax(rq_bits, __float_as_uint(__builtin_sqrtf(s2)));
+                if (!table_row) {
+                    const float* x = Xq + (size_t)qid[tid] * d;
+                    float s2 = 0.f;
+                    for (int t = 0; t < d; ++t) { const float e = x[t] - qc[t]; s2 = __builtin_fmaf(e, e, s2); }
+                    atomicMax(rq_bits, __float_as_uint(__builtin_sqrtf(s2)));
+                }
                 if (MASKED && p.tile_colour) {
                     const int c = p.qcolour[qid[tid]];
                     atomicMin(col_lo, c);
@@ -1008,7 +1018,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             const float rq = __uint_as_float(*rq_bits);
             // the colour all queries of the panel share (-2: they differ, or no colour summary)
             panel_colour = (MASKED && p.tile_colour && *col_lo == *col_hi) ? *col_lo : -2;
-            for (int t = tid; t < ntiles; t += WG_THREADS) {
+            for (int t = tid; t < (table_row ? 0 : ntiles); t += WG_THREADS) {
                 const float* c = p.tile_c + (size_t)t * d;
                 float s2 = 0.f;
                 for (int j = 0; j < d; j += 4) {
@@ -1028,10 +1038,18 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 // it has the colour all queries of this panel have
                 if (rt < 0.f) lb = __builtin_nanf("");
                 if (MASKED && p.tile_colour && p.tile_colour[t] == panel_colour) lb = __builtin_nanf("");
-                gap[t] = lb;
+                gap_own[t] = lb;
             }
             __syncthreads();
         }
+        // (a row of the table knows nothing of colours: tiles in the colour of all the panel's queries are
+        // sorted out where the bounds are read)
+        const bool own_colour_test = MASKED && table_row && p.tile_colour != nullptr && panel_colour >= 0;
+        auto gap_of = [&](int t) -> float {
+            float g = gap[t];
+            if (own_colour_test && p.tile_colour[t] == panel_colour) g = __builtin_nanf("");
+            return g;
+        };
         PHASE_MARK(1);
 
         const int my_q_local = wave * 32 + l32;
@@ -1113,7 +1131,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             while (i < nscan) {
                 const int ii = i + lane;
                 bool need = false;
-                if (ii < nscan) need = gap[scan_tile(ii)] <= thr_max;          // false for NaN
+                if (ii < nscan) need = gap_of(scan_tile(ii)) <= thr_max;          // false for NaN
                 const unsigned long long mask = __ballot(need);
                 if (mask) return i + __builtin_ctzll(mask);
                 i += 64;
@@ -1169,7 +1187,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             scan_from = first + 1;
         }
         float ahead_gap = __builtin_nanf("");          // lower bound of scan position scan_from + lane (NaN: none)
-        if (prune) ahead_gap = scan_from + lane < nscan ? gap[scan_tile(scan_from + lane)] : __builtin_nanf("");
+        if (prune) ahead_gap = scan_from + lane < nscan ? gap_of(scan_tile(scan_from + lane)) : __builtin_nanf("");
  if (tile < ntiles) gload(tile, 0);
         PHASE_MARK(2);
         // largest threshold of this wavefront's 32 queries, from their bounds: thr = 2 (h_q - bound)
@@ -1243,7 +1261,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     scan_from = nxt + 1;
                     tile_after = tile_of(nxt);
                     if (tile_after < ntiles) gload(tile_after, 0);
-                    if (prune) ahead_gap = scan_from + lane < nscan ? gap[scan_tile(scan_from + lane)] : __builtin_nanf("");
+                    if (prune) ahead_gap = scan_from + lane < nscan ? gap_of(scan_tile(scan_from + lane)) : __builtin_nanf("");
                     __builtin_amdgcn_sched_barrier(0);
                     PHASE_MARK(4);
                 }
@@ -1482,6 +1500,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             tile = tile_after;
         }
 
+#ifdef SLHC_STUDY_PANEL_STEPS
+        if (p.panel_steps && tid == 0) { p.panel_steps[panel] = step; p.panel_steps[npanels + panel] = (int)((clock64() - study_t0) >> 10); }
+#endif
         // ---- panel epilogue: lists are already ascending; write them out ----
         if (!PRUNE) {
             const int waiting_ = *deferred_count(L, wave);
