@@ -103,6 +103,11 @@ typedef struct slhc_stats {
                            (a sample of the row panels first, the rest under the thresholds that
                            leaves), which the library otherwise does only for rounds of >= 262144
                            rows under loose thresholds.  Same outputs.                          */
+#define SLHC_SPLIT_SCANS 4u    /* slhc_slhc_opt with SLHC_PRUNE only; a testing and tuning aid.  Every
+                           pruned connection sweep splits each query panel's scan of the candidate
+                           tiles into 5 work items that exchange what they find, which the library
+                           otherwise does (in 2 to 16 parts) only for launches with few panels and
+                           long scans.  Same outputs.                                           */
 
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */

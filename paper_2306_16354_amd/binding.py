@@ -33,6 +33,7 @@ class _Stats(ctypes.Structure):
 
 SLHC_PRUNE = 1
 SLHC_SPLIT_ROUNDS = 2
+SLHC_SPLIT_SCANS = 4
 SLHC_STATIC_MAX_ROWS = 1048576
 
 
@@ -195,12 +196,12 @@ def cross_1nn(X, colour, rows=None, m=None):
     return idx, dist
 
 
-def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False):
+def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
     prune=True is slhc_slhc; prune=False multiplies every tile (slhc_slhc_opt with flags 0);
-    split_rounds adds SLHC_SPLIT_ROUNDS."""
+    split_rounds adds SLHC_SPLIT_ROUNDS, split_scans SLHC_SPLIT_SCANS."""
     X = _device_matrix(X)
     N, d = X.shape
     lib = load_library()
@@ -220,7 +221,8 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False):
                              out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
                              out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
                              workspace.numel(), _stream(),
-                             (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0)))
+                             (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
+                             (SLHC_SPLIT_SCANS if split_scans else 0)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

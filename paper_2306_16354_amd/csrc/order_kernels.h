@@ -48,6 +48,9 @@ hipError_t order_adopt_pivots(const uint32_t* list, int m, int N, const int32_t*
 // gaps[p * T + t]: lower bound of the squared distance between any row of tile p and any row of tile t, from their
 // bounding balls (rounded towards zero; NaN where either tile has no valid row).  T x T floats.
 hipError_t order_tile_gaps(const float* tile_c, const float* tile_r, int T, int d, float* gaps, hipStream_t s);
+// *count += number of tiles (128 consecutive entries of slot[0 .. n_padded)) with an entry >= 0; `list` (optional,
+// room for every tile, *count zero at launch) receives their numbers in no particular order
+hipError_t order_count_used_tiles(const int32_t* slot, int n_padded, int32_t* count, int32_t* list, hipStream_t s);
 hipError_t order_tile_colours(const int32_t* colour_s, int n_padded, int32_t* tile_colour, hipStream_t s);
 // slot[inv[list[q]]] = q for q < m (slot pre-filled with -1 by the caller)
 hipError_t order_scatter_slots(const int32_t* inv, const int32_t* list, int m, int N, int n_padded, int32_t* slot,

@@ -410,6 +410,28 @@ hipError_t order_adopt_pivots(const uint32_t* list, int m, int N, const int32_t*
     return hipGetLastError();
 }
 
+// *count += tiles of 128 slots that hold at least one slot >= 0 (one wavefront per tile); their numbers go to
+// list[old *count ...] in no particular order
+__global__ void __launch_bounds__(TB) k_count_used_tiles(const int32_t* __restrict__ slot, int n_padded, int T,
+                                                         int32_t* __restrict__ count, int32_t* __restrict__ list)
+{
+    const int t = (blockIdx.x * TB + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+    if (t >= T) return;
+    const int r0 = t * TILE + lane, r1 = r0 + 64;
+    const bool any = (r0 < n_padded && slot[r0] >= 0) || (r1 < n_padded && slot[r1] >= 0);
+    if (__ballot(any) != 0ull && lane == 0) {
+        const int at = atomicAdd(count, 1);
+        if (list) list[at] = t;
+    }
+}
+
+hipError_t order_count_used_tiles(const int32_t* slot, int n_padded, int32_t* count, int32_t* list, hipStream_t s)
+{
+    const int T = (n_padded + TILE - 1) / TILE;
+    hipLaunchKernelGGL(k_count_used_tiles, dim3(blocks_for((long long)T * 64)), dim3(TB), 0, s, slot, n_padded, T, count, list);
+    return hipGetLastError();
+}
+
 hipError_t order_tile_gaps(const float* tile_c, const float* tile_r, int T, int d, float* gaps, hipStream_t s)
 {
     if (T < 1) return hipSuccess;

@@ -175,6 +175,19 @@ constexpr float LOWER_FACTOR = SLHC_LOWER_FACTOR;
 #endif
 constexpr int LOWER_MIN_ROWS = SLHC_LOWER_MIN_ROWS;
 constexpr int NESTED_K = 8;
+// pruned connection sweeps: a launch with fewer non-empty panels than this splits every panel's scan into parts
+// so that about this many work items result, at most SPLIT_MAX_PARTS per panel
+#ifndef SLHC_SPLIT_ITEMS_TARGET
+#define SLHC_SPLIT_ITEMS_TARGET 32768
+#endif
+constexpr int SPLIT_ITEMS_TARGET = SLHC_SPLIT_ITEMS_TARGET;
+constexpr int SPLIT_MAX_PARTS = 16;
+// ... and only as far as a part still has about this many tiles to multiply, going by the steps per panel of the
+// sweep before
+#ifndef SLHC_SPLIT_MIN_STEPS
+#define SLHC_SPLIT_MIN_STEPS 8.0
+#endif
+constexpr double SPLIT_MIN_STEPS = SLHC_SPLIT_MIN_STEPS;
 // up to this many tiles of the reordered copy the lower bounds between all pairs of tiles are tabulated once
 // (T x T floats: 4 GiB at the limit) instead of being computed for every query panel of every pruned sweep
 #ifndef SLHC_TILE_GAP_MAX_TILES
@@ -200,7 +213,7 @@ size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {
     float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *tile_gap, *n_w, *n_heights;
-    int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *counts, *rank, *shift, *far_count;
+    int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *tile_list, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
     uint32_t *tmp_a, *tmp_b, *tmp_c;
     void* sort_temp; size_t sort_temp_bytes;
@@ -228,7 +241,7 @@ struct OrderWs {
         // lower bounds between all pairs of tiles (order_tile_gaps), as long as the table stays moderate
         tile_gap = Tmax <= TILE_GAP_MAX_TILES ? c.take<float>((size_t)Tmax * Tmax) : nullptr;
         pid = c.take<int32_t>(n); perm = c.take<int32_t>(nm); inv = c.take<int32_t>(n); colour_s = c.take<int32_t>(nm);
-        qslot = c.take<int32_t>(nm); tile_colour = c.take<int32_t>((size_t)Tmax);
+        qslot = c.take<int32_t>(nm); tile_colour = c.take<int32_t>((size_t)Tmax); tile_list = c.take<int32_t>((size_t)Tmax);
         counts = c.take<int32_t>(pm); rank = c.take<int32_t>(pm); shift = c.take<int32_t>(pm); far_count = c.take<int32_t>(64);
         tmp_a = c.take<uint32_t>(n); tmp_b = c.take<uint32_t>(n); tmp_c = c.take<uint32_t>(n);
         sort_temp_bytes = slhc::pair_sort_temp_bytes((int)N);
@@ -1148,6 +1161,10 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     bool connect_pruned = (unsigned long long)st.knn_tile_steps * 4 <= tiles_1d * tiles_1d;
     unsigned long long conn_steps_seen = 0;
     double prev_steps_per_panel = 0.0;     // tile steps per query panel in the last pruned round
+    // tile steps per panel that holds a queried row, as far as known: the k-NN sweep's at first, then the last
+    // pruned round's; decides into how many parts a panel's scan is worth splitting
+    double steps_per_used_panel = pruned ? (double)st.knn_tile_steps / (double)((kws.order.Ns + 127) / 128) : 0.0;
+    long long used_panels_round = 0;
     st.components_after_knn = 1;
     // One read-back per round: the scan of the lists for round r+1 is enqueued right behind the relabelling
     // of round r, so the counters that come back carry the edges committed so far, whether the hook
@@ -1224,6 +1241,24 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     const OrderWs& o = kws.order;
                     HIP_TRY(slhc::order_fill_i32(o.qslot, o.Ns, -1, s));
                     HIP_TRY(slhc::order_scatter_slots(o.inv, rows, n, (int)N, o.Ns, o.qslot, s));
+                    // A launch with few panels is as long as its longest panel, and a panel whose queries admit
+                    // thousands of tiles outlasts the others several times over: with fewer non-empty panels
+                    // than SPLIT_ITEMS_TARGET, every panel's scan is split into parts (see the kernel).
+                    int32_t* used = ws.counters + 12;
+                    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(used), 1);
+                    HIP_TRY(hipGetLastError());
+                    HIP_TRY(slhc::order_count_used_tiles(o.qslot, o.Ns, used, o.tile_list, s));
+                    HIP_TRY(hipMemcpyAsync(h_cnt + 6, used, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+                    HIP_TRY(hipStreamSynchronize(s));
+                    const int used_panels = h_cnt[6] > 0 ? h_cnt[6] : 1;
+                    used_panels_round += used_panels;
+                    int parts = SPLIT_ITEMS_TARGET / used_panels;
+                    const int worth = (int)(steps_per_used_panel / SPLIT_MIN_STEPS);      // a part should have some tiles to multiply
+                    if (parts > worth) parts = worth;
+                    p.segments = parts < 2 ? 1 : (parts > SPLIT_MAX_PARTS ? SPLIT_MAX_PARTS : parts);
+                    if (flags & SLHC_SPLIT_SCANS) p.segments = 5;
+                    if (h_cnt[6] < 0 || h_cnt[6] > (o.Ns + 127) / 128) { set_err("bad count of queried tiles %d", h_cnt[6]); return SLHC_INTERNAL; }
+                    p.panel_list = o.tile_list; p.panel_list_n = h_cnt[6];
                     p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
                     p.qcolour = p.ccolour = o.colour_s;
                     p.qslot = o.qslot;
@@ -1255,13 +1290,14 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.rows = rows;
                 }
 #ifdef SLHC_STUDY_PANEL_STEPS
-                int* study_steps = reinterpret_cast<int*>(ws.keys_b);
+                int* study_steps = reinterpret_cast<int*>(kws.order.gap_ws);    // unused while the table of tile pairs serves
                 const int study_panels = (kws.order.Ns + 127) / 128;
                 if (round_pruned) { HIP_TRY(hipMemsetAsync(study_steps, 0, (size_t)study_panels * 8, s)); p.panel_steps = study_steps; }
 #endif
                 HIP_TRY(hipEventRecord(ev_conn.a, s));
-                // keys_a is free until the edge sort (the two-phase split above uses it in pruned rounds only)
-                HIP_TRY(slhc::launch_segmented_cross_1nn(p, round_pruned ? nullptr : ws.keys_a, s));
+                // keys_a / keys_b are free until the edge sort (the two-phase split above keeps its row lists in keys_a,
+                // in pruned rounds only)
+                HIP_TRY(slhc::launch_segmented_cross_1nn(p, round_pruned ? ws.keys_b : ws.keys_a, s));
                 HIP_TRY(hipEventRecord(ev_conn.b, s));
                 HIP_TRY(slhc::forest_apply_queries(f, rows, ws.q_idx, ws.q_dist, n, round_pruned ? ws.vals_a : nullptr, s));
                 HIP_TRY(hipStreamSynchronize(s));
@@ -1274,7 +1310,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     std::sort(order_.begin(), order_.end(), [&](int a, int b) { return hs[(size_t)study_panels + a] > hs[(size_t)study_panels + b]; });
                     long long tot_steps = 0, tot_cyc = 0; int used = 0;
                     for (int i = 0; i < study_panels; ++i) { tot_steps += hs[(size_t)i]; tot_cyc += hs[(size_t)study_panels + i]; used += hs[(size_t)study_panels + i] > 0; }
-                    std::fprintf(stderr, "[study] %d rows, %d panels used, steps %lld, kcycles %lld (per WG slot %.0f), kernel %.2f ms\n", n, used, tot_steps, tot_cyc, tot_cyc / 512.0, ev_conn.ms());
+                    std::fprintf(stderr, "[study] %d rows, %d panels used, parts %d, steps %lld, kcycles %lld (per WG slot %.0f), kernel %.2f ms\n", n, used, p.segments, tot_steps, tot_cyc, tot_cyc / 512.0, ev_conn.ms());
                     for (int r = 0; r < 12; ++r) { const int i = order_[(size_t)r]; std::fprintf(stderr, "[study]   panel %d: steps %d kcycles %d\n", i, hs[(size_t)i], hs[(size_t)study_panels + i]); }
                 }
 #endif
@@ -1330,6 +1366,8 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 const unsigned long long steps = h_surv[3] - conn_steps_seen;
                 conn_steps_seen = h_surv[3];
                 prev_steps_per_panel = (double)steps / (double)((queried + 127) / 128 > 0 ? (queried + 127) / 128 : 1);
+                if (used_panels_round > 0) steps_per_used_panel = (double)steps / (double)used_panels_round;
+                used_panels_round = 0;
                 const unsigned long long every = (unsigned long long)((nq + 127) / 128) * (unsigned long long)((N + 127) / 128);
                 if ((int64_t)nq * 8 >= N && steps * 3 > every) connect_pruned = false;
             }

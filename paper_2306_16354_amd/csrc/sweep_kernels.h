@@ -68,6 +68,10 @@ struct SweepParams {
     unsigned int* panel_counter;  // optional device word, zero at launch: panels are taken from it one at
                                   // a time instead of round-robin (use when panel costs differ widely)
     int own_tile_first;    // self-join in the same row order: start each panel at its own tile
+    // cross 1-NN with a slot map, optional: the panels that hold a queried row (any order); the others are then
+    // not visited at all
+    const int32_t* panel_list;
+    int panel_list_n;
     // k = 1 between two matrices with few query rows: the candidate tiles are split into `segments`
     // parts, one work item per (panel, part); every item merges its result into out_key[q] with a
     // 64-bit atomic minimum over (dist bits << 32 | idx), which is the (dist, idx) order.  Set by

@@ -926,16 +926,29 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 #endif
 
     int* next_panel = reinterpret_cast<int*>(L.wmax + 8);      // LDS word after the wmax slots
-    for (int panel = blockIdx.x;; panel += gridDim.x) {
+    // Pruned cross 1-NN sweeps with a slot map may split every panel's scan into p.segments work items (item =
+    // panel * segments + part): part s takes every segments-th position of the panel's scan order, starting at
+    // position s, so each part begins among the near tiles; the parts keep separate thresholds and meet in
+    // p.out_key by a 64-bit atomic minimum, which is the (distance, index) order of the lists.  A few panels
+    // whose queries admit thousands of tiles otherwise outlast the rest of a launch several times over.
+    constexpr bool CAN_SPLIT = PRUNE && MASKED && KL == 1;
+    const int nparts = (CAN_SPLIT && aligned && p.segments > 1 && p.out_key != nullptr) ? p.segments : 1;
+    const bool listed_panels = PRUNE && MASKED && aligned && p.panel_list != nullptr;
+    const int nitems = (listed_panels ? p.panel_list_n : npanels) * nparts;
+    for (int item = blockIdx.x;; item += gridDim.x) {
         __syncthreads();          // previous panel fully written out before its state is reused
         if (PRUNE && p.panel_counter) {
-            // panels are handed out one by one: with pruning their cost differs by orders of
-            // magnitude.  The counter only grows, so every workgroup reaches npanels and leaves.
+            // work items are handed out one by one: with pruning their cost differs by orders of
+            // magnitude.  The counter only grows, so every workgroup reaches nitems and leaves.
             if (tid == 0) *next_panel = (int)atomicAdd(p.panel_counter, 1u);
             __syncthreads();
-            panel = *next_panel;
+            item = *next_panel;
         }
-        if (panel >= npanels) break;
+        if (item >= nitems) break;
+        const int panel_at = nparts > 1 ? item / nparts : item;
+        const int part = nparts > 1 ? item - panel_at * nparts : 0;
+        const int panel = listed_panels ? p.panel_list[panel_at] : panel_at;
+        if ((unsigned int)panel >= (unsigned int)npanels) continue;          // never trust a list entry as an index
 #ifdef SLHC_STUDY_PANEL_STEPS
         const long long study_t0 = clock64();
 #endif
@@ -951,6 +964,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             bounds[tid] = row >= 0 ? -__builtin_inff() : __builtin_inff();
         }
         for (int i = tid; i < BM * KL; i += WG_THREADS) lists[i] = LIST_SENTINEL;
+        if (CAN_SPLIT && nparts > 1 && tid < BM && qid[tid] >= 0) {
+            // what the other parts of this panel have found for this query so far: an exact candidate like any
+            // other (the list of a 1-NN sweep is the one entry lists[tid])
+            const unsigned long long found = __hip_atomic_load(p.out_key + p.qslot[qid[tid]], __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+            if (found != LIST_SENTINEL) {
+                lists[tid] = found;
+                bounds[tid] = hqs[tid] - 0.5f * __uint_as_float((unsigned int)(found >> 32));
+            }
+        }
         if (tid < 8) { if (PRUNE) L.wmax[tid] = __builtin_inff(); else reinterpret_cast<int*>(L.wmax)[tid] = 0; }
         if (tid < 4) *deferred_count(L, tid) = 0;
         __syncthreads();
@@ -1115,11 +1138,14 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         else if (prune && MASKED && qid[0] >= 0) centre = qid[0] / BN;
         if (centre >= ntiles) centre = ntiles - 1;
         const int with_centre = own_tile >= 0 ? 0 : 1;        // the scan itself begins at the centre tile
-        const int nscan = own_tile >= 0 ? ntiles - 1 : ntiles;
+        const int nscan_all = own_tile >= 0 ? ntiles - 1 : ntiles;
+        // positions of this work item: part, part + nparts, ... of the panel's scan order
+        const int nscan = nparts > 1 ? (nscan_all > part ? (nscan_all - part + nparts - 1) / nparts : 0) : nscan_all;
         const int side_r = ntiles - 1 - centre, side_l = centre;
         const int side_min = side_r < side_l ? side_r : side_l;
         auto scan_tile = [&](int i) -> int {                   // 0 <= i < nscan
             if (!prune) return i;
+            if (nparts > 1) i = i * nparts + part;
             if (with_centre) { if (i == 0) return centre; --i; }
             if (i < 2 * side_min) { const int j = (i >> 1) + 1; return (i & 1) ? centre - j : centre + j; }
             const int r = i - 2 * side_min;
@@ -1206,6 +1232,13 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 8));
             wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
         };
+        // split scans: this query's slot in p.out_key, the entry last published there, the word last read
+        int part_slot = 0;
+        unsigned long long part_published = LIST_SENTINEL, part_seen = LIST_SENTINEL;
+        if (CAN_SPLIT && nparts > 1) {
+            if (my_qrow >= 0) { part_slot = p.qslot[my_qrow]; part_published = mylists[l32]; }
+            if (prune) refresh_wave_thr();       // the thresholds adopted at set-up
+        }
         int step = 0;                      // multiplied tiles of this panel (buffer parity)
         while (tile < ntiles) {
             const int col0 = tile * BN;
@@ -1492,6 +1525,28 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 if (lane == 0) reinterpret_cast<int*>(L.wmax)[tpar * 4 + wave] = waiting_;
             }
             if (shared_thr && flagged == 0) bound = own_bound;
+            if (CAN_SPLIT && nparts > 1) {
+                // Exchange with the other parts of the panel through p.out_key: publish this query's entry when
+                // it has improved, adopt the word read a step ago when it is better (its read has had a whole
+                // step to arrive), and read it again for the next step.
+                bool adopted = false;
+                if (lhalf == 0 && my_qrow >= 0) {
+                    const unsigned long long mine = mylists[l32];
+                    if (mine < part_published) { atomicMin(p.out_key + part_slot, mine); part_published = mine; }
+                    if (part_seen < mine) {
+                        mylists[l32] = part_seen;
+                        bounds[my_q_local] = hqs[my_q_local] - 0.5f * __uint_as_float((unsigned int)(part_seen >> 32));
+                        part_published = part_seen;
+                        adopted = true;
+                    }
+                    part_seen = __hip_atomic_load(p.out_key + part_slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (__any(adopted)) {
+                    __builtin_amdgcn_wave_barrier();
+                    bound = bounds[my_q_local];
+                    if (prune) refresh_wave_thr();
+                }
+            }
             PHASE_MARK(6);
             // (with a falling component threshold: no query of this wavefront can use a candidate beyond it)
             if (prune && lane == 0) L.wmax[tpar * 4 + wave] = lowering ? fminf(wave_thr_max, thr_c) : wave_thr_max;
@@ -1501,7 +1556,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
 
 #ifdef SLHC_STUDY_PANEL_STEPS
-        if (p.panel_steps && tid == 0) { p.panel_steps[panel] = step; p.panel_steps[npanels + panel] = (int)((clock64() - study_t0) >> 10); }
+        if (p.panel_steps && tid == 0) { atomicAdd(p.panel_steps + panel, step); atomicMax(p.panel_steps + npanels + panel, (int)((clock64() - study_t0) >> 10)); }
 #endif
         // ---- panel epilogue: lists are already ascending; write them out ----
         if (!PRUNE) {
@@ -1519,8 +1574,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 if (key == LIST_SENTINEL) idx = -1;
                 const size_t o = MASKED ? (size_t)(aligned ? p.qslot[row] : panel * BM + wave * 32 + ql)
                                         : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + lane;
-                p.out_idx[o] = idx;
-                p.out_dist[o] = dist;
+                if (CAN_SPLIT && nparts > 1) {
+                    if (key != LIST_SENTINEL) atomicMin(p.out_key + o, key);      // the parts of a panel meet here
+                } else {
+                    p.out_idx[o] = idx;
+                    p.out_dist[o] = dist;
+                }
             }
         }
         PHASE_MARK(7);
@@ -1754,12 +1813,15 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     if (npanels < 1) return hipSuccess;
     const size_t lds = sweep_lds_bytes(KL);
     const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
-    if (p.segments > 1 && (!p.out_key || p.k != 1 || p.tile_c)) return hipErrorInvalidValue;
-    const long long nitems = (long long)npanels * (p.segments > 1 ? p.segments : 1);
+    // candidate segments: the streaming kernel (no pruning); parts of a pruned scan: cross 1-NN with a slot map
+    if (p.segments > 1 && (!p.out_key || p.k != 1 || (p.tile_c && !(MASKED && p.qslot)))) return hipErrorInvalidValue;
+    const bool listed = MASKED && aligned && p.tile_c && p.panel_list;
+    if (listed && p.panel_list_n < 1) return hipSuccess;
+    const long long nitems = (long long)(listed ? p.panel_list_n : npanels) * (p.segments > 1 ? p.segments : 1);
     int grid = cus * per_cu;
     if (grid > nitems) grid = (int)nitems;
     const bool vec4 = (p.d % 4 == 0) && (((reinterpret_cast<uintptr_t>(p.Xq) | reinterpret_cast<uintptr_t>(p.Xc)) & 15) == 0);
-    if (vec4 && p.d <= 4 * KC && p.segments <= 1) {
+    if (vec4 && p.d <= 4 * KC && (p.segments <= 1 || p.tile_c)) {
         // up to 128 features: query fragments live in registers
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
@@ -1868,7 +1930,12 @@ hipError_t launch_segmented_cross_1nn(const SweepParams& p_in, unsigned long lon
     const int m = p.m;
     if (m < 1) return hipSuccess;
     p.k = 1;
-    p.segments = (p.tile_c || p.qslot || !keys) ? 1 : sweep_segments_for(m, p.NC, p.d % 4 == 0 && p.d <= 4 * KC);
+    if (p.tile_c && p.qslot) {
+        // pruned sweep with a slot map: the caller chooses into how many parts every panel's scan is split
+        if (!keys || p.segments < 2) p.segments = 1;
+    } else {
+        p.segments = (p.tile_c || p.qslot || !keys) ? 1 : sweep_segments_for(m, p.NC, p.d % 4 == 0 && p.d <= 4 * KC);
+    }
     if (p.segments <= 1) {
         p.segments = 0;
         p.out_key = nullptr;

@@ -971,6 +971,46 @@ def test_split_connection_rounds_are_identical(lib):
     assert split_seen >= 3
 
 
+# ----------------------------------------------------------------------------- split panel scans
+def test_split_panel_scans_are_identical(lib):
+    """SLHC_SPLIT_SCANS splits every query panel's scan of the candidate tiles in the pruned connection
+    sweeps into 5 work items that meet in a 64-bit atomic minimum and adopt each other's finds: the tree
+    must equal the every-tile path's bit for bit on seeded random shapes (blobs, duplicates, 1 to 32
+    neighbours, 4 to 128 features), together with the two-phase rounds too, and the oracle's on the small
+    ones.  The split must really have run: its work items multiply a different number of tiles."""
+    rng = np.random.default_rng(31337)
+    changed = 0
+    for case in range(20):
+        N = int(rng.integers(600, 30_000)) if case % 3 else int(rng.integers(600, 3000))
+        d = int(rng.choice([4, 8, 16, 32, 64, 100, 128]))
+        k = int(rng.integers(1, 33))
+        nb = int(rng.integers(2, 150))
+        spread = float(rng.choice([3.0, 20.0, 1000.0]))
+        sigma = float(rng.choice([0.05, 1.0, 3.0]))
+        centres = rng.uniform(-spread, spread, size=(nb, d))
+        X = (centres[rng.integers(0, nb, size=N)] + sigma * rng.standard_normal((N, d))).astype(np.float32)
+        ties = False
+        if rng.random() < 0.3:
+            m = N // 10
+            X[rng.integers(0, N, size=m)] = X[rng.integers(0, N, size=m)]
+            ties = True
+        print(f"split scans case {case}: N={N} d={d} k={k} blobs={nb} spread={spread} sigma={sigma} ties={ties}", flush=True)
+        Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+        a = lib.slhc(Xd, k, prune=False)
+        b = lib.slhc(Xd, k, prune=True, split_scans=True)
+        c = lib.slhc(Xd, k, prune=True, split_scans=True, split_rounds=True)
+        plain = lib.slhc(Xd, k, prune=True)
+        for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+            assert torch.equal(a[name_], b[name_]), name_
+            assert torch.equal(a[name_], c[name_]), name_
+        if b["stats"]["pruned"] and b["stats"]["connect_tile_steps"] != plain["stats"]["connect_tile_steps"]:
+            changed += 1
+        if N <= 3000:
+            check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
+    print("cases in which the split scans multiplied a different number of tiles:", changed, flush=True)
+    assert changed >= 5
+
+
 # ----------------------------------------------------------------------------- non-finite input, bad rows
 @pytest.mark.parametrize("bad", [float("nan"), float("inf"), -float("inf"), 3e20])
 def test_nonfinite_rows(lib, bad):
