@@ -535,6 +535,10 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         p.tile_gap = o.tile_gap;
         p.own_tile_first = 1;
         p.panel_counter = reinterpret_cast<unsigned int*>(ws.counters + 8);     // zeroed above
+#ifdef SLHC_STUDY_PANEL_STEPS
+        p.panel_steps = reinterpret_cast<int*>(o.qslot);       // free until the connection rounds
+        HIP_TRY(hipMemsetAsync(o.qslot, 0, (size_t)((o.Ns + 127) / 128) * 8, stream));
+#endif
 #ifdef SLHC_PHASE_TIMERS
         p.phase_cycles = ws.counters + 16;
 #endif
@@ -1128,6 +1132,17 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     if ((h_surv[4] & 0xffffffffull) != 0) { set_err("a row of X is not finite (NaN, infinity, or a squared norm beyond float32)"); return SLHC_NONFINITE; }
     st.knn_filter_survivors = (int64_t)h_surv[0];
     st.knn_tile_steps = (int64_t)h_surv[2];
+#ifdef SLHC_STUDY_PANEL_STEPS
+    if (pruned) {
+        const int T_ = (kws.order.Ns + 127) / 128;
+        std::vector<int> hs((size_t)T_ * 2);
+        HIP_TRY(hipMemcpy(hs.data(), kws.order.qslot, hs.size() * 4, hipMemcpyDeviceToHost));
+        long long tot = 0; int longest = 0, most = 0;
+        for (int i = 0; i < T_; ++i) { tot += hs[(size_t)T_ + i]; if (hs[(size_t)T_ + i] > longest) longest = hs[(size_t)T_ + i]; if (hs[(size_t)i] > most) most = hs[(size_t)i]; }
+        std::fprintf(stderr, "[study] k-NN sweep: %d panels, kcycles %lld (per WG slot %.0f), longest panel %d kcycles, most steps %d, kernel %.2f ms\n",
+                     T_, tot, tot / 512.0, longest, most, ev_knn.ms());
+    }
+#endif
     st.ms_norm_kernel = ev_norm.ms();
     st.ms_order = ev_order.ms();
     st.ms_knn_kernel = ev_knn.ms();
