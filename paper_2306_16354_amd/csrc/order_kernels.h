@@ -1,6 +1,6 @@
 // Spatially coherent row order and bounding balls of candidate tiles (order_kernels.hip).
 // Used to skip (query panel, candidate tile) pairs that provably cannot contribute; the paper's
-// kernels multiply every tile (Sec. 3.1.1 "we still perform N^2 distance computations").
+// kernels multiply every tile (Sec. 3.1.1: all N^2 distances are computed).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
