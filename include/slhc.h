@@ -108,6 +108,10 @@ typedef struct slhc_stats {
                            tiles into 5 work items that exchange what they find, which the library
                            otherwise does (in 2 to 16 parts) only for launches with few panels and
                            long scans.  Same outputs.                                           */
+#define SLHC_NO_TILE_TABLE 8u  /* with SLHC_PRUNE only; a testing aid.  The pruned sweeps compute the lower
+                           bounds of every query panel against the candidate tiles themselves, as
+                           they do for row orders of more than 32768 tiles, instead of reading them
+                           from the table of all tile pairs.  Same outputs.                     */
 
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */

@@ -34,6 +34,7 @@ class _Stats(ctypes.Structure):
 SLHC_PRUNE = 1
 SLHC_SPLIT_ROUNDS = 2
 SLHC_SPLIT_SCANS = 4
+SLHC_NO_TILE_TABLE = 8
 SLHC_STATIC_MAX_ROWS = 1048576
 
 
@@ -126,7 +127,7 @@ def slhc_workspace_bytes(N, d, k):
     return out.value
 
 
-def knn_graph(X, k, out=None, workspace=None, prune=False):
+def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True):
     """slhc_knn_graph (prune=False) / slhc_knn_graph_opt with SLHC_PRUNE: returns (idx int32 [N,k],
     dist float32 [N,k]) device tensors.  Asynchronous on the current stream."""
     X = _device_matrix(X)
@@ -141,7 +142,7 @@ def knn_graph(X, k, out=None, workspace=None, prune=False):
         idx, dist = out
     _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream(),
-                                  SLHC_PRUNE if prune else 0))
+                                  (SLHC_PRUNE if prune else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
     return idx, dist
 
 
@@ -196,12 +197,12 @@ def cross_1nn(X, colour, rows=None, m=None):
     return idx, dist
 
 
-def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False):
+def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False, tile_table=True):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
     prune=True is slhc_slhc; prune=False multiplies every tile (slhc_slhc_opt with flags 0);
-    split_rounds adds SLHC_SPLIT_ROUNDS, split_scans SLHC_SPLIT_SCANS."""
+    split_rounds adds SLHC_SPLIT_ROUNDS, split_scans SLHC_SPLIT_SCANS, tile_table=False SLHC_NO_TILE_TABLE."""
     X = _device_matrix(X)
     N, d = X.shape
     lib = load_library()
@@ -222,7 +223,7 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
                              out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
                              workspace.numel(), _stream(),
                              (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
-                             (SLHC_SPLIT_SCANS if split_scans else 0)))
+                             (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

@@ -532,7 +532,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
         p.q_out_row = o.perm; p.c_id = o.perm;
         p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
-        p.tile_gap = o.tile_gap;
+        p.tile_gap = (flags & SLHC_NO_TILE_TABLE) ? nullptr : o.tile_gap;
         p.own_tile_first = 1;
         p.panel_counter = reinterpret_cast<unsigned int*>(ws.counters + 8);     // zeroed above
 #ifdef SLHC_STUDY_PANEL_STEPS
@@ -1279,7 +1279,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.qslot = o.qslot;
                     p.c_id = o.perm;
                     p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
-                    p.tile_gap = o.tile_gap;
+                    p.tile_gap = (flags & SLHC_NO_TILE_TABLE) ? nullptr : o.tile_gap;
                     p.tile_colour = o.tile_colour;
                     // thresholds shared by the queries of a component: what the forest already knows (a
                     // working copy that the sweep lowers further as its queries find lighter edges;

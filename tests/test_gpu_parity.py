@@ -576,10 +576,18 @@ def test_pruned_random_shapes(lib):
             ties = True
         print(f"random case {case}: N={N} d={d} k={k} blobs={nb} spread={spread} sigma={sigma} ties={ties}", flush=True)
         b = _pruned_equals_every_tile(lib, X, k)
-        b2 = lib.slhc(torch.from_numpy(np.ascontiguousarray(X)).cuda(), k)
+        Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+        b2 = lib.slhc(Xd, k)
         # which rows are queried is a function of the forest state alone; how many tiles their panels skip
         # depends on which panel lowers a component's threshold first, so tile steps may differ
         assert b2["stats"]["connect_query_rows"] == b["stats"]["connect_query_rows"]
+        # the sweeps' own lower bounds (what row orders of more than 32768 tiles get) instead of the table
+        b3 = lib.slhc(Xd, k, tile_table=False, split_scans=bool(case % 2))
+        for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+            assert torch.equal(b[name_], b3[name_]), name_
+        i3, d3 = lib.knn_graph(Xd, k, prune=True, tile_table=False)
+        i0, d0 = lib.knn_graph(Xd, k)
+        assert torch.equal(i0, i3) and torch.equal(d0, d3)
         if N <= 3000:
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
