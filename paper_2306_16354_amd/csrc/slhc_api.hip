@@ -249,7 +249,9 @@ struct OrderWs {
         n_src = c.take<int32_t>(pm); n_dst = c.take<int32_t>(pm); n_w = c.take<float>(pm);
         n_children = c.take<int32_t>(2 * pm); n_heights = c.take<float>(pm); n_sizes = c.take<int32_t>(pm);
         const int32_t kp = Pmax - 1 < NESTED_K ? Pmax - 1 : NESTED_K;
-        nested_bytes = slhc_ws_bytes(Pmax, d, kp, false);
+        // (the clustering runs on the pivots in use, fewer than Pmax: a k-NN sweep of few panels then also wants
+        // its scratch for candidate ranges, which the layout for Pmax rows may not contain)
+        nested_bytes = slhc_ws_bytes(Pmax, d, kp, false) + (size_t)grid * 128 * (size_t)kp * 8 + 1024;
         nested_ws = c.take<unsigned char>(nested_bytes);
     }
 };
@@ -260,12 +262,26 @@ struct KnnWs {
     float* hn;
     bool has_order;
     OrderWs order;
+    // lists per candidate range of a k-NN sweep with few panels (see launch_knn_sweep); k = 0: none
+    int32_t* part_idx; float* part_dist; long long part_rows;
     size_t bytes;
-    KnnWs(void* ws, int64_t N, int32_t d, bool with_order)
+    KnnWs(void* ws, int64_t N, int32_t d, bool with_order, int32_t k = 0)
     {
         Carver c(ws);
         counters = c.take<unsigned long long>(32);
         hn = c.take<float>((size_t)N);
+        part_idx = nullptr; part_dist = nullptr; part_rows = 0;
+        {
+            // ranges x rows never exceeds the workgroup slots x 128: a sweep is only split while its panels
+            // fill less than half the slots
+            int grid = slhc::sweep_grid_limit();
+            if (grid < 1) grid = 512;
+            if (k > 1 && ((N + 127) / 128) * 2 <= grid) {
+                part_rows = (long long)grid * 128;
+                part_idx = c.take<int32_t>((size_t)part_rows * k);
+                part_dist = c.take<float>((size_t)part_rows * k);
+            }
+        }
         has_order = with_order && prunable(N, d);
         if (has_order) order.carve(c, N, d);
         bytes = c.off;
@@ -285,7 +301,7 @@ struct SlhcWs {
     {
         Carver c(ws);
         const size_t n = (size_t)N;
-        knn_ws = c.take<unsigned char>(KnnWs(nullptr, N, d, with_order).bytes);
+        knn_ws = c.take<unsigned char>(KnnWs(nullptr, N, d, with_order, k).bytes);
         nbr_idx = c.take<int32_t>(n * k);
         nbr_dist = c.take<float>(n * k);
         colour = c.take<int32_t>(n); ptr = c.take<int32_t>(n); ext_idx = c.take<int32_t>(n);
@@ -544,6 +560,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
 #endif
     } else {
         p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
+        p.part_idx = ws.part_idx; p.part_dist = ws.part_dist; p.part_rows = ws.part_rows;
 #ifdef SLHC_PHASE_TIMERS
         p.phase_cycles = ws.counters + 16;
 #endif
@@ -718,7 +735,7 @@ int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
         if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        *bytes = KnnWs(nullptr, N, d, true).bytes;
+        *bytes = KnnWs(nullptr, N, d, true, k).bytes;
         return SLHC_OK;
     });
 }
@@ -730,7 +747,7 @@ int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t*
         if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        KnnWs ws(workspace, N, d, true);
+        KnnWs ws(workspace, N, d, true, k);
         if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
         return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
     });
@@ -1121,7 +1138,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     HIP_TRY(ev_knn.create());
     HIP_TRY(ev_conn.create());
     bool pruned = false;
-    KnnWs kws(ws.knn_ws, N, d, with_order);      // half norms and row order are reused by the connection sweeps
+    KnnWs kws(ws.knn_ws, N, d, with_order, k);   // half norms and row order are reused by the connection sweeps
     rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, kws, s, flags, &pruned, &ev_norm, &ev_order, &ev_knn);
     if (rc != SLHC_OK) return rc;
     PinnedHost pin_surv;

@@ -78,6 +78,13 @@ struct SweepParams {
     // launch_segmented_1nn; 0 / nullptr otherwise.
     int segments;
     unsigned long long* out_key;
+    // k-NN with k > 1 and few query panels (launch_knn_sweep decides): the candidate tiles are split into
+    // `segments` ranges, one work item per (panel, range); item (panel, s) writes its lists to
+    // part_idx / part_dist [s][NQ][k], and a merge kernel picks the k smallest of a row's lists.  Scratch of
+    // part_rows * k entries each (rows x segments must fit); nullptr: never split.
+    int32_t* part_idx;
+    float* part_dist;
+    long long part_rows;
     unsigned long long* survivors;   // optional device counter: pairs that passed the filter
     unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
 #ifdef SLHC_PHASE_TIMERS

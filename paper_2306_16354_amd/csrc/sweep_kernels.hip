@@ -932,7 +932,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     // p.out_key by a 64-bit atomic minimum, which is the (distance, index) order of the lists.  A few panels
     // whose queries admit thousands of tiles otherwise outlast the rest of a launch several times over.
     constexpr bool CAN_SPLIT = PRUNE && MASKED && KL == 1;
-    const int nparts = (CAN_SPLIT && aligned && p.segments > 1 && p.out_key != nullptr) ? p.segments : 1;
+    // k-NN sweeps of few panels (k > 1, every tile): part s of a panel takes the s-th range of the candidate
+    // tiles and writes lists of its own; see SweepParams::part_idx.
+    constexpr bool CAN_RANGE = !PRUNE && !MASKED && KL > 1;
+    const int nparts = (CAN_SPLIT && aligned && p.segments > 1 && p.out_key != nullptr) ? p.segments
+                     : (CAN_RANGE && p.segments > 1 && p.part_idx != nullptr && p.part_dist != nullptr) ? p.segments : 1;
     const bool listed_panels = PRUNE && MASKED && aligned && p.panel_list != nullptr;
     const int nitems = (listed_panels ? p.panel_list_n : npanels) * nparts;
     for (int item = blockIdx.x;; item += gridDim.x) {
@@ -1140,11 +1144,14 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         const int with_centre = own_tile >= 0 ? 0 : 1;        // the scan itself begins at the centre tile
         const int nscan_all = own_tile >= 0 ? ntiles - 1 : ntiles;
         // positions of this work item: part, part + nparts, ... of the panel's scan order
-        const int nscan = nparts > 1 ? (nscan_all > part ? (nscan_all - part + nparts - 1) / nparts : 0) : nscan_all;
+        const int range_begin = (CAN_RANGE && nparts > 1) ? (int)((long long)part * ntiles / nparts) : 0;
+        const int range_end = (CAN_RANGE && nparts > 1) ? (int)((long long)(part + 1) * ntiles / nparts) : ntiles;
+        const int nscan = (CAN_RANGE && nparts > 1) ? range_end - range_begin
+                        : nparts > 1 ? (nscan_all > part ? (nscan_all - part + nparts - 1) / nparts : 0) : nscan_all;
         const int side_r = ntiles - 1 - centre, side_l = centre;
         const int side_min = side_r < side_l ? side_r : side_l;
         auto scan_tile = [&](int i) -> int {                   // 0 <= i < nscan
-            if (!prune) return i;
+            if (!prune) return i + range_begin;
             if (nparts > 1) i = i * nparts + part;
             if (with_centre) { if (i == 0) return centre; --i; }
             if (i < 2 * side_min) { const int j = (i >> 1) + 1; return (i & 1) ? centre - j : centre + j; }
@@ -1576,6 +1583,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                                         : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + lane;
                 if (CAN_SPLIT && nparts > 1) {
                     if (key != LIST_SENTINEL) atomicMin(p.out_key + o, key);      // the parts of a panel meet here
+                } else if (CAN_RANGE && nparts > 1) {
+                    const size_t po = ((size_t)part * (size_t)p.NQ + (size_t)row) * k + lane;
+                    p.part_idx[po] = idx;
+                    p.part_dist[po] = dist;
                 } else {
                     p.out_idx[o] = idx;
                     p.out_dist[o] = dist;
@@ -1814,14 +1825,15 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
     const size_t lds = sweep_lds_bytes(KL);
     const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
     // candidate segments: the streaming kernel (no pruning); parts of a pruned scan: cross 1-NN with a slot map
-    if (p.segments > 1 && (!p.out_key || p.k != 1 || (p.tile_c && !(MASKED && p.qslot)))) return hipErrorInvalidValue;
+    const bool ranges = !MASKED && p.k > 1 && p.segments > 1 && p.part_idx && p.part_dist && !p.tile_c;     // k-NN in candidate ranges
+    if (p.segments > 1 && !ranges && (!p.out_key || p.k != 1 || (p.tile_c && !(MASKED && p.qslot)))) return hipErrorInvalidValue;
     const bool listed = MASKED && aligned && p.tile_c && p.panel_list;
     if (listed && p.panel_list_n < 1) return hipSuccess;
     const long long nitems = (long long)(listed ? p.panel_list_n : npanels) * (p.segments > 1 ? p.segments : 1);
     int grid = cus * per_cu;
     if (grid > nitems) grid = (int)nitems;
     const bool vec4 = (p.d % 4 == 0) && (((reinterpret_cast<uintptr_t>(p.Xq) | reinterpret_cast<uintptr_t>(p.Xc)) & 15) == 0);
-    if (vec4 && p.d <= 4 * KC && (p.segments <= 1 || p.tile_c)) {
+    if (vec4 && p.d <= 4 * KC && (p.segments <= 1 || p.tile_c || ranges)) {
         // up to 128 features: query fragments live in registers
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
@@ -1838,7 +1850,7 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
         return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, false>, grid, lds, p, stream);
     }
     // tile pruning and the slot map exist in the register-resident-query variant only
-    if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter) return hipErrorInvalidValue;
+    if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter || ranges) return hipErrorInvalidValue;
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
     return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
 }
@@ -1958,13 +1970,67 @@ int sweep_grid_limit()
     return 2 * cus;
 }
 
-hipError_t launch_knn_sweep(const SweepParams& p, hipStream_t stream)
+// The k smallest entries, by (distance, index), of a row's `segments` ascending lists of k: one thread per row.
+// Unused entries of a list are (-1, +inf) and sort last.
+__global__ void __launch_bounds__(256) merge_ranges_kernel(const int32_t* __restrict__ part_idx,
+                                                           const float* __restrict__ part_dist, int segments, int NQ,
+                                                           int k, int32_t* __restrict__ out_idx, float* __restrict__ out_dist)
 {
-    if (p.k == 1) return launch_sweep_t<1, false>(p, stream);
-    if (p.k <= 8) return launch_sweep_t<8, false>(p, stream);
-    if (p.k <= 16) return launch_sweep_t<16, false>(p, stream);
-    if (p.k <= 32) return launch_sweep_t<32, false>(p, stream);
-    return launch_sweep_t<64, false>(p, stream);
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    if (row >= NQ) return;
+    int at[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) at[s] = 0;
+    for (int j = 0; j < k; ++j) {
+        unsigned long long best = ~0ull;
+        int from = 0;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            if (s < segments && at[s] < k) {
+                const size_t o = ((size_t)s * (size_t)NQ + (size_t)row) * k + at[s];
+                const unsigned long long key = ((unsigned long long)__float_as_uint(part_dist[o]) << 32) |
+                                               (unsigned long long)(unsigned int)part_idx[o];
+                if (key < best) { best = key; from = s; }
+            }
+        }
+        ++at[from];
+        out_idx[(size_t)row * k + j] = (int)(unsigned int)(best & 0xffffffffull);
+        out_dist[(size_t)row * k + j] = __uint_as_float((unsigned int)(best >> 32));
+    }
+}
+
+#ifndef SLHC_RANGE_MIN_TILES
+#define SLHC_RANGE_MIN_TILES 2
+#endif
+constexpr int RANGE_MIN_TILES = SLHC_RANGE_MIN_TILES;      // candidate tiles a range of a split k-NN sweep holds at least
+
+hipError_t launch_knn_sweep(const SweepParams& p_in, hipStream_t stream)
+{
+    SweepParams p = p_in;
+    // Few panels (less than half the workgroup slots), k > 1, every tile, query fragments in registers: split the
+    // candidate tiles into ranges so that the whole chip works, at least 8 tiles per range, at most 16 ranges.
+    if (p.k > 1) p.segments = 0;          // (k = 1: launch_segmented_1nn has set the segments of its own scheme)
+    if (p.k > 1 && p.part_idx && p.part_dist && !p.tile_c && !p.q_out_row && p.d % 4 == 0 && p.d <= 4 * KC &&
+        (((reinterpret_cast<uintptr_t>(p.Xq) | reinterpret_cast<uintptr_t>(p.Xc)) & 15) == 0)) {
+        int cus = 0;
+        hipError_t e = device_cus(&cus);
+        if (e != hipSuccess) return e;
+        const int slots = 2 * cus, npanels = (p.NQ + BM - 1) / BM, ntiles = (p.NC + BN - 1) / BN;
+        int s = npanels > 0 ? slots / npanels : 1;
+        if (s > ntiles / RANGE_MIN_TILES) s = ntiles / RANGE_MIN_TILES;
+        if (s > 16) s = 16;
+        if (s >= 2 && (long long)s * p.NQ <= p.part_rows) p.segments = s;
+    }
+    hipError_t e;
+    if (p.k == 1) e = launch_sweep_t<1, false>(p, stream);
+    else if (p.k <= 8) e = launch_sweep_t<8, false>(p, stream);
+    else if (p.k <= 16) e = launch_sweep_t<16, false>(p, stream);
+    else if (p.k <= 32) e = launch_sweep_t<32, false>(p, stream);
+    else e = launch_sweep_t<64, false>(p, stream);
+    if (e != hipSuccess || p.k == 1 || p.segments < 2) return e;
+    hipLaunchKernelGGL(merge_ranges_kernel, dim3((p.NQ + 255) / 256), dim3(256), 0, stream, p.part_idx, p.part_dist,
+                       p.segments, p.NQ, p.k, p.out_idx, p.out_dist);
+    return hipGetLastError();
 }
 
 hipError_t launch_cross_1nn_sweep(const SweepParams& p, hipStream_t stream)

@@ -592,6 +592,28 @@ def test_pruned_random_shapes(lib):
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
 
+# ----------------------------------------------------------------------------- k-NN sweeps split into candidate ranges
+@pytest.mark.parametrize("N,d,k", [(4096, 16, 16), (777, 8, 5), (2000, 128, 64), (16384, 64, 32), (9000, 100, 33),
+                                    (32768, 4, 2), (300, 4, 3)])
+def test_knn_candidate_ranges_equal_unsplit(lib, N, d, k):
+    """With fewer query panels than half the workgroup slots the every-tile k-NN sweep (k > 1) splits the
+    candidate tiles into up to 16 ranges, one work item per (panel, range), and a merge kernel picks the k
+    smallest of a row's lists (the paper's multi-block row epilogue, App. A, without its mutex).  The lists
+    must equal, bit for bit, those of the entry point that never splits (it has no room for partial lists),
+    and sampled rows must equal the oracle's."""
+    rng = np.random.default_rng(N + d + k)
+    X = rng.standard_normal((N, d)).astype(np.float32)
+    X[rng.integers(0, N, size=N // 20)] = X[rng.integers(0, N, size=N // 20)]        # duplicates: ties by index
+    Xd = torch.from_numpy(X).cuda()
+    idx, dist = lib.knn_graph(Xd, k)
+    ref = (torch.empty((N, k), dtype=torch.int32, device="cuda"), torch.empty((N, k), dtype=torch.float32, device="cuda"))
+    lib.knn_graph_static(Xd, k, ref)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, ref[0]) and torch.equal(dist, ref[1])
+    rows = rng.choice(N, size=min(N, 200), replace=False)
+    check_knn(X, k, idx.cpu().numpy()[rows], dist.cpu().numpy()[rows], rows=rows, min_exact=0.9)
+
+
 # ----------------------------------------------------------------------------- 1-NN between two matrices
 # The oracle has no two-matrix search of its own; its cross-colour 1-NN on the stacked matrix
 # [Q; Y] with colour 0 for the query rows and 1 for the index rows is the same definition.
