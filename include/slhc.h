@@ -258,8 +258,11 @@ int slhc_slhc(const float* X, int64_t N, int32_t d, int32_t k,
               int32_t* mst_src, int32_t* mst_dst, float* mst_w,
               int32_t* children, float* heights, int32_t* sizes,
               slhc_stats* stats, void* workspace, size_t workspace_bytes, void* stream);
-/* slhc_slhc is slhc_slhc_opt with flags = SLHC_PRUNE; flags = 0 multiplies every tile in the k-NN
- * and connection sweeps (the paper's brute-force method).  Same outputs either way. */
+/* slhc_slhc is slhc_slhc_opt with flags = SLHC_PRUNE from SLHC_AUTO_PRUNE_MIN_ROWS rows on and with flags = 0
+ * below (building the row order costs more than it saves there; slhc_stats.pruned tells which ran);
+ * flags = 0 multiplies every tile in the k-NN and connection sweeps (the paper's brute-force method).
+ * Same outputs either way. */
+#define SLHC_AUTO_PRUNE_MIN_ROWS 24576
 int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k,
                   int32_t* mst_src, int32_t* mst_dst, float* mst_w,
                   int32_t* children, float* heights, int32_t* sizes,

@@ -201,7 +201,8 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
-    prune=True is slhc_slhc; prune=False multiplies every tile (slhc_slhc_opt with flags 0);
+    prune=True asks for tile pruning (slhc_slhc_opt with SLHC_PRUNE), prune=False multiplies every tile
+    (flags 0), prune=None is slhc_slhc, which prunes from 24 576 rows on;
     split_rounds adds SLHC_SPLIT_ROUNDS, split_scans SLHC_SPLIT_SCANS, tile_table=False SLHC_NO_TILE_TABLE."""
     X = _device_matrix(X)
     N, d = X.shape
@@ -218,12 +219,18 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
         sizes=torch.empty(N - 1, dtype=torch.int32, device=dev),
     )
     st = _Stats()
-    _check(lib.slhc_slhc_opt(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
+    if prune is None:
+        _check(lib.slhc_slhc(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
                              out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
                              out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
-                             workspace.numel(), _stream(),
-                             (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
-                             (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
+                             workspace.numel(), _stream()))
+    else:
+        _check(lib.slhc_slhc_opt(X.data_ptr(), N, d, k, out["mst_src"].data_ptr(), out["mst_dst"].data_ptr(),
+                                 out["mst_w"].data_ptr(), out["children"].data_ptr(), out["heights"].data_ptr(),
+                                 out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
+                                 workspace.numel(), _stream(),
+                                 (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
+                                 (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

@@ -592,6 +592,20 @@ def test_pruned_random_shapes(lib):
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
 
+# ----------------------------------------------------------------------------- default entry point
+def test_default_entry_point_prunes_from_its_limit(lib):
+    """slhc_slhc runs the every-tile path below SLHC_AUTO_PRUNE_MIN_ROWS rows and the pruned one from there
+    on; the trees are those of the explicit flags either way."""
+    for n in (3000, 24575, 24576):
+        X, _, k = gen.make("c2", n=n)
+        Xd = torch.from_numpy(X).cuda()
+        auto = lib.slhc(Xd, k, prune=None)
+        assert bool(auto["stats"]["pruned"]) == (n >= 24576)
+        other = lib.slhc(Xd, k, prune=not auto["stats"]["pruned"])
+        for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+            assert torch.equal(auto[name_], other[name_]), name_
+
+
 # ----------------------------------------------------------------------------- k-NN sweeps split into candidate ranges
 @pytest.mark.parametrize("N,d,k", [(4096, 16, 16), (777, 8, 5), (2000, 128, 64), (16384, 64, 32), (9000, 100, 33),
                                     (32768, 4, 2), (300, 4, 3)])
