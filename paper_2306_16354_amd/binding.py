@@ -35,6 +35,7 @@ SLHC_PRUNE = 1
 SLHC_SPLIT_ROUNDS = 2
 SLHC_SPLIT_SCANS = 4
 SLHC_NO_TILE_TABLE = 8
+SLHC_FP32_FILTER = 16
 SLHC_STATIC_MAX_ROWS = 1048576
 
 
@@ -127,7 +128,7 @@ def slhc_workspace_bytes(N, d, k):
     return out.value
 
 
-def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True):
+def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32_filter=False):
     """slhc_knn_graph (prune=False) / slhc_knn_graph_opt with SLHC_PRUNE: returns (idx int32 [N,k],
     dist float32 [N,k]) device tensors.  Asynchronous on the current stream."""
     X = _device_matrix(X)
@@ -142,7 +143,8 @@ def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True):
         idx, dist = out
     _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream(),
-                                  (SLHC_PRUNE if prune else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
+                                  (SLHC_PRUNE if prune else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
+                                  (SLHC_FP32_FILTER if fp32_filter else 0)))
     return idx, dist
 
 
@@ -197,7 +199,8 @@ def cross_1nn(X, colour, rows=None, m=None):
     return idx, dist
 
 
-def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False, tile_table=True):
+def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False, tile_table=True,
+         fp32_filter=False):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
@@ -230,7 +233,8 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
                                  out["sizes"].data_ptr(), ctypes.byref(st), workspace.data_ptr(),
                                  workspace.numel(), _stream(),
                                  (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
-                                 (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE)))
+                                 (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
+                                 (SLHC_FP32_FILTER if fp32_filter else 0)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

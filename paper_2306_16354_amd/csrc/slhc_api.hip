@@ -199,6 +199,8 @@ constexpr int TILE_GAP_MAX_TILES = SLHC_TILE_GAP_MAX_TILES;
 #define SLHC_DENDROGRAM_THREADS_MIN_ROWS 200000
 #endif
 constexpr int64_t DENDROGRAM_THREADS_MIN_ROWS = SLHC_DENDROGRAM_THREADS_MIN_ROWS;
+// tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
+bool split_products_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <= 128; }
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
 #ifndef SLHC_PIVOT_STRIDE
 #define SLHC_PIVOT_STRIDE 64
@@ -264,6 +266,10 @@ struct KnnWs {
     OrderWs order;
     // lists per candidate range of a k-NN sweep with few panels (see launch_knn_sweep); k = 0: none
     int32_t* part_idx; float* part_dist; long long part_rows;
+    // every-tile sweeps on the bf16 MFMA: X split into bfloat16 halves (see SweepParams::Xq_split) and the half
+    // norms with the slack that goes with it; nullptr when d does not allow it
+    float* Xsplit; float* hn_split;
+    bool split_ready = false;        // filled in this call
     size_t bytes;
     KnnWs(void* ws, int64_t N, int32_t d, bool with_order, int32_t k = 0)
     {
@@ -271,6 +277,11 @@ struct KnnWs {
         counters = c.take<unsigned long long>(32);
         hn = c.take<float>((size_t)N);
         part_idx = nullptr; part_dist = nullptr; part_rows = 0;
+        Xsplit = nullptr; hn_split = nullptr;
+        if (split_products_ok(d) && k > 0) {
+            Xsplit = c.take<float>((size_t)N * d);
+            hn_split = c.take<float>((size_t)N);
+        }
         {
             // ranges x rows never exceeds the workgroup slots x 128: a sweep is only split while its panels
             // fill less than half the slots
@@ -561,6 +572,12 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     } else {
         p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
         p.part_idx = ws.part_idx; p.part_dist = ws.part_dist; p.part_rows = ws.part_rows;
+        if (ws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
+            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, stream));
+            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
+            p.Xq_split = p.Xc_split = ws.Xsplit; p.hq = p.hc = ws.hn_split;
+            ws.split_ready = true;
+        }
 #ifdef SLHC_PHASE_TIMERS
         p.phase_cycles = ws.counters + 16;
 #endif
@@ -1322,6 +1339,16 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
                     p.qcolour = p.ccolour = ws.colour;
                     p.rows = rows;
+                    if (kws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
+                        if (!kws.split_ready) {          // (a pruned k-NN sweep did not need it)
+                            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, kws.Xsplit, s));
+                            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, kws.hn_split, s, nullptr, true));
+                            kws.split_ready = true;
+                        }
+                        // (the larger slack of these half norms also suits the streaming kernel, should the launch
+                        // below choose it: more slack only lets more pairs through to the exact evaluation)
+                        p.Xq_split = p.Xc_split = kws.Xsplit; p.hq = p.hc = kws.hn_split;
+                    }
                 }
 #ifdef SLHC_STUDY_PANEL_STEPS
                 int* study_steps = reinterpret_cast<int*>(kws.order.gap_ws);    // unused while the table of tile pairs serves

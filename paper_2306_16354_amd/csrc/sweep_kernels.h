@@ -14,6 +14,14 @@ struct SweepParams {
     const float* Xc;       // [NC, d] candidate rows
     const float* hc;       // [NC]
     int NQ, NC, d, k;
+    // Optional (every-tile sweeps of sweep_kernel_qreg, d % 32 == 0, d >= 64): the same two matrices with every
+    // value split into two bfloat16 halves, hi = bf16(x) and lo = bf16(x - hi), laid out chunk by chunk: the 32
+    // floats of columns 32c .. 32c+31 of a row are replaced by 32 hi values then 32 lo values (launch_split_bf16).
+    // The tile products are then accumulated as hi*hi + hi*lo + lo*hi on the bf16 MFMA, which runs at 16 times
+    // the fp32 rate; hq / hc must come from launch_half_norms with split_slack_coefficient(d), whose slack
+    // covers the dropped lo*lo terms.  Only the filter changes: pairs that pass are re-evaluated from Xq / Xc.
+    const float* Xq_split;
+    const float* Xc_split;
     int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
     const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)
@@ -96,8 +104,12 @@ struct SweepParams {
 };
 
 float filter_slack_coefficient(int d);
+float split_slack_coefficient(int d);                 // the same for products accumulated from split bf16 halves
+// X [N, d] -> the chunk-wise split copy described at SweepParams::Xq_split (d % 32 == 0)
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream);
 // `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
-hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr);
+hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr,
+                             bool split_slack = false);
 // Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
 // *flop receives the floating-point operations of the launch.  `sink`: one device float.
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);

@@ -33,6 +33,7 @@ namespace slhc {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int WG_THREADS = 256;
 constexpr int BM = 128;            // query rows per workgroup (32 per wavefront)
@@ -891,9 +892,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 #define FINE_MARK(i) PHASE_MARK(i)
 #endif
 
-template <int KL, bool MASKED, int DCH, bool PRUNE>
+template <int KL, bool MASKED, int DCH, bool PRUNE, bool SPLIT = false>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
 {
+    static_assert(!(SPLIT && PRUNE), "split bf16 products: every-tile sweeps only");
     const SweepLds<KL> L(sweep_smem);
     float* bounds = L.bounds; int* qid = L.qid; float* hqs = L.hqs;
     unsigned long long* lists = L.lists;
@@ -1115,15 +1117,23 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         unsigned int fresh_bits = __float_as_uint(thr_c);
 
         // query fragments: lane (l32, lhalf) holds columns kk*8 + 4*lhalf .. +3 of its query row
+        // (SPLIT: per chunk of 32 columns and per 16-column step s, the 8 hi values of columns 16 s + 8 lhalf ..
+        // in qf[4 chunk + s] and the 8 lo values in qf[4 chunk + 2 + s]; a chunk of the split copy holds its 32 hi
+        // values in the first 16 words and its 32 lo values in the last 16)
         v4f qf[DCH * 4];
         {
             const unsigned int qo = (unsigned int)(my_qrow >= 0 ? my_qrow : 0) * (unsigned int)d;
 #pragma unroll
             for (int kk = 0; kk < DCH * 4; ++kk) {
-                const int col = kk * 8 + 4 * lhalf;
-                const bool live = col < d;
-                const v4f v = *reinterpret_cast<const v4f*>(Xq + (qo + (live ? (unsigned int)col : 0u)));
-                qf[kk] = live ? v : v4f{0.f, 0.f, 0.f, 0.f};
+                if (SPLIT) {
+                    const int word = (kk >> 2) * KC + ((kk & 2) ? 16 : 0) + 4 * (2 * (kk & 1) + lhalf);
+                    qf[kk] = *reinterpret_cast<const v4f*>(p.Xq_split + (qo + (unsigned int)word));
+                } else {
+                    const int col = kk * 8 + 4 * lhalf;
+                    const bool live = col < d;
+                    const v4f v = *reinterpret_cast<const v4f*>(Xq + (qo + (live ? (unsigned int)col : 0u)));
+                    qf[kk] = live ? v : v4f{0.f, 0.f, 0.f, 0.f};
+                }
             }
         }
 
@@ -1197,7 +1207,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         auto gload = [&](int tile, int chunk) {
             const bool clamped = (tile + 1) * BN > N;
             if (clamped != row_off_clamped) { set_row_off(tile); row_off_clamped = clamped; }
-            const float* base = Xc + ((size_t)tile * BN * (size_t)d + (size_t)(chunk * KC));
+            const float* base = (SPLIT ? p.Xc_split : Xc) + ((size_t)tile * BN * (size_t)d + (size_t)(chunk * KC));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const unsigned int off = (chunk == DCH - 1 && d < DCH * KC) ? row_off[i] - dead_adj : row_off[i];
@@ -1318,6 +1328,27 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                         }
                     }
                 }
+                if (SPLIT) {
+                    // x_c . x_q ~ hi_c hi_q + hi_c lo_q + lo_c hi_q, 16 columns per instruction
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        v8bf ch[4], cl[4];
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const float* at = Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf);
+                            ch[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(at));
+                            cl[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(at + 16));
+                        }
+                        const v8bf qh = __builtin_bit_cast(v8bf, qf[chunk * 4 + s2]);
+                        const v8bf ql = __builtin_bit_cast(v8bf, qf[chunk * 4 + 2 + s2]);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], qh, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], ql, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], qh, acc[b], 0, 0, 0);
+                    }
+                } else {
 #pragma unroll
                 for (int kk = 0; kk < KC / 8; ++kk) {
                     v4f cf[4];
@@ -1331,6 +1362,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                         for (int b = 0; b < 4; ++b)
                             acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(cf[b][e], q[e], acc[b], 0, 0, 0);
                     }
+                }
                 }
                 // Nothing that consumes the loads issued at the top of this chunk may move up into its
                 // multiplies: the chunks are unrolled, and the scheduler otherwise hoists the select that
@@ -1791,9 +1823,52 @@ float filter_slack_coefficient(int d)
     return (float)(d + 8) * 1.1920928955078125e-07f;
 }
 
-hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite)
+float split_slack_coefficient(int d)
 {
-    const float scale = 0.5f * (1.0f - filter_slack_coefficient(d));
+    // x = hi + lo + r with |r| <= 2^-16 |x| (two roundings to 8 significant bits).  The accumulated sum
+    // hi_c hi_q + hi_c lo_q + lo_c hi_q leaves out lo_c lo_q and the r terms: at most 3 * 2^-16 |x_c x_q| per
+    // column, i.e. 3 * 2^-16 (n_q + n_c) / 2 per pair.  Its products are exact in float32 and there are 3 d of
+    // them to accumulate, counted like the d of filter_slack_coefficient.
+    return 3.0f * 1.52587890625e-05f + (float)(3 * d + 8) * 1.1920928955078125e-07f;
+}
+
+// one thread per 8 columns: hi = bf16(x), lo = bf16(x - hi), both rounded to nearest even
+__global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ X, long long octets, int d,
+                                                         float* __restrict__ Xsplit)
+{
+    const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (o >= octets) return;
+    const int per_row = d >> 3;
+    const long long row = o / per_row;
+    const int oct = (int)(o - row * per_row);              // columns 8 oct .. 8 oct + 7
+    const int chunk = oct >> 2, piece = oct & 3;
+    const float* src = X + row * d + 8 * oct;
+    const v4f a = *reinterpret_cast<const v4f*>(src), b = *reinterpret_cast<const v4f*>(src + 4);
+    v8bf hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = e < 4 ? a[e] : b[e - 4];
+        const __bf16 h = (__bf16)x;
+        hi[e] = h;
+        lo[e] = (__bf16)(x - (float)h);
+    }
+    float* dst = Xsplit + row * d + chunk * KC;            // chunk: 16 words of hi, 16 words of lo
+    *reinterpret_cast<v4f*>(dst + 4 * piece) = __builtin_bit_cast(v4f, hi);
+    *reinterpret_cast<v4f*>(dst + 16 + 4 * piece) = __builtin_bit_cast(v4f, lo);
+}
+
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream)
+{
+    if (d % KC != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit)) & 15) != 0) return hipErrorInvalidValue;
+    const long long octets = (long long)N * (d >> 3);
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, Xsplit);
+    return hipGetLastError();
+}
+
+hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite,
+                             bool split_slack)
+{
+    const float scale = 0.5f * (1.0f - (split_slack ? split_slack_coefficient(d) : filter_slack_coefficient(d)));
     const long long threads = (long long)N * 16;
     const int blocks = (int)((threads + 255) / 256);
     const bool vec4 = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
@@ -1844,6 +1919,12 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
             return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, true>, grid, lds, p, stream);
         }
         if (p.qslot || p.tile_colour || p.panel_counter || p.own_tile_first) return hipErrorInvalidValue;
+        if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= 2 &&
+            (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
+            if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, false, true>, grid, lds, p, stream);
+            if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, false, true>, grid, lds, p, stream);
+            return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, false, true>, grid, lds, p, stream);
+        }
         if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, false>, grid, lds, p, stream);
         if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, false>, grid, lds, p, stream);
         if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, false>, grid, lds, p, stream);

@@ -55,7 +55,7 @@ def test_status_numbering_matches_the_header():
                       "SLHC_WORKSPACE_TOO_SMALL": "3", "SLHC_HIP_ERROR": "4", "SLHC_NONFINITE": "5",
                       "SLHC_INTERNAL": "6", "SLHC_HOST_MEMORY": "7"}
     assert re.search(r"#define SLHC_ABI_VERSION 2\b", text)
-    assert re.search(r"#define SLHC_PRUNE 1u", text) and re.search(r"#define SLHC_SPLIT_ROUNDS 2u", text) and re.search(r"#define SLHC_SPLIT_SCANS 4u", text) and re.search(r"#define SLHC_NO_TILE_TABLE 8u", text) and re.search(r"#define SLHC_AUTO_PRUNE_MIN_ROWS 24576", text)
+    assert re.search(r"#define SLHC_PRUNE 1u", text) and re.search(r"#define SLHC_SPLIT_ROUNDS 2u", text) and re.search(r"#define SLHC_SPLIT_SCANS 4u", text) and re.search(r"#define SLHC_NO_TILE_TABLE 8u", text) and re.search(r"#define SLHC_AUTO_PRUNE_MIN_ROWS 24576", text) and re.search(r"#define SLHC_FP32_FILTER 16u", text)
 
 
 def test_no_exception_crosses_the_boundary():
