@@ -199,8 +199,6 @@ constexpr int TILE_GAP_MAX_TILES = SLHC_TILE_GAP_MAX_TILES;
 #define SLHC_DENDROGRAM_THREADS_MIN_ROWS 200000
 #endif
 constexpr int64_t DENDROGRAM_THREADS_MIN_ROWS = SLHC_DENDROGRAM_THREADS_MIN_ROWS;
-// tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
-bool split_products_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <= 128; }
 bool prunable(int64_t N, int32_t d) { return d % 4 == 0 && d <= 128 && N >= PRUNE_MIN_ROWS; }
 #ifndef SLHC_PIVOT_STRIDE
 #define SLHC_PIVOT_STRIDE 64
@@ -212,9 +210,13 @@ int64_t padded_rows_limit(int64_t N) { return N + N / 2 + 256; }
 
 size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 
+// tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
+bool split_products_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <= 128; }
+
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {
     float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *tile_gap, *n_w, *n_heights;
+    float *Xs_split, *hs_split;      // the reordered copy in split bfloat16 halves and its half norms (nullptr: d does not allow it)
     int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *tile_list, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
     uint32_t *tmp_a, *tmp_b, *tmp_c;
@@ -236,6 +238,8 @@ struct OrderWs {
         Xp = c.take<float>(pm * d); hp = c.take<float>(pm);
         pdist = c.take<float>(n); sample = c.take<float>(SAMPLE);
         Xs = c.take<float>(nm * d); hs = c.take<float>(nm);
+        Xs_split = nullptr; hs_split = nullptr;
+        if (split_products_ok(d)) { Xs_split = c.take<float>(nm * d); hs_split = c.take<float>(nm); }
         tile_c = c.take<float>((size_t)Tmax * d); tile_r = c.take<float>((size_t)Tmax);
         int grid = slhc::sweep_grid_limit();
         if (grid < 1) grid = 512;
@@ -270,6 +274,7 @@ struct KnnWs {
     // norms with the slack that goes with it; nullptr when d does not allow it
     float* Xsplit; float* hn_split;
     bool split_ready = false;        // filled in this call
+    bool order_split_ready = false;  // likewise the split copy of the reordered rows
     size_t bytes;
     KnnWs(void* ws, int64_t N, int32_t d, bool with_order, int32_t k = 0)
     {
@@ -557,6 +562,14 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (prune) {
         const OrderWs& o = ws.order;
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
+        if (o.Xs_split && ws.hn_split && !(flags & SLHC_FP32_FILTER)) {
+            // the reordered copy in split halves too; its half norms are those of the rows (padding: +inf)
+            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
+            HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream));
+            HIP_TRY(slhc::order_gather_f32(ws.hn_split, o.perm, o.Ns, (int)N, __builtin_inff(), o.hs_split, stream));
+            p.Xq_split = p.Xc_split = o.Xs_split; p.hq = p.hc = o.hs_split;
+            ws.order_split_ready = true;
+        }
         p.q_out_row = o.perm; p.c_id = o.perm;
         p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
         p.tile_gap = (flags & SLHC_NO_TILE_TABLE) ? nullptr : o.tile_gap;
@@ -1311,6 +1324,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     if (h_cnt[6] < 0 || h_cnt[6] > (o.Ns + 127) / 128) { set_err("bad count of queried tiles %d", h_cnt[6]); return SLHC_INTERNAL; }
                     p.panel_list = o.tile_list; p.panel_list_n = h_cnt[6];
                     p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
+                    if (kws.order_split_ready) { p.Xq_split = p.Xc_split = o.Xs_split; p.hq = p.hc = o.hs_split; }
                     p.qcolour = p.ccolour = o.colour_s;
                     p.qslot = o.qslot;
                     p.c_id = o.perm;

@@ -14,7 +14,7 @@ struct SweepParams {
     const float* Xc;       // [NC, d] candidate rows
     const float* hc;       // [NC]
     int NQ, NC, d, k;
-    // Optional (every-tile sweeps of sweep_kernel_qreg, d % 32 == 0, d >= 64): the same two matrices with every
+    // Optional (sweep_kernel_qreg, d % 32 == 0, d >= 64): the same two matrices with every
     // value split into two bfloat16 halves, hi = bf16(x) and lo = bf16(x - hi), laid out chunk by chunk: the 32
     // floats of columns 32c .. 32c+31 of a row are replaced by 32 hi values then 32 lo values (launch_split_bf16).
     // The tile products are then accumulated as hi*hi + hi*lo + lo*hi on the bf16 MFMA, which runs at 16 times

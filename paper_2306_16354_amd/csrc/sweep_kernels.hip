@@ -895,7 +895,6 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 template <int KL, bool MASKED, int DCH, bool PRUNE, bool SPLIT = false>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p)
 {
-    static_assert(!(SPLIT && PRUNE), "split bf16 products: every-tile sweeps only");
     const SweepLds<KL> L(sweep_smem);
     float* bounds = L.bounds; int* qid = L.qid; float* hqs = L.hqs;
     unsigned long long* lists = L.lists;
@@ -1913,6 +1912,12 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
             if (!p.tile_r || !p.gap_ws) return hipErrorInvalidValue;
+            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= 2 &&
+                (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
+                if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, true, true>, grid, lds, p, stream);
+                if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, true, true>, grid, lds, p, stream);
+                return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, true, true>, grid, lds, p, stream);
+            }
             if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, true>, grid, lds, p, stream);
             if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, true>, grid, lds, p, stream);
             if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, true>, grid, lds, p, stream);

@@ -592,6 +592,48 @@ def test_pruned_random_shapes(lib):
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
 
+# ----------------------------------------------------------------------------- tile products from split bfloat16 halves
+@pytest.mark.parametrize("kind", ["offset", "mantissa", "mixed_scale", "duplicates", "lattice", "tiny"])
+@pytest.mark.parametrize("d", [64, 96, 128])
+def test_split_bf16_filter_loses_nothing(lib, kind, d):
+    """From 64 to 128 features the every-tile sweeps form their tile products from bfloat16 halves
+    (hi*hi + hi*lo + lo*hi) and widen the filter's slack by what that drops.  The filter only decides
+    which pairs are evaluated exactly, so lists and trees must equal those of the float32 products bit for
+    bit, and the oracle's on sampled rows, also where the slack is put to the test: a common offset far
+    larger than the distances, values that use all 24 bits, rows of very different scale, duplicates, a
+    lattice with many exact ties, tiny values."""
+    rng = np.random.default_rng(len(kind) * 1000 + d)
+    N = int(rng.integers(3000, 9000))
+    k = int(rng.choice([1, 5, 16, 32, 64]))
+    X = rng.standard_normal((N, d))
+    if kind == "offset":
+        X = 0.01 * X + 1000.0 * rng.standard_normal((1, d))
+    elif kind == "mantissa":
+        X = X * (1.0 + 2.0 ** -23 * rng.integers(0, 2 ** 22, size=(N, d)))
+    elif kind == "mixed_scale":
+        X = X * np.where(rng.random((N, 1)) < 0.1, 3.0e3, 1.0)
+    elif kind == "duplicates":
+        X[rng.integers(0, N, size=N // 3)] = X[rng.integers(0, N, size=N // 3)]
+    elif kind == "lattice":
+        X = np.round(X)
+    elif kind == "tiny":
+        X = X * 1.0e-15
+    X = np.ascontiguousarray(X.astype(np.float32))
+    Xd = torch.from_numpy(X).cuda()
+    print(f"split bf16 filter: {kind} N={N} d={d} k={k}", flush=True)
+    a = lib.knn_graph(Xd, k, fp32_filter=True)
+    b = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    rows = rng.choice(N, size=150, replace=False)
+    check_knn(X, k, b[0].cpu().numpy()[rows], b[1].cpu().numpy()[rows], rows=rows,
+              min_exact=0.0 if kind in ("duplicates", "lattice") else 0.9)
+    ta = lib.slhc(Xd, min(k, 16), prune=False, fp32_filter=True)
+    tb = lib.slhc(Xd, min(k, 16), prune=False)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(ta[name_], tb[name_]), name_
+
+
 # ----------------------------------------------------------------------------- default entry point
 def test_default_entry_point_prunes_from_its_limit(lib):
     """slhc_slhc runs the every-tile path below SLHC_AUTO_PRUNE_MIN_ROWS rows and the pruned one from there
