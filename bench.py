@@ -34,6 +34,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X published dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X published dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -48,6 +49,8 @@ def main():
     ap.add_argument("--knn-only", action="store_true", help="time slhc_knn_graph alone (kernel study)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-pruned-leg", action="store_true", help="skip the extra runs with tile pruning")
+    ap.add_argument("--no-fp32-leg", action="store_true",
+                    help="skip the extra k-NN launches with float32 tile products (roofline_fp32_products)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy three times and exit (reference for HBM counters)")
     ap.add_argument("--loop-study", action="store_true",
@@ -137,6 +140,24 @@ def main():
 
     empirical_tflops = slhc.probe_fp32_mfma(dev)       # register-only MFMA loop, same process, right after the steps
 
+    # Which products the timed sweeps formed: float32 on the fp32 MFMA, or (64 to 128 features, the library's
+    # default) split bfloat16 halves hi*hi + hi*lo + lo*hi on the bf16 MFMA.  Either way every pair that can
+    # enter a list is re-evaluated in float32, so the outputs are the same bits.
+    split = (not args.knn_only and bool(stats[-1].get("split_products", 0))) or \
+            (args.knn_only and d % 32 == 0 and 64 <= d <= 128)
+    peak_tflops = PEAK_BF16_MFMA_TFLOPS if split else PEAK_FP32_MFMA_TFLOPS
+    # the float32-product variant of the same sweep, once, outside the timed region (the kernel earlier
+    # reports quote)
+    fp32_ms = None
+    if split and not args.no_fp32_leg:
+        for rep_ in range(2):                                   # second pass reported
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            knn_out = slhc.knn_graph(Xd, k, out=knn_out, workspace=ws, fp32_filter=True)
+            e1.record()
+            torch.cuda.synchronize()
+            fp32_ms = e0.elapsed_time(e1)
+
     knn_kernel_ms = mean("ms_knn_kernel")
     knn_ms = knn_kernel_ms + mean("ms_norm_kernel")
     pairs = float(N) * float(N)
@@ -155,7 +176,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32 (tile products from split bf16 halves on the bf16 MFMA, accumulated in f32; every listed pair "
+                 "re-evaluated in f32)" if split else "f32",
         "data": "synthetic",
         "config": {
             "workload": f"{args.workload}: N={N} d={d} k={k} squared-L2 "
@@ -165,25 +187,39 @@ def main():
             "N": N, "d": d, "k": k,
         },
         "slhc_seconds": None if args.knn_only else ms_per_step / 1e3,
-        "pct_fp32_mfma_peak": 100.0 * achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
+        "pct_fp32_mfma_peak": None if split else 100.0 * achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
         "roofline": {
-            "kernel": "sweep_kernel (fused distance tile + filter + top-k)",
+            "kernel": "sweep_kernel (fused distance tile + filter + top-k)" +
+                      (", products from split bf16 halves" if split else ""),
             "bound": "mfma",
             "achieved": achieved_tflops,
-            "peak": PEAK_FP32_MFMA_TFLOPS,
+            "peak": peak_tflops,
             "unit": "TFLOP/s",
-            "frac": achieved_tflops / PEAK_FP32_MFMA_TFLOPS,
+            "frac": achieved_tflops / peak_tflops,
             "traffic": None,
             "launch_ms": knn_kernel_ms,
             "algorithmic_flop_per_launch": flops,
+            "executed_mfma_flop_per_launch": 3.0 * flops if split else flops,
+            "frac_executed": (3.0 if split else 1.0) * achieved_tflops / peak_tflops,
+            "note": ("achieved counts the algorithmic 2 d N^2 against the bf16 MFMA peak; the kernel executes three "
+                     "bf16 products per multiply-add (frac_executed) and is bound by LDS operand reads, the "
+                     "candidate stream and the exact re-evaluation of the pairs that pass, not by the MFMA pipe")
+                    if split else "",
             "empirical_peak": empirical_tflops,
-            "frac_of_empirical_peak": achieved_tflops / empirical_tflops,
+            "frac_of_empirical_peak": None if split else achieved_tflops / empirical_tflops,
             "empirical_peak_note": "TFLOP/s of a register-only v_mfma_f32_32x32x2_f32 loop (4 accumulator blocks "
                                    "per wavefront, 8 wavefronts per CU) measured in this run: what the chip "
                                    "sustains at the clocks it holds under MFMA load",
         },
         "input_generation_s": gen_s,
     }
+    if fp32_ms is not None:
+        ft = flops / (fp32_ms * 1e-3) / 1e12
+        line["roofline_fp32_products"] = {
+            "kernel": "sweep_kernel with float32 products (SLHC_FP32_FILTER): norms + sweep, one launch outside the timed region",
+            "bound": "mfma", "achieved": ft, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": ft / PEAK_FP32_MFMA_TFLOPS, "launch_ms": fp32_ms, "pairs_per_s": pairs / (fp32_ms * 1e-3),
+            "frac_of_empirical_peak": ft / empirical_tflops}
     # HBM traffic is not measurable from inside the run; it comes from the committed rocprofv3 counter runs
     # of this same workload (profiles/traffic.json: one entry per kernel, keyed by workload and kernel name,
     # FETCH_SIZE + WRITE_SIZE scaled by what the same counters read for a plain copy of known size)
@@ -203,7 +239,9 @@ def main():
             obj["traffic_unit"] = ent["per"]
             obj["traffic_kernel"] = ent["kernel"]
 
-    attach_traffic(line["roofline"], "knn_sweep")
+    attach_traffic(line["roofline"], "knn_sweep_split" if split else "knn_sweep")
+    if "roofline_fp32_products" in line:
+        attach_traffic(line["roofline_fp32_products"], "knn_sweep")
     if not args.knn_only:
         line["stages_ms"] = {n: mean(n) for n in ("ms_knn", "ms_norm_kernel", "ms_knn_kernel", "ms_boruvka",
                                                   "ms_connect", "ms_connect_kernels", "ms_sort",
@@ -216,10 +254,10 @@ def main():
         if cq > 0 and mean("ms_connect_kernels") > 0:
             ct = 2.0 * d * cq * N / (mean("ms_connect_kernels") * 1e-3) / 1e12
             line["roofline_connect"] = {"kernel": "sweep_kernel (cross-component 1-NN)", "bound": "mfma",
-                                        "achieved": ct, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                                        "frac": ct / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
-                                        "frac_of_empirical_peak": ct / empirical_tflops}
-            attach_traffic(line["roofline_connect"], "connect_sweeps")
+                                        "achieved": ct, "peak": peak_tflops, "unit": "TFLOP/s",
+                                        "frac": ct / peak_tflops, "traffic": None,
+                                        "frac_executed": (3.0 if split else 1.0) * ct / peak_tflops}
+            attach_traffic(line["roofline_connect"], "connect_sweeps_split" if split else "connect_sweeps")
 
     if not args.knn_only:
         # graph / Boruvka stage against the HBM roofline: per round every list entry (4 B index) and the

@@ -45,7 +45,7 @@
 extern "C" {
 #endif
 
-#define SLHC_ABI_VERSION 2
+#define SLHC_ABI_VERSION 3
 
 /* Largest k of the fused path: the selection keeps one list entry per lane of a 64-wide
  * wavefront.  (The paper's fused k-NN has the same limit, Sec. 2 and Sec. 3.1.1: k <= 64.) */
@@ -89,6 +89,9 @@ typedef struct slhc_stats {
     int64_t connect_tile_steps;      /* same, summed over the connection sweeps                    */
     int32_t pruned;                  /* 1 when tile pruning was active in this call                */
     int32_t order_padded_rows;       /* rows of the reordered copy incl. padding (0 when not pruned) */
+    int32_t split_products;          /* 1 when the k-NN sweep formed its tile products from split bfloat16
+                                        halves (see SLHC_FP32_FILTER), 0 when in float32              */
+    int32_t reserved0;
 } slhc_stats;
 
 /* Option flags of the *_opt entry points. */

@@ -29,6 +29,7 @@ class _Stats(ctypes.Structure):
         ("ms_connect_kernels", ctypes.c_float), ("ms_order", ctypes.c_float),
         ("knn_tile_steps", ctypes.c_int64), ("connect_tile_steps", ctypes.c_int64),
         ("pruned", ctypes.c_int32), ("order_padded_rows", ctypes.c_int32),
+        ("split_products", ctypes.c_int32), ("reserved0", ctypes.c_int32),
     ]
 
 SLHC_PRUNE = 1

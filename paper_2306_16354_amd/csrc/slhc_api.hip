@@ -343,13 +343,22 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
 int bits_for(long long n) { int b = 1; while (b < 32 && (1LL << b) < n) ++b; return b; }
 
 // Nearest pivot of every row by the fused sweep (k = 1 against the P pivot rows).
-int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, int P, hipStream_t s)
+// `x_split` / `hn_split` (optional): X in split bfloat16 halves and the half norms that go with it; the pivots
+// then get a split copy of their own (in the buffers of the reordered copy's, which are free until step 4).
+int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, int P, hipStream_t s,
+                     const float* x_split = nullptr, const float* hn_split = nullptr)
 {
     slhc::SweepParams p{};
     p.Xq = X; p.hq = hn; p.NQ = (int)N;
     p.Xc = o.Xp; p.hc = o.hp; p.NC = P;
     p.d = d; p.k = 1;
     p.out_idx = o.pid; p.out_dist = o.pdist;
+    if (x_split && hn_split && o.Xs_split && o.hs_split) {
+        HIP_TRY(slhc::launch_split_bf16(o.Xp, P, d, o.Xs_split, s));
+        HIP_TRY(slhc::launch_half_norms(o.Xp, P, d, o.hs_split, s, nullptr, true));
+        p.Xq_split = x_split; p.hq = hn_split;
+        p.Xc_split = o.Xs_split; p.hc = o.hs_split;
+    }
     HIP_TRY(slhc::launch_knn_sweep(p, s));
     return SLHC_OK;
 }
@@ -368,7 +377,7 @@ int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, Orde
 // `nonfinite`: device word the norm kernel set when a row is not finite; checked first, because
 // nothing below is defined for such rows.
 int build_order(const float* X, int64_t N, int32_t d, const float* hn, const unsigned int* nonfinite, OrderWs& o,
-                hipStream_t s)
+                hipStream_t s, const float* x_split = nullptr, const float* hn_split = nullptr)
 {
     const int n = (int)N;
     const int P1 = o.P1;
@@ -390,7 +399,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, const uns
 
     // ---- 1. pivots and assignment
     HIP_TRY(slhc::order_pick_rows(X, hn, n, d, P1, o.Xp, o.hp, s));
-    int rc = assign_to_pivots(X, N, d, hn, o, P1, s);
+    int rc = assign_to_pivots(X, N, d, hn, o, P1, s, x_split, hn_split);
     if (rc != SLHC_OK) return rc;
     const int S = n < OrderWs::SAMPLE ? n : OrderWs::SAMPLE;
     HIP_TRY(slhc::order_pick_f32(o.pdist, n, S, o.sample, s));
@@ -548,7 +557,14 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (pruned_out) *pruned_out = prune;
     if (ev_order) HIP_TRY(hipEventRecord(ev_order->a, stream));
     if (prune) {
-        const int rc = build_order(X, N, d, ws.hn, reinterpret_cast<const unsigned int*>(ws.counters + 4), ws.order, stream);
+        const bool split = ws.Xsplit && ws.hn_split && !(flags & SLHC_FP32_FILTER);
+        if (split) {        // X in split halves: for the nearest-pivot sweep here and for every-tile sweeps later
+            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, stream));
+            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
+            ws.split_ready = true;
+        }
+        const int rc = build_order(X, N, d, ws.hn, reinterpret_cast<const unsigned int*>(ws.counters + 4), ws.order, stream,
+                                   split ? ws.Xsplit : nullptr, split ? ws.hn_split : nullptr);
         if (rc != SLHC_OK) return rc;
     }
     if (ev_order) HIP_TRY(hipEventRecord(ev_order->b, stream));
@@ -564,7 +580,6 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
         if (o.Xs_split && ws.hn_split && !(flags & SLHC_FP32_FILTER)) {
             // the reordered copy in split halves too; its half norms are those of the rows (padding: +inf)
-            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
             HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream));
             HIP_TRY(slhc::order_gather_f32(ws.hn_split, o.perm, o.Ns, (int)N, __builtin_inff(), o.hs_split, stream));
             p.Xq_split = p.Xc_split = o.Xs_split; p.hq = p.hc = o.hs_split;
@@ -1477,6 +1492,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     st.connect_filter_survivors = (int64_t)h_surv[1];
     st.connect_tile_steps = (int64_t)h_surv[3];
     st.pruned = pruned ? 1 : 0;
+    st.split_products = (kws.split_ready || kws.order_split_ready) ? 1 : 0;
     if (pruned) { st.order_pivots = kws.order.P; st.order_padded_rows = kws.order.Ns; }
     const double t_forest = now_ms();
     st.ms_connect = (float)ms_connect;
