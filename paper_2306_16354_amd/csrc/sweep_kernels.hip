@@ -932,6 +932,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     // position s, so each part begins among the near tiles; the parts keep separate thresholds and meet in
     // p.out_key by a 64-bit atomic minimum, which is the (distance, index) order of the lists.  A few panels
     // whose queries admit thousands of tiles otherwise outlast the rest of a launch several times over.
+    // The pairs that pass the filter are either resolved step by step, all flagged blocks through one queue
+    // (pruned sweeps, whose near tiles leave dozens per step; split-product sweeps, whose wider slack lets two to
+    // three times as many through: 1M x 128 4.5 per wavefront and step, 1003 -> 901 ms against queueing), or queued
+    // across steps and resolved eight at a time (every-tile sweeps with float32 products: one or two per step).
+    constexpr bool BATCHED = PRUNE || SPLIT;
     constexpr bool CAN_SPLIT = PRUNE && MASKED && KL == 1;
     // k-NN sweeps of few panels (k > 1, every tile): part s of a panel takes the s-th range of the candidate
     // tiles and writes lists of its own; see SweepParams::part_idx.
@@ -1431,7 +1436,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 // multiplies of the other workgroup's wavefront on this SIMD (measured: 0.8 %)
                 __builtin_amdgcn_s_setprio(1);
                 const int my_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
-                if (PRUNE) {
+                if (BATCHED) {
                     // First tile of a k-NN panel (k > 1): fill the lists from its best candidates (see
                     // seed_range).  Later tiles were tried too and gain nothing: what passes there are
                     // mostly real list updates.
@@ -1541,7 +1546,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 __builtin_amdgcn_s_setprio(0);
                 if (prune) refresh_wave_thr();
             }
-            if (!PRUNE) {
+            if (!BATCHED) {
                 // Deferred pairs are resolved by all four wavefronts in the same step: a wavefront in the
                 // rare path keeps the other three waiting at the next barrier, so four queues that fill
                 // and resolve at different steps stall the workgroup four times as often as queues
@@ -1597,7 +1602,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         if (p.panel_steps && tid == 0) { atomicAdd(p.panel_steps + panel, step); atomicMax(p.panel_steps + npanels + panel, (int)((clock64() - study_t0) >> 10)); }
 #endif
         // ---- panel epilogue: lists are already ascending; write them out ----
-        if (!PRUNE) {
+        if (!BATCHED) {
             const int waiting_ = *deferred_count(L, wave);
             if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
         }
