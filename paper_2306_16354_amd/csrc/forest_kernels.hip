@@ -35,6 +35,14 @@ static inline int blocks_for(long long n) { return (int)((n + TB - 1) / TB); }
 // access is skipped, so corrupt state can never become an out-of-bounds access.
 __device__ inline bool in_range(int i, int n) { return (unsigned int)i < (unsigned int)n; }
 __device__ inline void report(const ForestState& f, int site) { atomicCAS(&f.counters[3], 0, site); }
+// The first failed check of a state error also leaves what it saw in counters[16..23], for the host's message.
+__device__ inline void report_with(const ForestState& f, int site, int a, int b, int c, int d, int e, int g)
+{
+    if (atomicCAS(&f.counters[3], 0, site) == 0) {
+        f.counters[16] = site; f.counters[17] = a; f.counters[18] = b; f.counters[19] = c;
+        f.counters[20] = d; f.counters[21] = e; f.counters[22] = g;
+    }
+}
 
 // atomicMin that first looks: the per-component minima only decrease, so a value that does not beat
 // what is already there never needs the atomic (a stale, larger value read here only costs an atomic).  In late rounds one component holds most vertices and
@@ -117,7 +125,9 @@ __global__ void __launch_bounds__(TB) k_round_reset(ForestState f)
     f.best_w[v] = INF_BITS;
     f.best_e[v] = ~0ull;
     f.min_lb[v] = INF_BITS;
-    if (v == 0) { f.counters[0] = 0; f.counters[2] = 0; }
+    // (counters[2], the "hook chains unresolved" flag, is cleared by k_commit: the scan of the next round, and
+    // with it this kernel, is enqueued behind the relabelling, before the host has read the flag)
+    if (v == 0) f.counters[0] = 0;
 }
 
 // G lanes per vertex walk its list from ptr[v] on, G entries at a time, until an entry of another colour
@@ -234,6 +244,8 @@ __global__ void __launch_bounds__(TB) k_apply_queries(ForestState f, const int32
         if (!in_range(v, f.N) || u < -1 || u >= f.N || !in_range(f.colour[v], f.N)) report(f, 6);
         else {
             c = f.colour[v];
+            // an answer inside the query's own component can only come from a broken sweep
+            if (u >= 0 && f.colour[u] == c) report_with(f, 14, q, v, u, c, (int)__float_as_uint(w), nq);
             bool exact = true;
             if (thresholds) {
                 const uint32_t fb = thresholds[c];
@@ -332,6 +344,7 @@ __global__ void __launch_bounds__(TB_WIDE) k_commit(ForestState f)
     __shared__ int wave_count[TB_WIDE / 64];
     __shared__ int wave_base[TB_WIDE / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (blockIdx.x == 0 && threadIdx.x == 0) f.counters[2] = 0;     // set again by k_jump if a hook chain stays unresolved
     int lo[COMMIT_ITEMS], hi[COMMIT_ITEMS];
     uint32_t wbits[COMMIT_ITEMS];
     unsigned int adds = 0;             // bit i: vertex i of this thread appends its component's edge
@@ -352,7 +365,8 @@ __global__ void __launch_bounds__(TB_WIDE) k_commit(ForestState f)
             else {
                 const int clo = f.colour[elo], chi = f.colour[ehi];
                 const int other = (clo == v) ? chi : clo;
-                if (!in_range(other, f.N) || other == v || (clo != v && chi != v)) report(f, 9);
+                if (!in_range(other, f.N) || other == v || (clo != v && chi != v))
+                    report_with(f, 9, v, elo, ehi, clo, chi, (int)wb);
                 else {
                     const bool mutual = (f.best_w[other] == wb) && (f.best_e[other] == e);
                     if (!mutual || v < other) { adds |= 1u << i; lo[i] = elo; hi[i] = ehi; wbits[i] = wb; }

@@ -1257,7 +1257,15 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     auto read_counters = [&]() -> int {
         HIP_TRY(hipMemcpyAsync(h_cnt, ws.counters, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
-        if (h_cnt[3] != 0) { set_err("forest state check %d failed", h_cnt[3]); return SLHC_INTERNAL; }
+        if (h_cnt[3] != 0) {
+            // what the failed check saw (counters[16..22], written by the thread whose report came first)
+            HIP_TRY(hipMemcpyAsync(h_cnt + 8, ws.counters + 16, 7 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            set_err("forest state check %d failed in round %d (%s rounds, %d connection rounds): %d %d %d %d %d %d", h_cnt[3],
+                    st.boruvka_rounds, pruned ? "pruned" : "every-tile", st.connect_rounds,
+                    h_cnt[9], h_cnt[10], h_cnt[11], h_cnt[12], h_cnt[13], h_cnt[14]);
+            return SLHC_INTERNAL;
+        }
         return SLHC_OK;
     };
     rc = enqueue_scan();
@@ -1390,7 +1398,30 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                 HIP_TRY(slhc::launch_segmented_cross_1nn(p, round_pruned ? ws.keys_b : ws.keys_a, s));
                 HIP_TRY(hipEventRecord(ev_conn.b, s));
                 HIP_TRY(slhc::forest_apply_queries(f, rows, ws.q_idx, ws.q_dist, n, round_pruned ? ws.vals_a : nullptr, s));
+                HIP_TRY(hipMemcpyAsync(h_cnt + 7, ws.counters + 3, sizeof(int32_t), hipMemcpyDeviceToHost, s));
                 HIP_TRY(hipStreamSynchronize(s));
+                if (h_cnt[7] == 14) {
+                    // an answer inside the query's own component: say what the sweep was given
+                    HIP_TRY(hipMemcpy(h_cnt + 8, ws.counters + 16, 7 * sizeof(int32_t), hipMemcpyDeviceToHost));
+                    const int q = h_cnt[9], v = h_cnt[10], u = h_cnt[11];
+                    int dv[12] = {-9, -9, -9, -9, -9, -9, -9, -9, -9, -9, -9, -9};
+                    auto peek = [&](const void* base, long long index, int* out) {
+                        if (base && index >= 0) (void)hipMemcpy(out, static_cast<const int32_t*>(base) + index, 4, hipMemcpyDeviceToHost);
+                    };
+                    peek(ws.colour, v, &dv[0]); peek(ws.colour, u, &dv[1]);
+                    peek(ws.q_idx, q, &dv[2]); peek(rows, q, &dv[3]);
+                    if (round_pruned) {
+                        const OrderWs& o = kws.order;
+                        peek(o.inv, v, &dv[4]); peek(o.inv, u, &dv[5]);
+                        if (dv[4] >= 0 && dv[4] < o.Ns) { peek(o.colour_s, dv[4], &dv[6]); peek(o.qslot, dv[4], &dv[8]); peek(o.perm, dv[4], &dv[10]); }
+                        if (dv[5] >= 0 && dv[5] < o.Ns) { peek(o.colour_s, dv[5], &dv[7]); peek(o.qslot, dv[5], &dv[9]); peek(o.perm, dv[5], &dv[11]); }
+                    }
+                    set_err("sweep answer inside the query's component: round %d, %s sweep of %d rows in %d parts, q %d v %d u %d; "
+                            "colour v %d u %d, q_idx[q] %d rows[q] %d, position v %d u %d, colour_s %d %d, qslot %d %d, perm %d %d",
+                            st.boruvka_rounds, round_pruned ? "pruned" : "every-tile", n, p.segments, q, v, u,
+                            dv[0], dv[1], dv[2], dv[3], dv[4], dv[5], dv[6], dv[7], dv[8], dv[9], dv[10], dv[11]);
+                    return SLHC_INTERNAL;
+                }
 #ifdef SLHC_STUDY_PANEL_STEPS
                 if (round_pruned) {
                     std::vector<int> hs((size_t)study_panels * 2);

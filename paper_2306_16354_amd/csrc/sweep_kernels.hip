@@ -927,6 +927,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 #endif
 
     int* next_panel = reinterpret_cast<int*>(L.wmax + 8);      // LDS word after the wmax slots
+    unsigned int* panel_thr_bits = reinterpret_cast<unsigned int*>(L.wmax + 9);   // see the panel prologue
     // Pruned cross 1-NN sweeps with a slot map may split every panel's scan into p.segments work items (item =
     // panel * segments + part): part s takes every segments-th position of the panel's scan order, starting at
     // position s, so each part begins among the near tiles; the parts keep separate thresholds and meet in
@@ -1051,6 +1052,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             const float rq = __uint_as_float(*rq_bits);
             // the colour all queries of the panel share (-2: they differ, or no colour summary)
             panel_colour = (MASKED && p.tile_colour && *col_lo == *col_hi) ? *col_lo : -2;
+            // The component's shared threshold is read ONCE per panel, by one thread, and handed to the others
+            // through LDS (published by the barrier below): other workgroups lower the word while this one
+            // starts, and four wavefronts that each read it for themselves can get four different values,
+            // which then make them skip different tiles.
+            if (MASKED && tid == 0 && p.comp_best != nullptr && panel_colour >= 0 && panel_colour < p.comp_count)
+                *panel_thr_bits = __hip_atomic_load(p.comp_best + panel_colour, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             for (int t = tid; t < (table_row ? 0 : ntiles); t += WG_THREADS) {
                 const float* c = p.tile_c + (size_t)t * d;
                 float s2 = 0.f;
@@ -1102,7 +1109,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         const bool shared_thr = PRUNE && MASKED && p.comp_best != nullptr && panel_colour >= 0 &&
                                 panel_colour < p.comp_count;
         float thr_c = __builtin_inff();
-        if (shared_thr) thr_c = __uint_as_float(p.comp_best[panel_colour]);
+        if (shared_thr) thr_c = __uint_as_float(*panel_thr_bits);       // the same value in all four wavefronts
         // With p.comp_best_lower the threshold also falls while the sweep runs: a wavefront whose query
         // finds a foreign row at distance w with lower_factor * w < thr_c lowers the component's word to
         // that (atomic minimum over the bits of non-negative floats), and every wavefront re-reads the
@@ -1112,9 +1119,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         // the final value (see SweepParams).
         // A wavefront's copy of the threshold (thr_c) differs from its neighbours' while it falls, and the
         // four wavefronts must take the same tile-skipping decision (they share the barrier sequence and
-        // each stages a quarter of every tile): the decision therefore only uses the value all of them
-        // read at the start of the panel (thr_c0) and what each has published in the LDS slots; a
-        // wavefront's own copy only tightens its own filter.
+        // each stages a quarter of every tile): the decision therefore only uses the one value that was
+        // read for the whole workgroup at the start of the panel (thr_c0, handed out through LDS) and
+        // what each wavefront has published in the LDS slots; a wavefront's own copy only tightens its
+        // own filter.
         const bool lowering = shared_thr && p.comp_best_lower != nullptr &&
                               (p.comp_size == nullptr || p.comp_size[panel_colour] >= p.comp_lower_min_size);
         const float thr_c0 = thr_c;

@@ -409,6 +409,17 @@ def test_slhc_increasing_gaps_line(lib):
     assert out["mst_w"].cpu().tolist() == [float((i + 1) ** 2) for i in range(N - 1)]
 
 
+def test_slhc_hook_chain_longer_than_the_device_passes(lib):
+    # every point's lightest edge leads to its left neighbour, so the first round hooks all N components into
+    # one chain; beyond ~1000 hooks the two device passes of pointer jumping do not reach its end and the host
+    # has to finish the chain before the relabelling (weights (i+1)^2 stay exact in float32 up to N = 4096)
+    N = 3000
+    X, pos = gen.increasing_gaps_line(N, 2, seed=5)
+    out = lib.slhc(torch.from_numpy(X).cuda(), 3)
+    check_slhc(X, out, tie_free=True)
+    assert out["mst_w"].cpu().tolist() == [float((i + 1) ** 2) for i in range(N - 1)]
+
+
 def test_slhc_unit_lattice_all_ties(lib):
     X = gen.integer_lattice(12, 2, seed=8)
     out = lib.slhc(torch.from_numpy(X).cuda(), 4)
