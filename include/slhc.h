@@ -45,7 +45,7 @@
 extern "C" {
 #endif
 
-#define SLHC_ABI_VERSION 3
+#define SLHC_ABI_VERSION 4
 
 /* Largest k of the fused path: the selection keeps one list entry per lane of a 64-wide
  * wavefront.  (The paper's fused k-NN has the same limit, Sec. 2 and Sec. 3.1.1: k <= 64.) */
@@ -122,6 +122,14 @@ typedef struct slhc_stats {
                            pair that may enter a list is re-evaluated in float32 either way, so the
                            outputs are the same bit for bit.                                     */
 
+#define SLHC_PANEL_ORDER 32u   /* A testing and tuning aid.  Every-tile sweeps of many query panels (from 4 panels
+                           per workgroup slot on, d <= 128) otherwise hand out their work range by range:
+                           the candidate tiles are cut into ranges of about 2 MiB, all workgroups sweep the
+                           same range at a time (served by every XCD's L2 instead of being fetched from
+                           memory once per panel), and a panel's lists and thresholds travel from range to
+                           range through the output arrays.  With this flag every workgroup sweeps all
+                           candidates for one panel at a time, as the smaller launches do.  Same outputs.  */
+
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */
 const char* slhc_last_error(void);              /* thread-local, never NULL  */
@@ -178,6 +186,9 @@ int slhc_knn_graph_static(const float* X, int64_t N, int32_t d, int32_t k,
  * Synchronous.
  */
 int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream);
+/* The same for v_mfma_f32_32x32x16_bf16, the multiply of the sweeps that form their tile products from split
+ * bfloat16 halves (SLHC_FP32_FILTER describes them); same arguments. */
+int slhc_probe_bf16_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid like slhc_probe_fp32_mfma, for the panel loop of the sweeps (paper Sec. 3.1.1, the

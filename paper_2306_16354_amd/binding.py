@@ -37,6 +37,7 @@ SLHC_SPLIT_ROUNDS = 2
 SLHC_SPLIT_SCANS = 4
 SLHC_NO_TILE_TABLE = 8
 SLHC_FP32_FILTER = 16
+SLHC_PANEL_ORDER = 32
 SLHC_STATIC_MAX_ROWS = 1048576
 
 
@@ -64,6 +65,8 @@ def load_library():
     lib.slhc_knn_graph_static.restype = ctypes.c_int
     lib.slhc_probe_fp32_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     lib.slhc_probe_fp32_mfma.restype = ctypes.c_int
+    lib.slhc_probe_bf16_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp, sz, vp]
+    lib.slhc_probe_bf16_mfma.restype = ctypes.c_int
     lib.slhc_probe_panel_loop.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     lib.slhc_probe_panel_loop.restype = ctypes.c_int
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
@@ -129,7 +132,7 @@ def slhc_workspace_bytes(N, d, k):
     return out.value
 
 
-def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32_filter=False):
+def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32_filter=False, panel_order=False):
     """slhc_knn_graph (prune=False) / slhc_knn_graph_opt with SLHC_PRUNE: returns (idx int32 [N,k],
     dist float32 [N,k]) device tensors.  Asynchronous on the current stream."""
     X = _device_matrix(X)
@@ -145,7 +148,7 @@ def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32
     _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream(),
                                   (SLHC_PRUNE if prune else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
-                                  (SLHC_FP32_FILTER if fp32_filter else 0)))
+                                  (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0)))
     return idx, dist
 
 
@@ -157,6 +160,14 @@ def knn_graph_static(X, k, out):
     idx, dist = out
     _check(load_library().slhc_knn_graph_static(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(), _stream()))
     return idx, dist
+
+
+def probe_bf16_mfma(device="cuda"):
+    """slhc_probe_bf16_mfma: TFLOP/s a register-only v_mfma_f32_32x32x16_bf16 loop sustains on the current device."""
+    ws = _workspace(256, device)
+    out = ctypes.c_double(0.0)
+    _check(load_library().slhc_probe_bf16_mfma(ctypes.byref(out), ws.data_ptr(), ws.numel(), _stream()))
+    return out.value
 
 
 def probe_fp32_mfma(device="cuda"):
@@ -201,7 +212,7 @@ def cross_1nn(X, colour, rows=None, m=None):
 
 
 def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False, tile_table=True,
-         fp32_filter=False):
+         fp32_filter=False, panel_order=False):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
@@ -235,7 +246,7 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
                                  workspace.numel(), _stream(),
                                  (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
                                  (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
-                                 (SLHC_FP32_FILTER if fp32_filter else 0)))
+                                 (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

@@ -273,6 +273,8 @@ struct KnnWs {
     // every-tile sweeps on the bf16 MFMA: X split into bfloat16 halves (see SweepParams::Xq_split) and the half
     // norms with the slack that goes with it; nullptr when d does not allow it
     float* Xsplit; float* hn_split;
+    // scratch of the every-tile sweeps that go range by range (see SweepParams::carry_ws): 2 + panels words
+    unsigned int* carry_ws; long long carry_ws_words;
     bool split_ready = false;        // filled in this call
     bool order_split_ready = false;  // likewise the split copy of the reordered rows
     size_t bytes;
@@ -298,6 +300,8 @@ struct KnnWs {
                 part_dist = c.take<float>((size_t)part_rows * k);
             }
         }
+        carry_ws_words = 2 + (long long)((N + 127) / 128);
+        carry_ws = c.take<unsigned int>((size_t)carry_ws_words);
         has_order = with_order && prunable(N, d);
         if (has_order) order.carve(c, N, d);
         bytes = c.off;
@@ -600,6 +604,10 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     } else {
         p.Xq = p.Xc = X; p.hq = p.hc = ws.hn; p.NQ = p.NC = (int)N;
         p.part_idx = ws.part_idx; p.part_dist = ws.part_dist; p.part_rows = ws.part_rows;
+        if (!(flags & SLHC_PANEL_ORDER)) {
+            p.carry_ws = ws.carry_ws; p.carry_ws_words = ws.carry_ws_words;
+            p.carry_fault = reinterpret_cast<unsigned int*>(ws.counters + 4);
+        }
         if (ws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
             HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, stream));
             HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
@@ -839,6 +847,27 @@ int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes
         HIP_TRY(slhc::launch_mfma_probe(2000, static_cast<float*>(workspace), s, &flop));      // warm-up: clocks settle
         HIP_TRY(hipEventRecord(ev.a, s));
         HIP_TRY(slhc::launch_mfma_probe(40000, static_cast<float*>(workspace), s, &flop));     // ~40 ms
+        HIP_TRY(hipEventRecord(ev.b, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        const float ms = ev.ms();
+        if (!(ms > 0.f)) { set_err("probe timing failed"); return SLHC_HIP_ERROR; }
+        *tflops = flop / (ms * 1e-3) / 1e12;
+        return SLHC_OK;
+    });
+}
+
+int slhc_probe_bf16_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return guarded([&]() -> int {
+        if (!tflops || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (workspace_bytes < 256) { set_err("workspace %zu < 256 bytes", workspace_bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        EventPair ev;
+        HIP_TRY(ev.create());
+        double flop = 0.0;
+        HIP_TRY(slhc::launch_mfma_bf16_probe(2000, static_cast<float*>(workspace), s, &flop));     // warm-up: clocks settle
+        HIP_TRY(hipEventRecord(ev.a, s));
+        HIP_TRY(slhc::launch_mfma_bf16_probe(80000, static_cast<float*>(workspace), s, &flop));    // ~40 ms
         HIP_TRY(hipEventRecord(ev.b, s));
         HIP_TRY(hipStreamSynchronize(s));
         const float ms = ev.ms();
@@ -1193,6 +1222,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     unsigned long long* h_surv = static_cast<unsigned long long*>(pin_surv.p);
     HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if ((h_surv[4] & 2ull) != 0) { set_err("a work item of the k-NN sweep waited for its predecessor in vain"); return SLHC_INTERNAL; }
     if ((h_surv[4] & 0xffffffffull) != 0) { set_err("a row of X is not finite (NaN, infinity, or a squared norm beyond float32)"); return SLHC_NONFINITE; }
     st.knn_filter_survivors = (int64_t)h_surv[0];
     st.knn_tile_steps = (int64_t)h_surv[2];
@@ -1376,6 +1406,10 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     p.Xq = p.Xc = X; p.hq = p.hc = kws.hn; p.NQ = p.NC = (int)N;
                     p.qcolour = p.ccolour = ws.colour;
                     p.rows = rows;
+                    if (!(flags & SLHC_PANEL_ORDER)) {
+                        p.carry_ws = kws.carry_ws; p.carry_ws_words = kws.carry_ws_words;
+                        p.carry_fault = reinterpret_cast<unsigned int*>(kws.counters + 4);
+                    }
                     if (kws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
                         if (!kws.split_ready) {          // (a pruned k-NN sweep did not need it)
                             HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, kws.Xsplit, s));
@@ -1507,8 +1541,9 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
         rc = enqueue_scan();                                  // next round's scan; its counters are read at the top
         if (rc != SLHC_OK) return rc;
     }
-    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 4 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_surv, kws.counters, 5 * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if ((h_surv[4] & 2ull) != 0) { set_err("a work item of a connection sweep waited for its predecessor in vain"); return SLHC_INTERNAL; }
 #ifdef SLHC_PHASE_TIMERS
     if (log.on) {
         unsigned long long* h_ph = h_surv + 4;           // 64-byte staging buffer: not enough, use two copies

@@ -93,6 +93,16 @@ struct SweepParams {
     int32_t* part_idx;
     float* part_dist;
     long long part_rows;
+    // Every-tile sweeps of many panels (sweep_kernel_qreg; the launcher decides and sets carry_ranges): the work
+    // items are (range of candidate tiles, panel), handed out range by range so that all workgroups sweep the
+    // same few megabytes of candidates at a time, and a panel's lists travel from range to range through
+    // out_idx / out_dist.  carry_ws: scratch of 2 + (panels) words (hand-out counter, spare, ranges finished
+    // per panel), cleared by the launcher; nullptr: never.  carry_fault (optional device word): bit 1 is set if
+    // a work item's wait for its predecessor ever runs out (never seen; the results are then not valid).
+    unsigned int* carry_ws;
+    long long carry_ws_words;
+    int carry_ranges;
+    unsigned int* carry_fault;
     unsigned long long* survivors;   // optional device counter: pairs that passed the filter
     unsigned long long* tiles_done;  // optional device counter: (panel, tile) steps multiplied
 #ifdef SLHC_PHASE_TIMERS
@@ -113,6 +123,8 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
 // Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
 // *flop receives the floating-point operations of the launch.  `sink`: one device float.
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);
+// the same with v_mfma_f32_32x32x16_bf16, the multiply of the split-product sweeps
+hipError_t launch_mfma_bf16_probe(int iters, float* sink, hipStream_t stream, double* flop);
 // The multiplies of launch_mfma_probe with the panel loop's ingredients added (steps 0..3, see the kernel);
 // `stream_rows`: [rows, 128] floats to stream from (steps >= 2; rows a power of two), iters chunks of 64 multiplies.
 hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int rows, float* sink, hipStream_t stream,

@@ -35,6 +35,10 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+#ifndef SLHC_SPLIT_FRAGS
+#define SLHC_SPLIT_FRAGS 2      // 2: the LDS reads of a whole chunk go ahead of its multiplies; 1: those of half a chunk
+#endif
+
 constexpr int WG_THREADS = 256;
 constexpr int BM = 128;            // query rows per workgroup (32 per wavefront)
 constexpr int BN = 128;            // candidate rows per tile
@@ -945,19 +949,32 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     const int nparts = (CAN_SPLIT && aligned && p.segments > 1 && p.out_key != nullptr) ? p.segments
                      : (CAN_RANGE && p.segments > 1 && p.part_idx != nullptr && p.part_dist != nullptr) ? p.segments : 1;
     const bool listed_panels = PRUNE && MASKED && aligned && p.panel_list != nullptr;
-    const int nitems = (listed_panels ? p.panel_list_n : npanels) * nparts;
+    // Every-tile sweeps of many panels, range by range (p.carry_ranges, set by the launcher): the candidate tiles
+    // are cut into ranges of a few megabytes and the work items (range, panel) are handed out in that order, so
+    // that all workgroups in flight sweep the same range and its tiles are served by the L2 of every XCD instead
+    // of being fetched from memory once per panel.  A panel's lists travel from range to range through the
+    // output arrays: item (r, panel) starts from what item (r - 1, panel) wrote, thresholds included, so no
+    // list is filled twice.  Item (r - 1, panel) was handed out a whole round of panels earlier and has long
+    // finished; carry_ws[2 + panel] counts the ranges written, and an item waits for its predecessor there (the
+    // workgroup that took the predecessor is running and waits only for still earlier items, so every wait
+    // ends; it is bounded all the same, and a wait that runs out is reported in carry_fault).
+    constexpr bool CAN_CARRY = !PRUNE;
+    const int ncarry = (CAN_CARRY && p.carry_ranges > 1 && p.carry_ws != nullptr) ? p.carry_ranges : 1;
+    const int nitems = ncarry > 1 ? npanels * ncarry : (listed_panels ? p.panel_list_n : npanels) * nparts;
+    unsigned int* hand_out = ncarry > 1 ? p.carry_ws : (PRUNE ? p.panel_counter : nullptr);
     for (int item = blockIdx.x;; item += gridDim.x) {
         __syncthreads();          // previous panel fully written out before its state is reused
-        if (PRUNE && p.panel_counter) {
+        if (hand_out) {
             // work items are handed out one by one: with pruning their cost differs by orders of
             // magnitude.  The counter only grows, so every workgroup reaches nitems and leaves.
-            if (tid == 0) *next_panel = (int)atomicAdd(p.panel_counter, 1u);
+            if (tid == 0) *next_panel = (int)atomicAdd(hand_out, 1u);
             __syncthreads();
             item = *next_panel;
         }
         if (item >= nitems) break;
-        const int panel_at = nparts > 1 ? item / nparts : item;
-        const int part = nparts > 1 ? item - panel_at * nparts : 0;
+        const int crange = ncarry > 1 ? item / npanels : 0;
+        const int panel_at = ncarry > 1 ? item - crange * npanels : (nparts > 1 ? item / nparts : item);
+        const int part = (ncarry == 1 && nparts > 1) ? item - panel_at * nparts : 0;
         const int panel = listed_panels ? p.panel_list[panel_at] : panel_at;
         if ((unsigned int)panel >= (unsigned int)npanels) continue;          // never trust a list entry as an index
 #ifdef SLHC_STUDY_PANEL_STEPS
@@ -995,6 +1012,34 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
         // a panel without a single query has nothing to do (every wavefront reads the same qid)
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
+        if (CAN_CARRY && crange > 0) {
+            // the lists item (crange - 1, panel) left in the output arrays, and the thresholds they imply
+            if (tid == 0) {
+                int spins = 0;
+                while (__hip_atomic_load(p.carry_ws + 2 + panel, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (unsigned int)crange) {
+                    __builtin_amdgcn_s_sleep(16);
+                    if (++spins > (1 << 22)) { if (p.carry_fault) atomicOr(p.carry_fault, 2u); break; }
+                }
+            }
+            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            for (int i = tid; i < BM * KL; i += WG_THREADS) {
+                const int ql = i / KL, j = i - ql * KL;
+                const int row = qid[ql];
+                if (row >= 0 && j < k) {
+                    const size_t o = MASKED ? (size_t)(panel * BM + ql)
+                                            : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + j;
+                    const int idx = ((global_ints)p.out_idx)[o];
+                    if (idx >= 0) lists[i] = make_key(((global_floats)p.out_dist)[o], idx);
+                }
+            }
+            __syncthreads();
+            if (tid < BM && qid[tid] >= 0) {
+                const unsigned long long worst = lists[(size_t)tid * KL + k - 1];
+                if (worst != LIST_SENTINEL) bounds[tid] = hqs[tid] - 0.5f * __uint_as_float((unsigned int)(worst >> 32));
+            }
+            __syncthreads();
+        }
         PHASE_MARK(0);
 
         int panel_colour = -2;       // the colour all queries of the panel share (-2: they differ / unknown)
@@ -1166,9 +1211,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         const int with_centre = own_tile >= 0 ? 0 : 1;        // the scan itself begins at the centre tile
         const int nscan_all = own_tile >= 0 ? ntiles - 1 : ntiles;
         // positions of this work item: part, part + nparts, ... of the panel's scan order
-        const int range_begin = (CAN_RANGE && nparts > 1) ? (int)((long long)part * ntiles / nparts) : 0;
-        const int range_end = (CAN_RANGE && nparts > 1) ? (int)((long long)(part + 1) * ntiles / nparts) : ntiles;
-        const int nscan = (CAN_RANGE && nparts > 1) ? range_end - range_begin
+        const bool ranged = (CAN_RANGE && nparts > 1) || (CAN_CARRY && ncarry > 1);
+        const int range_at = ncarry > 1 ? crange : part, range_count = ncarry > 1 ? ncarry : nparts;
+        const int range_begin = ranged ? (int)((long long)range_at * ntiles / range_count) : 0;
+        const int range_end = ranged ? (int)((long long)(range_at + 1) * ntiles / range_count) : ntiles;
+        const int nscan = ranged ? range_end - range_begin
                         : nparts > 1 ? (nscan_all > part ? (nscan_all - part + nparts - 1) / nparts : 0) : nscan_all;
         const int side_r = ntiles - 1 - centre, side_l = centre;
         const int side_min = side_r < side_l ? side_r : side_l;
@@ -1341,16 +1388,46 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     }
                 }
                 if (SPLIT) {
-                    // x_c . x_q ~ hi_c hi_q + hi_c lo_q + lo_c hi_q, 16 columns per instruction
+                    // x_c . x_q ~ hi_c hi_q + hi_c lo_q + lo_c hi_q, 16 columns per instruction.
+                    // All LDS reads of a group of multiplies are issued before the first of them, into registers of
+                    // their own, and a scheduling fence keeps them there: left to itself the scheduler saves
+                    // registers by reading each fragment just before the multiply that needs it, which exposes
+                    // one LDS round trip per multiply or two (the sweep then runs at the speed of the LDS latency,
+                    // not of either pipe).
+#if SLHC_SPLIT_FRAGS == 2
+                    v8bf ch[2][4], cl[2][4];
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            ch[s2][b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf)));
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            cl[s2][b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf) + 16));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        const v8bf qh = __builtin_bit_cast(v8bf, qf[chunk * 4 + s2]);
+                        const v8bf ql = __builtin_bit_cast(v8bf, qf[chunk * 4 + 2 + s2]);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[s2][b], qh, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[s2][b], ql, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[s2][b], qh, acc[b], 0, 0, 0);
+                    }
+#else
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
                         v8bf ch[4], cl[4];
 #pragma unroll
-                        for (int b = 0; b < 4; ++b) {
-                            const float* at = Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf);
-                            ch[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(at));
-                            cl[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(at + 16));
-                        }
+                        for (int b = 0; b < 4; ++b)
+                            ch[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf)));
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            cl[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf) + 16));
+                        __builtin_amdgcn_sched_barrier(0);
                         const v8bf qh = __builtin_bit_cast(v8bf, qf[chunk * 4 + s2]);
                         const v8bf ql = __builtin_bit_cast(v8bf, qf[chunk * 4 + 2 + s2]);
 #pragma unroll
@@ -1359,7 +1436,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                         for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], ql, acc[b], 0, 0, 0);
 #pragma unroll
                         for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], qh, acc[b], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+#endif
                 } else {
 #pragma unroll
                 for (int kk = 0; kk < KC / 8; ++kk) {
@@ -1386,7 +1465,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
 
             // ---- first tile of a 1-NN panel: seed the thresholds (see seed_block) ----
-            if (k == 1 && step == 0) {
+            if (k == 1 && step == 0 && crange == 0) {
                 const int seed_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
                 SeedPick pick{-__builtin_inff(), -1};
                 pick = seed_block<KL, MASKED>(acc[0], 0, pick, seed_tag, col0, tpar, N);
@@ -1448,7 +1527,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     // First tile of a k-NN panel (k > 1): fill the lists from its best candidates (see
                     // seed_range).  Later tiles were tried too and gain nothing: what passes there are
                     // mostly real list updates.
-                    if (!MASKED && k > 1 && step == 0) {
+                    if (!MASKED && k > 1 && step == 0 && crange == 0) {
                         SeedRange range{__builtin_inff(), -__builtin_inff()};
                         range = seed_range(acc[0], range);
                         range = seed_range(acc[1], range);
@@ -1637,6 +1716,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 }
             }
         }
+        if (CAN_CARRY && ncarry > 1) {
+            // the lists of this range are written: let item (crange + 1, panel) start from them
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
+            if (tid == 0) __hip_atomic_store(p.carry_ws + 2 + panel, (unsigned int)(crange + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
         PHASE_MARK(7);
     }
 #ifdef SLHC_PHASE_TIMERS
@@ -1687,6 +1772,43 @@ __global__ void __launch_bounds__(WG_THREADS, 2) mfma_probe_kernel(int iters, fl
 #pragma unroll
         for (int r = 0; r < 16; ++r) total += acc[b][r];
     if (total == 123456.789f) sink[0] = total;          // keeps the chain alive; practically never taken
+}
+
+// The same for the multiply of the split-product sweeps, v_mfma_f32_32x32x16_bf16.
+__global__ void __launch_bounds__(WG_THREADS, 2) mfma_bf16_probe_kernel(int iters, float seed, float* __restrict__ sink)
+{
+    v16f acc[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+    v8bf a, c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(seed + (float)((threadIdx.x + e) & 7) * 0.125f); c[e] = (__bf16)(seed * 0.5f); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, c, acc[b], 0, 0, 0);
+        }
+    }
+    float total = 0.f;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) total += acc[b][r];
+    if (total == 123456.789f) sink[0] = total;
+}
+
+hipError_t launch_mfma_bf16_probe(int iters, float* sink, hipStream_t stream, double* flop)
+{
+    int cus = 0;
+    hipError_t e = device_cus(&cus);
+    if (e != hipSuccess) return e;
+    const int grid = 2 * cus;
+    hipLaunchKernelGGL(mfma_bf16_probe_kernel, dim3(grid), dim3(WG_THREADS), 0, stream, iters, 1.0f, sink);
+    *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+    return hipGetLastError();
 }
 
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop)
@@ -1899,9 +2021,30 @@ static hipError_t launch_with_lds(K kernel, int grid, size_t lds, const SweepPar
     return hipGetLastError();
 }
 
-template <int KL, bool MASKED>
-static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
+__global__ void __launch_bounds__(256) zero_words_kernel(unsigned int* __restrict__ w, long long n)
 {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) w[i] = 0u;
+}
+
+#ifndef SLHC_CARRY_RANGE_BYTES
+#define SLHC_CARRY_RANGE_BYTES (32 << 20)
+#endif
+#ifndef SLHC_CARRY_MIN_ROUNDS
+#define SLHC_CARRY_MIN_ROUNDS 4
+#endif
+// candidate bytes per range of a sweep that goes range by range: half of an XCD's 4 MiB L2, so that the range
+// the workgroups are in and the one the first of them move on to both fit
+constexpr long long CARRY_RANGE_BYTES = SLHC_CARRY_RANGE_BYTES;
+// ... and only with at least this many panels per workgroup slot: a panel's item in range r + 1 is handed out
+// that many rounds of items after its item in range r, which therefore has finished by then
+constexpr int CARRY_MIN_ROUNDS = SLHC_CARRY_MIN_ROUNDS;
+
+template <int KL, bool MASKED>
+static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
+{
+    SweepParams p = p_in;
+    p.carry_ranges = 0;
     int cus = 0;
     hipError_t e = device_cus(&cus);
     if (e != hipSuccess) return e;
@@ -1937,6 +2080,22 @@ static hipError_t launch_sweep_t(const SweepParams& p, hipStream_t stream)
             return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, true>, grid, lds, p, stream);
         }
         if (p.qslot || p.tile_colour || p.panel_counter || p.own_tile_first) return hipErrorInvalidValue;
+        if (p.carry_ws && p.segments <= 1 && npanels >= (long long)CARRY_MIN_ROUNDS * cus * per_cu &&
+            p.carry_ws_words >= 2 + (long long)npanels) {
+            const int ntiles = (p.NC + BN - 1) / BN;
+            long long per_range = CARRY_RANGE_BYTES / ((long long)BN * p.d * 4);
+            if (per_range < 4) per_range = 4;
+            long long ranges = (ntiles + per_range - 1) / per_range;
+            while (ranges * npanels >= (1LL << 30)) ranges = (ranges + 1) / 2;       // work items are counted in an int
+            if (ranges >= 2) {
+                p.carry_ranges = (int)ranges;
+                const long long words = 2 + (long long)npanels;
+                hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned int)((words + 255) / 256)), dim3(256), 0, stream, p.carry_ws, words);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                grid = cus * per_cu;
+            }
+        }
         if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= 2 &&
             (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
             if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, false, true>, grid, lds, p, stream);

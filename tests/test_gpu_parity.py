@@ -865,6 +865,31 @@ def test_c5_full_size_pruned_equals_every_tile(lib):
     check_tree_properties(X, k, gi, b, np.random.default_rng(57))
 
 
+# ----------------------------------------------------------------------------- sweeps range by range
+@pytest.mark.parametrize("N,d,k", [(270_000, 64, 8), (263_000, 32, 5), (300_001, 128, 33), (262_144, 96, 1)])
+def test_range_order_equals_panel_order(lib, N, d, k):
+    """Every-tile k-NN sweeps of at least four panels per workgroup slot hand out their work range by range and
+    carry a panel's lists from range to range through the output arrays; the lists must equal those of the
+    sweep that takes one panel at a time (split and float32 products), and sampled rows must equal the oracle's."""
+    rng = np.random.default_rng(N + d)
+    centres = rng.uniform(-20, 20, size=(200, d))
+    X = (centres[rng.integers(0, 200, size=N)] + rng.standard_normal((N, d))).astype(np.float32)
+    X[rng.integers(0, N, size=500)] = X[rng.integers(0, N, size=500)]          # some exact copies
+    Xd = torch.from_numpy(X).cuda()
+    print("range order", N, d, k, flush=True)
+    a = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    for fp32 in (False, True):
+        b = lib.knn_graph(Xd, k, panel_order=True, fp32_filter=fp32)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    c = lib.knn_graph(Xd, k, fp32_filter=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+    rows = rng.choice(N, size=96, replace=False)
+    check_knn(X, k, a[0].cpu().numpy()[rows], a[1].cpu().numpy()[rows], rows=rows, min_exact=0.99)
+
+
 # ----------------------------------------------------------------------------- full size (headline)
 def test_headline_full_size_properties(lib):
     """c3 at its full size (1M x 128, k=32), in the launch configuration bench.py times.  The
@@ -894,12 +919,22 @@ def test_headline_full_size_properties(lib):
     torch.cuda.synchronize()
     assert torch.equal(idx, idx_p) and torch.equal(dist, dist_p)
     del idx_p, dist_p
+    print("headline: knn panel by panel, split and float32 products", flush=True)   # (the default goes range by range)
+    for fp32 in (False, True):
+        idx_p, dist_p = lib.knn_graph(Xd, k, panel_order=True, fp32_filter=fp32)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx_p) and torch.equal(dist, dist_p)
+        del idx_p, dist_p
 
     print("headline: slhc", flush=True)
     out = lib.slhc(Xd, k)                      # with tile pruning (the default)
     print("stats", out["stats"], flush=True)
     brute = lib.slhc(Xd, k, prune=False)       # every tile multiplied: what bench.py's roofline step times
     print("stats (every tile)", brute["stats"], flush=True)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(out[name_], brute[name_]), name_
+    del brute
+    brute = lib.slhc(Xd, k, prune=False, panel_order=True)     # connection sweeps panel by panel as well
     for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
         assert torch.equal(out[name_], brute[name_]), name_
     del brute

@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported(cdll):
 
 
 def test_version_and_strings(cdll):
-    assert cdll.slhc_abi_version() == 3
+    assert cdll.slhc_abi_version() == 4
     assert cdll.slhc_strerror(0) == b"ok"
     assert cdll.slhc_strerror(3) == b"workspace too small"
     assert cdll.slhc_strerror(5) == b"input not finite"
@@ -54,7 +54,7 @@ def test_status_numbering_matches_the_header():
     assert values == {"SLHC_OK": "0", "SLHC_INVALID_ARG": "1", "SLHC_UNSUPPORTED": "2",
                       "SLHC_WORKSPACE_TOO_SMALL": "3", "SLHC_HIP_ERROR": "4", "SLHC_NONFINITE": "5",
                       "SLHC_INTERNAL": "6", "SLHC_HOST_MEMORY": "7"}
-    assert re.search(r"#define SLHC_ABI_VERSION 3\b", text)
+    assert re.search(r"#define SLHC_ABI_VERSION 4\b", text)
     assert re.search(r"#define SLHC_PRUNE 1u", text) and re.search(r"#define SLHC_SPLIT_ROUNDS 2u", text) and re.search(r"#define SLHC_SPLIT_SCANS 4u", text) and re.search(r"#define SLHC_NO_TILE_TABLE 8u", text) and re.search(r"#define SLHC_AUTO_PRUNE_MIN_ROWS 24576", text) and re.search(r"#define SLHC_FP32_FILTER 16u", text)
 
 
