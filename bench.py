@@ -89,13 +89,16 @@ def main():
         names = ["operands in registers", "+ barrier per chunk, A operands from LDS",
                  "+ next chunk: global loads, LDS stores", "+ filter compares per tile",
                  "as 2, chunk loaded straight into LDS", "as 3, chunk loaded straight into LDS",
-                 "as 2, unequal wavefront priorities", "as 3, unequal wavefront priorities"]
+                 "as 2, unequal wavefront priorities", "as 3, unequal wavefront priorities",
+                 "bf16 multiplies of the split-product sweeps (v_mfma_f32_32x32x16_bf16), operands in registers",
+                 "bf16: + barrier per chunk of 24 multiplies, hi and lo fragments from LDS",
+                 "bf16: + next chunk: global loads, LDS stores", "bf16: + filter compares per tile"]
         out_rows = []
         for rep in range(2):                                                    # second pass reported
-            out_rows = [{"steps": st, "what": names[st], "tflops": slhc.probe_panel_loop(st, ws_probe)} for st in range(8)]
+            out_rows = [{"steps": st, "what": names[st], "tflops": slhc.probe_panel_loop(st, ws_probe)} for st in range(12)]
         for r in out_rows:
-            r["frac_of_peak"] = r["tflops"] / PEAK_FP32_MFMA_TFLOPS
-        print(json.dumps({"loop_study": out_rows, "peak": PEAK_FP32_MFMA_TFLOPS}))
+            r["frac_of_peak"] = r["tflops"] / (PEAK_BF16_MFMA_TFLOPS if r["steps"] >= 8 else PEAK_FP32_MFMA_TFLOPS)
+        print(json.dumps({"loop_study": out_rows, "peak": PEAK_FP32_MFMA_TFLOPS, "peak_bf16": PEAK_BF16_MFMA_TFLOPS}))
         return
 
     t0 = time.time()

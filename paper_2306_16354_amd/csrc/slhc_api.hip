@@ -881,7 +881,7 @@ int slhc_probe_panel_loop(int32_t steps, double* tflops, void* workspace, size_t
 {
     return guarded([&]() -> int {
         if (!tflops || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
-        if (steps < 0 || steps > 7) { set_err("steps must be 0..7 (steps=%d)", steps); return SLHC_INVALID_ARG; }
+        if (steps < 0 || steps > 11) { set_err("steps must be 0..11 (steps=%d)", steps); return SLHC_INVALID_ARG; }
         // a sink word, then the rows to stream from: the largest power of two of 512-byte rows that fits
         if (workspace_bytes < 256 + 512 * 256) { set_err("workspace %zu < %d bytes", workspace_bytes, 256 + 512 * 256); return SLHC_WORKSPACE_TOO_SMALL; }
         int rows = 256;

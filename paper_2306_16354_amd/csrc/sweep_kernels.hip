@@ -1828,7 +1828,7 @@ hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double*
 // loaded from `stream` (rows of 128 floats, `rows` a power of two) into registers and stored to LDS, double
 // buffered as in the sweep; 3 = also 16 compares and a ballot per accumulator block after every fourth
 // chunk.  Nothing it computes means anything.
-template <int STEPS, bool DIRECT, bool ASYM = false>
+template <int STEPS, bool DIRECT, bool ASYM = false, bool BF16 = false>
 __global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, const float* __restrict__ stream,
                                                                    int rows, float* __restrict__ sink)
 {
@@ -1888,6 +1888,30 @@ __global__ void __launch_bounds__(WG_THREADS, 2) loop_probe_kernel(int iters, co
             stage((it & 1) ? buf0 : buf1, ((it + 1) & 3) * KC + ld_col);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (BF16) {
+            // the multiplies of the split-product sweeps: 16 LDS reads (hi and lo fragments), 24 bf16 multiplies
+            v8bf ch[2][4], cl[2][4];
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    ch[s2][b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDR + 4 * (2 * s2 + lhalf)));
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    cl[s2][b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cb + (b * 32 + l32) * LDR + 4 * (2 * s2 + lhalf) + 16));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const v8bf qh = __builtin_bit_cast(v8bf, q[s2]), ql = __builtin_bit_cast(v8bf, q[2 + s2]);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[s2][b], qh, acc[b], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[s2][b], ql, acc[b], 0, 0, 0);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[s2][b], qh, acc[b], 0, 0, 0);
+            }
+        } else
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             v4f cf[4];
@@ -1927,6 +1951,7 @@ hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int
                              double* flop)
 {
     if (steps <= 0) return launch_mfma_probe(iters * 4, sink, stream, flop);     // 16 multiplies per iteration there
+    if (steps == 8) return launch_mfma_bf16_probe(iters * 2, sink, stream, flop);
     int cus = 0;
     hipError_t e = device_cus(&cus);
     if (e != hipSuccess) return e;
@@ -1938,6 +1963,12 @@ hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(WG_THREADS), lds, stream, iters, stream_rows, rows, sink);
         return hipGetLastError();
     };
+    if (steps >= 9) {          // 9..11: steps 1..3 with the 24 bf16 multiplies of a split-product chunk
+        *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 24.0 * (2.0 * 32 * 32 * 16);
+        if (steps == 9) return run(&loop_probe_kernel<1, false, false, true>);
+        if (steps == 10) return run(&loop_probe_kernel<2, false, false, true>);
+        return run(&loop_probe_kernel<3, false, false, true>);
+    }
     *flop = (double)grid * (WG_THREADS / 64) * (double)iters * 64.0 * (2.0 * 32 * 32 * 2);
     if (steps == 1) return run(&loop_probe_kernel<1, false>);
     if (steps == 2) return run(&loop_probe_kernel<2, false>);
