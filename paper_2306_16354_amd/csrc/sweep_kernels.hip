@@ -11,9 +11,16 @@
 //   * a workgroup (4 wavefronts) owns a panel of 128 query rows and sweeps all N candidate rows
 //     in tiles of 128; workgroups are persistent and all sweep the candidates in the same order,
 //     but they drift out of step, so most of a panel's candidate stream misses the XCD's L2
-//     (measured at 1M x 128: about 10 % hits, 3.5 TB through the fabric per launch); the
-//     stream runs at a fifth of the HBM peak and stays hidden behind the MFMA work;
-//   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32.  Candidates are the A
+//     (measured at 1M x 128: 10-17 % hits, 3.5-4.4 TB through the fabric per launch).  With
+//     float32 products that stream runs at a fifth of the HBM peak behind the MFMA work; with
+//     split bfloat16 products (below) the multiplies of a chunk are six times shorter than a
+//     load takes, and the sweep waits for its loads.  Launches of many panels go range by range
+//     (SweepParams::carry_ws): all workgroups sweep the same 32 MiB of candidates at a time, which
+//     the memory-side cache then serves, and a panel's lists travel from range to range;
+//   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32, or, from 64 to 128 features,
+//     from split bfloat16 halves as hi_c hi_q + hi_c lo_q + lo_c hi_q with
+//     v_mfma_f32_32x32x16_bf16 (16 times the rate; the filter's slack covers the dropped terms, and
+//     only the filter sees these products).  Candidates are the A
 //     operand and queries the B operand, so a lane's 16 accumulators of a 32x32 block belong to
 //     ONE query: the query's threshold is a per-lane scalar;
 //   * the accumulator starts at -h_c with h = (1-c)/2 * ||x||^2, so after the K loop it holds
@@ -1022,15 +1029,18 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 }
             }
             __syncthreads();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            // (thread 0's acquire has invalidated this CU's L1; the lists are read past it all the same)
             for (int i = tid; i < BM * KL; i += WG_THREADS) {
                 const int ql = i / KL, j = i - ql * KL;
                 const int row = qid[ql];
                 if (row >= 0 && j < k) {
                     const size_t o = MASKED ? (size_t)(panel * BM + ql)
                                             : (size_t)(p.q_out_row ? p.q_out_row[row] : row) * k + j;
-                    const int idx = ((global_ints)p.out_idx)[o];
-                    if (idx >= 0) lists[i] = make_key(((global_floats)p.out_dist)[o], idx);
+                    const int idx = (int)__hip_atomic_load(reinterpret_cast<const unsigned int*>(p.out_idx) + o, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                    const unsigned int dbits = __hip_atomic_load(reinterpret_cast<const unsigned int*>(p.out_dist) + o,
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (idx >= 0) lists[i] = ((unsigned long long)dbits << 32) | (unsigned int)idx;
                 }
             }
             __syncthreads();
@@ -1717,8 +1727,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
         }
         if (CAN_CARRY && ncarry > 1) {
-            // the lists of this range are written: let item (crange + 1, panel) start from them
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            // the lists of this range are written: let item (crange + 1, panel) start from them.  Every thread
+            // waits for its own stores to be acknowledged (workgroup-scope release), the barrier collects that, and
+            // one thread alone makes them visible to the other XCDs and raises the word (an agent-scope release
+            // in every thread would have each of them write back the L2).
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __syncthreads();
             if (tid == 0) __hip_atomic_store(p.carry_ws + 2 + panel, (unsigned int)(crange + 1), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
