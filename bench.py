@@ -148,7 +148,7 @@ def main():
     # default) split bfloat16 halves hi*hi + hi*lo + lo*hi on the bf16 MFMA.  Either way every pair that can
     # enter a list is re-evaluated in float32, so the outputs are the same bits.
     split = (not args.knn_only and bool(stats[-1].get("split_products", 0))) or \
-            (args.knn_only and d % 32 == 0 and 64 <= d <= 128)
+            (args.knn_only and ((d % 32 == 0 and 64 <= d <= 128) or (d > 128 and d % 4 == 0)))
     peak_tflops = PEAK_BF16_MFMA_TFLOPS if split else PEAK_FP32_MFMA_TFLOPS
     # the float32-product variant of the same sweep, once, outside the timed region (the kernel earlier
     # reports quote)

@@ -116,9 +116,10 @@ typedef struct slhc_stats {
                            they do for row orders of more than 32768 tiles, instead of reading them
                            from the table of all tile pairs.  Same outputs.                     */
 #define SLHC_FP32_FILTER 16u   /* The every-tile sweeps accumulate their tile products in float32 (fp32 MFMA),
-                           as they always do below 64 features or when d is not a multiple of 32,
-                           instead of in split bfloat16 halves (bf16 MFMA, 16 times the rate), which
-                           is the default from 64 to 128 features.  Only the filter differs: every
+                           as they always do below 64 features and up to 128 when d is not a multiple of
+                           32, instead of in split bfloat16 halves (bf16 MFMA, 16 times the rate), which
+                           is the default from 64 to 128 features (multiples of 32) and beyond 128
+                           (multiples of 4).  Only the filter differs: every
                            pair that may enter a list is re-evaluated in float32 either way, so the
                            outputs are the same bit for bit.                                     */
 

@@ -211,7 +211,9 @@ int64_t padded_rows_limit(int64_t N) { return N + N / 2 + 256; }
 size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 
 // tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
-bool split_products_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <= 128; }
+// (in the register-resident-query kernel); beyond 128 features the streaming kernel takes any multiple of 4 columns,
+// its split copy padded to whole chunks
+bool split_products_ok(int32_t d) { return (d % 32 == 0 && d >= 64 && d <= 128) || (d > 128 && d % 4 == 0); }
 
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {
@@ -286,7 +288,7 @@ struct KnnWs {
         part_idx = nullptr; part_dist = nullptr; part_rows = 0;
         Xsplit = nullptr; hn_split = nullptr;
         if (split_products_ok(d) && k > 0) {
-            Xsplit = c.take<float>((size_t)N * d);
+            Xsplit = c.take<float>((size_t)N * (size_t)slhc::split_row_stride(d));
             hn_split = c.take<float>((size_t)N);
         }
         {

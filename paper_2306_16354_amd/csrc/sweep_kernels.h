@@ -14,7 +14,8 @@ struct SweepParams {
     const float* Xc;       // [NC, d] candidate rows
     const float* hc;       // [NC]
     int NQ, NC, d, k;
-    // Optional (sweep_kernel_qreg, d % 32 == 0, d >= 64): the same two matrices with every
+    // Optional (sweep_kernel_qreg: d % 32 == 0, d >= 64; the streaming sweep_kernel: d > 128, d % 4 == 0, rows of
+    // split_row_stride(d) words with zeros past column d): the same two matrices with every
     // value split into two bfloat16 halves, hi = bf16(x) and lo = bf16(x - hi), laid out chunk by chunk: the 32
     // floats of columns 32c .. 32c+31 of a row are replaced by 32 hi values then 32 lo values (launch_split_bf16).
     // The tile products are then accumulated as hi*hi + hi*lo + lo*hi on the bf16 MFMA, which runs at 16 times
@@ -117,6 +118,7 @@ float filter_slack_coefficient(int d);
 float split_slack_coefficient(int d);                 // the same for products accumulated from split bf16 halves
 // X [N, d] -> the chunk-wise split copy described at SweepParams::Xq_split (d % 32 == 0)
 hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream);
+int split_row_stride(int d);                          // words per row of the split copy: d rounded up to whole chunks of 32
 // `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr,
                              bool split_slack = false);

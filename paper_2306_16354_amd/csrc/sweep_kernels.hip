@@ -593,9 +593,10 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
         FINE_MARK(2);                                                                                       \
     } while (0)
 
-template <int KL, bool MASKED, bool VEC4>
+template <int KL, bool MASKED, bool VEC4, bool SPLIT = false>
 __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 {
+    static_assert(!SPLIT || VEC4, "the split copy is read in 16-byte pieces");
     const SweepLds<KL> L(sweep_smem);
     float* Qs = L.Qs; float* Cs = L.Cs; float* hcs = L.hcs; int* ccol = L.ccol;
     float* bounds = L.bounds; int* qid = L.qid; float* hqs = L.hqs;
@@ -620,6 +621,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     unsigned long long* mylists = lists + (size_t)wave * 32 * KL;
     unsigned long long survivors = 0;
     unsigned long long tiles_done = 0;
+    // SPLIT: the chunks are staged from the split bfloat16 copies (see SweepParams::Xq_split), whose rows hold
+    // whole chunks (stride nchunks * 32 words, zeros past column d), and multiplied on the bf16 MFMA; the exact
+    // re-evaluation of the pairs that pass reads Xq / Xc as always.
+    const float* __restrict__ Xq_ld = SPLIT ? p.Xq_split : Xq;
+    const float* __restrict__ Xc_ld = SPLIT ? p.Xc_split : Xc;
+    const int d_ld = SPLIT ? nchunks * KC : d;
 
     // Work item = (query panel, segment of the candidate tiles).  With one segment a workgroup
     // sweeps all candidates for its panel; with few query rows the candidates are split so that
@@ -652,7 +659,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = qid[ld_row + 32 * i];
-            qoff[i] = (unsigned int)(r >= 0 ? r : 0) * (unsigned int)d;
+            qoff[i] = (unsigned int)(r >= 0 ? r : 0) * (unsigned int)d_ld;
         }
         const int my_q_local = wave * 32 + l32;
         const int my_qrow = qid[my_q_local];
@@ -667,7 +674,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
         // offsets that change once per panel (queries) and once per tile (candidates, rows clamped to N - 1), so
         // a chunk costs little address arithmetic.  Only the last chunk can reach past column d: there the dead
         // lanes take the chunk's first quad instead and their values are zeroed when they are staged.
-        const bool last_has_dead = d < nchunks * KC;
+        const bool last_has_dead = !SPLIT && d < nchunks * KC;
         const bool dead_lane = (nchunks - 1) * KC + ld_col >= d;           // in the last chunk
         unsigned int qlo[4], clo[4];
 #pragma unroll
@@ -681,11 +688,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                     for (int i = 0; i < 4; ++i) {
                         int crow = crow0 + 32 * i;
                         crow = crow < N ? crow : N - 1;
-                        clo[i] = (unsigned int)crow * (unsigned int)d + (unsigned int)ld_col;
+                        clo[i] = (unsigned int)crow * (unsigned int)d_ld + (unsigned int)ld_col;
                     }
                 }
-                const float* qb = Xq + chunk * KC;
-                const float* cb = Xc + chunk * KC;
+                const float* qb = Xq_ld + chunk * KC;
+                const float* cb = Xc_ld + chunk * KC;
                 if (chunk == nchunks - 1 && last_has_dead) {
                     const unsigned int back = dead_lane ? (unsigned int)ld_col : 0u;
 #pragma unroll
@@ -779,6 +786,29 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
                         }
                     }
                 }
+                if (SPLIT) {
+                    // x_c . x_q ~ hi_c hi_q + hi_c lo_q + lo_c hi_q, 16 columns per instruction (see sweep_kernel_qreg)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        v8bf ch[4], cl[4];
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            ch[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cs + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf)));
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            cl[b] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Cs + (b * 32 + l32) * LDK + 4 * (2 * s2 + lhalf) + 16));
+                        const v8bf qh = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Qs + my_q_local * LDK + 4 * (2 * s2 + lhalf)));
+                        const v8bf ql = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4f*>(Qs + my_q_local * LDK + 4 * (2 * s2 + lhalf) + 16));
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], qh, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ch[b], ql, acc[b], 0, 0, 0);
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cl[b], qh, acc[b], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else
 #pragma unroll
                 for (int kk = 0; kk < KC / 8; ++kk) {
                     const v4f qf = *reinterpret_cast<const v4f*>(Qs + my_q_local * LDK + kk * 8 + 4 * lhalf);
@@ -2010,18 +2040,21 @@ float split_slack_coefficient(int d)
     return 3.0f * 1.52587890625e-05f + (float)(3 * d + 8) * 1.1920928955078125e-07f;
 }
 
-// one thread per 8 columns: hi = bf16(x), lo = bf16(x - hi), both rounded to nearest even
-__global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ X, long long octets, int d,
+// one thread per 8 columns: hi = bf16(x), lo = bf16(x - hi), both rounded to nearest even.  A row of the split
+// copy holds whole chunks of 32 columns (stride = d rounded up to a multiple of 32 words); columns past d are 0.
+__global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ X, long long octets, int d, int stride,
                                                          float* __restrict__ Xsplit)
 {
     const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
     if (o >= octets) return;
-    const int per_row = d >> 3;
+    const int per_row = stride >> 3;
     const long long row = o / per_row;
     const int oct = (int)(o - row * per_row);              // columns 8 oct .. 8 oct + 7
     const int chunk = oct >> 2, piece = oct & 3;
     const float* src = X + row * d + 8 * oct;
-    const v4f a = *reinterpret_cast<const v4f*>(src), b = *reinterpret_cast<const v4f*>(src + 4);
+    v4f a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    if (8 * oct + 4 <= d) a = *reinterpret_cast<const v4f*>(src);          // d is a multiple of 4
+    if (8 * oct + 8 <= d) b = *reinterpret_cast<const v4f*>(src + 4);
     v8bf hi, lo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -2030,16 +2063,19 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict
         hi[e] = h;
         lo[e] = (__bf16)(x - (float)h);
     }
-    float* dst = Xsplit + row * d + chunk * KC;            // chunk: 16 words of hi, 16 words of lo
+    float* dst = Xsplit + row * stride + chunk * KC;       // chunk: 16 words of hi, 16 words of lo
     *reinterpret_cast<v4f*>(dst + 4 * piece) = __builtin_bit_cast(v4f, hi);
     *reinterpret_cast<v4f*>(dst + 16 + 4 * piece) = __builtin_bit_cast(v4f, lo);
 }
 
+int split_row_stride(int d) { return (d + KC - 1) / KC * KC; }
+
 hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream)
 {
-    if (d % KC != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit)) & 15) != 0) return hipErrorInvalidValue;
-    const long long octets = (long long)N * (d >> 3);
-    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, Xsplit);
+    if (d % 4 != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit)) & 15) != 0) return hipErrorInvalidValue;
+    const int stride = split_row_stride(d);
+    const long long octets = (long long)N * (stride >> 3);
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, stride, Xsplit);
     return hipGetLastError();
 }
 
@@ -2153,6 +2189,9 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
     }
     // tile pruning and the slot map exist in the register-resident-query variant only
     if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter || ranges) return hipErrorInvalidValue;
+    if (vec4 && p.Xq_split && p.Xc_split && p.d > 4 * KC &&
+        (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0))
+        return launch_with_lds(&sweep_kernel<KL, MASKED, true, true>, grid, lds, p, stream);
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);
     return launch_with_lds(&sweep_kernel<KL, MASKED, false>, grid, lds, p, stream);
 }
