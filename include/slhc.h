@@ -190,6 +190,15 @@ int slhc_probe_fp32_mfma(double* tflops, void* workspace, size_t workspace_bytes
 /* The same for v_mfma_f32_32x32x16_bf16, the multiply of the sweeps that form their tile products from split
  * bfloat16 halves (SLHC_FP32_FILTER describes them); same arguments. */
 int slhc_probe_bf16_mfma(double* tflops, void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * Checking aid for the filter slack of those sweeps (paper Sec. 3.1.1: the tile contraction; how far its value may
+ * be off decides which pairs must be re-evaluated): one v_mfma_f32_32x32x16_bf16 per trial on the caller's values,
+ *   D[t] = C[t] + sum_{k<16} A[16 t + k] * B[16 t + k],
+ * so that a test can compare the instruction with an exact sum.  A, B [16 * trials], C, D [trials]: DEVICE,
+ * float32, A and B holding bfloat16-representable values (others are rounded to bfloat16 first).  Asynchronous
+ * on `stream`; 0 <= trials <= 2^24.
+ */
+int slhc_probe_bf16_mfma_values(const float* A, const float* B, const float* C, float* D, int32_t trials, void* stream);
 
 /*
  * Measurement aid like slhc_probe_fp32_mfma, for the panel loop of the sweeps (paper Sec. 3.1.1, the

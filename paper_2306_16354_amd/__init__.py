@@ -8,5 +8,5 @@ raises.
 """
 from .binding import (SlhcError, abi_version, cross_1nn, knn_graph, library_path, slhc,  # noqa: F401
                       knn_workspace_bytes, slhc_workspace_bytes, load_library, flat_clusters, fused_1nn, csr_msf,
-                      flat_clusters_workspace_bytes, knn_graph_static, SLHC_STATIC_MAX_ROWS, probe_fp32_mfma, probe_bf16_mfma,
+                      flat_clusters_workspace_bytes, knn_graph_static, SLHC_STATIC_MAX_ROWS, probe_fp32_mfma, probe_bf16_mfma, probe_bf16_mfma_values,
                       probe_panel_loop)

@@ -67,6 +67,8 @@ def load_library():
     lib.slhc_probe_fp32_mfma.restype = ctypes.c_int
     lib.slhc_probe_bf16_mfma.argtypes = [ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     lib.slhc_probe_bf16_mfma.restype = ctypes.c_int
+    lib.slhc_probe_bf16_mfma_values.argtypes = [vp, vp, vp, vp, ctypes.c_int32, vp]
+    lib.slhc_probe_bf16_mfma_values.restype = ctypes.c_int
     lib.slhc_probe_panel_loop.argtypes = [i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     lib.slhc_probe_panel_loop.restype = ctypes.c_int
     lib.slhc_cross_1nn_workspace_bytes.argtypes = [i64, i32, i64, ctypes.POINTER(sz)]
@@ -160,6 +162,15 @@ def knn_graph_static(X, k, out):
     idx, dist = out
     _check(load_library().slhc_knn_graph_static(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(), _stream()))
     return idx, dist
+
+
+def probe_bf16_mfma_values(A, B, C):
+    """slhc_probe_bf16_mfma_values: D[t] = C[t] + sum_k A[t, k] B[t, k] by one bf16 MFMA per row (A, B [T, 16], C [T])."""
+    A, B, C = A.contiguous(), B.contiguous(), C.contiguous()
+    assert A.dtype == B.dtype == C.dtype == torch.float32 and A.shape == B.shape and A.shape[1] == 16 and C.numel() == A.shape[0]
+    D = torch.empty_like(C)
+    _check(load_library().slhc_probe_bf16_mfma_values(A.data_ptr(), B.data_ptr(), C.data_ptr(), D.data_ptr(), A.shape[0], _stream()))
+    return D
 
 
 def probe_bf16_mfma(device="cuda"):

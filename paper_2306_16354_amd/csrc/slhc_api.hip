@@ -879,6 +879,16 @@ int slhc_probe_bf16_mfma(double* tflops, void* workspace, size_t workspace_bytes
     });
 }
 
+int slhc_probe_bf16_mfma_values(const float* A, const float* B, const float* C, float* D, int32_t trials, void* stream)
+{
+    return guarded([&]() -> int {
+        if (!A || !B || !C || !D) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
+        if (trials < 0 || trials > (1 << 24)) { set_err("trials must be 0..2^24 (trials=%d)", trials); return SLHC_INVALID_ARG; }
+        HIP_TRY(slhc::launch_mfma_bf16_values(A, B, C, D, trials, static_cast<hipStream_t>(stream)));
+        return SLHC_OK;
+    });
+}
+
 int slhc_probe_panel_loop(int32_t steps, double* tflops, void* workspace, size_t workspace_bytes, void* stream)
 {
     return guarded([&]() -> int {

@@ -127,6 +127,8 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);
 // the same with v_mfma_f32_32x32x16_bf16, the multiply of the split-product sweeps
 hipError_t launch_mfma_bf16_probe(int iters, float* sink, hipStream_t stream, double* flop);
+// D[t] = C[t] + sum_{k<16} A[t][k] B[t][k] by one v_mfma_f32_32x32x16_bf16 per trial (device arrays, A and B [trials][16])
+hipError_t launch_mfma_bf16_values(const float* A, const float* B, const float* C, float* D, int trials, hipStream_t stream);
 // The multiplies of launch_mfma_probe with the panel loop's ingredients added (steps 0..3, see the kernel);
 // `stream_rows`: [rows, 128] floats to stream from (steps >= 2; rows a power of two), iters chunks of 64 multiplies.
 hipError_t launch_loop_probe(int steps, int iters, const float* stream_rows, int rows, float* sink, hipStream_t stream,

@@ -1843,6 +1843,34 @@ __global__ void __launch_bounds__(WG_THREADS, 2) mfma_bf16_probe_kernel(int iter
     if (total == 123456.789f) sink[0] = total;
 }
 
+// One v_mfma_f32_32x32x16_bf16 per trial on caller-given values: D[t] = C[t] + sum_k A[t][k] B[t][k], k < 16, the
+// values rounded to bfloat16 first (pass bfloat16-representable ones).  For checking the rounding behaviour that
+// split_slack_coefficient relies on against an exact sum computed elsewhere.
+__global__ void __launch_bounds__(64) mfma_bf16_values_kernel(const float* __restrict__ A, const float* __restrict__ B,
+                                                              const float* __restrict__ C, float* __restrict__ D, int trials)
+{
+    const int t = blockIdx.x, lane = threadIdx.x;
+    if (t >= trials) return;
+    v8bf a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)A[(size_t)t * 16 + 8 * (lane >> 5) + e];
+        b[e] = (__bf16)B[(size_t)t * 16 + 8 * (lane >> 5) + e];
+    }
+    v16f acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = C[t];
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+    if (lane == 0) D[t] = acc[0];
+}
+
+hipError_t launch_mfma_bf16_values(const float* A, const float* B, const float* C, float* D, int trials, hipStream_t stream)
+{
+    if (trials < 1) return hipSuccess;
+    hipLaunchKernelGGL(mfma_bf16_values_kernel, dim3(trials), dim3(64), 0, stream, A, B, C, D, trials);
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_bf16_probe(int iters, float* sink, hipStream_t stream, double* flop)
 {
     int cus = 0;
