@@ -174,6 +174,11 @@ __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict_
     }
 }
 
+// A value that is the same in all lanes, as the compiler can see it: queue lengths come back from real calls in
+// vector registers, and a counter fed from them would live in a vector register (in practice in scratch memory,
+// read and written once per visit of the rare path) instead of a scalar one.
+__device__ inline int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 __device__ inline unsigned long long make_key(float dist, int idx)
 {
     return ((unsigned long long)__float_as_uint(dist) << 32) | (unsigned int)idx;
@@ -573,13 +578,13 @@ __device__ __attribute__((noinline)) int defer_block(v16f t, int b, float bound,
         FINE_MARK(6);                                                                                       \
         _Pragma("unroll") for (int b_ = 0; b_ < 4; ++b_) {                                                  \
             if (flagged & (1u << b_)) {                                                                     \
-                int r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_);    \
+                int r_ = wave_uniform(compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_)); \
                 STUDY_AGAIN(r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, qn_)); \
                 if (r_ < 0) {                                                                               \
                     survivors += (unsigned int)qn_;                                                         \
                     resolve_queue<KL_, VEC4_>(qn_, col0, Xq, Xc, p.c_id, d, k);                             \
                     bound = bounds[my_q_local];                                                             \
-                    r_ = compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, 0);      \
+                    r_ = wave_uniform(compact_block<KL_, MASKED_>(acc[b_], b_, bound, my_tag, col0, colbuf_, N, 0)); \
                 }                                                                                           \
                 qn_ = r_;                                                                                   \
             }                                                                                               \
@@ -1590,11 +1595,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                             int queued = 0;
 #pragma unroll
                             for (int b = 0; b < 4; ++b) {
-                                int r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, queued);
+                                int r = wave_uniform(compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, queued));
                                 if (r < 0) {                                 // queue full: resolve, then this block alone
                                     survivors += (unsigned int)queued;
                                     resolve_queue<KL, true>(queued, col0, Xq, Xc, p.c_id, d, k);
-                                    r = compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, 0);
+                                    r = wave_uniform(compact_block<KL, MASKED>(acc[b], b, reach_bound, seed_tag, col0, tpar, N, 0));
                                 }
                                 queued = r;
                             }
@@ -1657,7 +1662,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     if ((flagged & 4u) && defer_block<KL, MASKED>(acc[2], 2, bound, my_tag, col0, tpar, N) < 0) heavy |= 4u;
                     if ((flagged & 8u) && defer_block<KL, MASKED>(acc[3], 3, bound, my_tag, col0, tpar, N) < 0) heavy |= 8u;
                     PHASE_MARK(1);
-                    int waiting_ = *deferred_count(L, wave);
+                    int waiting_ = wave_uniform(*deferred_count(L, wave));
                     if (__builtin_expect(heavy != 0, 0)) {
                         if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
                         waiting_ = 0;
@@ -1683,7 +1688,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                 // lengths and resolve what they hold as soon as one queue has reached DEFER_MIN.
                 const int4 lens = *reinterpret_cast<const int4*>(reinterpret_cast<const int*>(L.wmax) + (tpar ^ 1) * 4);
                 const int longest = max(max(lens.x, lens.y), max(lens.z, lens.w));
-                int waiting_ = *deferred_count(L, wave);
+                int waiting_ = wave_uniform(*deferred_count(L, wave));
                 if (__builtin_expect(longest >= DEFER_MIN, 0) && waiting_ > 0) {
                     __builtin_amdgcn_s_setprio(1);
                     survivors += (unsigned int)waiting_;
@@ -1730,7 +1735,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
 #endif
         // ---- panel epilogue: lists are already ascending; write them out ----
         if (!BATCHED) {
-            const int waiting_ = *deferred_count(L, wave);
+            const int waiting_ = wave_uniform(*deferred_count(L, wave));
             if (waiting_ > 0) { survivors += (unsigned int)waiting_; resolve_deferred<KL, true>(waiting_, Xq, Xc, p.c_id, d, k); }
         }
         __builtin_amdgcn_wave_barrier();
