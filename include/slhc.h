@@ -129,7 +129,11 @@ typedef struct slhc_stats {
                            same range at a time (served by every XCD's L2 instead of being fetched from
                            memory once per panel), and a panel's lists and thresholds travel from range to
                            range through the output arrays.  With this flag every workgroup sweeps all
-                           candidates for one panel at a time, as the smaller launches do.  Same outputs.  */
+                           candidates for one panel at a time, as the smaller launches do.  Same outputs.
+                           (Going range by range, a work item waits for the item that wrote its panel's
+                           lists one range earlier; the wait is bounded, and if it ever ran out the
+                           synchronous entry points would return SLHC_INTERNAL.  slhc_knn_graph is
+                           asynchronous and cannot; the condition has never been observed.)            */
 
 int slhc_abi_version(void);
 const char* slhc_strerror(int status);          /* static string, never NULL */
