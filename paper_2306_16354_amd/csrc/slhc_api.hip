@@ -213,7 +213,10 @@ size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 // tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
 // (in the register-resident-query kernel); beyond 128 features the streaming kernel takes any multiple of 4 columns,
 // its split copy padded to whole chunks
-bool split_products_ok(int32_t d) { return (d % 32 == 0 && d >= 64 && d <= 128) || (d > 128 && d % 4 == 0); }
+#ifndef SLHC_SPLIT_MIN_CHUNKS
+#define SLHC_SPLIT_MIN_CHUNKS 2
+#endif
+bool split_products_ok(int32_t d) { return (d % 32 == 0 && d >= 32 * SLHC_SPLIT_MIN_CHUNKS && d <= 128) || (d > 128 && d % 4 == 0); }
 
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {

@@ -42,6 +42,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
+#ifndef SLHC_SPLIT_MIN_CHUNKS
+#define SLHC_SPLIT_MIN_CHUNKS 2   // split bfloat16 products from this many chunks of 32 columns on (see split_products_ok)
+#endif
 #ifndef SLHC_SPLIT_FRAGS
 #define SLHC_SPLIT_FRAGS 2      // 2: the LDS reads of a whole chunk go ahead of its multiplies; 1: those of half a chunk
 #endif
@@ -2181,8 +2184,11 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
             if (!p.tile_r || !p.gap_ws) return hipErrorInvalidValue;
-            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= 2 &&
+            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS &&
                 (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
+#if SLHC_SPLIT_MIN_CHUNKS < 2
+                if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, true, true>, grid, lds, p, stream);
+#endif
                 if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, true, true>, grid, lds, p, stream);
                 if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, true, true>, grid, lds, p, stream);
                 return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, true, true>, grid, lds, p, stream);
@@ -2209,8 +2215,11 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
                 grid = cus * per_cu;
             }
         }
-        if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= 2 &&
+        if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS &&
             (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
+#if SLHC_SPLIT_MIN_CHUNKS < 2
+            if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, false, true>, grid, lds, p, stream);
+#endif
             if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, false, true>, grid, lds, p, stream);
             if (dch == 3) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 3, false, true>, grid, lds, p, stream);
             return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 4, false, true>, grid, lds, p, stream);
