@@ -210,13 +210,13 @@ int64_t padded_rows_limit(int64_t N) { return N + N / 2 + 256; }
 
 size_t slhc_ws_bytes(int64_t N, int32_t d, int32_t k, bool with_order);
 
-// tile products from split bfloat16 halves: whole chunks of 32 columns, at least two of them
-// (in the register-resident-query kernel); beyond 128 features the streaming kernel takes any multiple of 4 columns,
+// tile products from split bfloat16 halves: whole chunks of 32 columns up to 128 features (the
+// register-resident-query kernel); beyond 128 features the streaming kernel takes any multiple of 4 columns,
 // its split copy padded to whole chunks
-#ifndef SLHC_SPLIT_MIN_CHUNKS
-#define SLHC_SPLIT_MIN_CHUNKS 2
-#endif
-bool split_products_ok(int32_t d) { return (d % 32 == 0 && d >= 32 * SLHC_SPLIT_MIN_CHUNKS && d <= 128) || (d > 128 && d % 4 == 0); }
+bool split_products_ok(int32_t d) { return (d % 32 == 0 && d >= 32 && d <= 128) || (d > 128 && d % 4 == 0); }
+// ... in the pruned sweeps from two chunks on only: at 32 features a tile's multiplies are too short for the
+// wider filter to pay (2M x 32: pruned connection sweeps 30 ms with float32 products, 60 ms with split ones)
+bool split_products_pruned_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <= 128; }
 
 // Buffers of the spatially coherent row order (see build_order).
 struct OrderWs {
@@ -587,7 +587,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (prune) {
         const OrderWs& o = ws.order;
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-        if (o.Xs_split && ws.hn_split && !(flags & SLHC_FP32_FILTER)) {
+        if (o.Xs_split && ws.hn_split && split_products_pruned_ok(d) && !(flags & SLHC_FP32_FILTER)) {
             // the reordered copy in split halves too; its half norms are those of the rows (padding: +inf)
             HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream));
             HIP_TRY(slhc::order_gather_f32(ws.hn_split, o.perm, o.Ns, (int)N, __builtin_inff(), o.hs_split, stream));

@@ -43,7 +43,10 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 #ifndef SLHC_SPLIT_MIN_CHUNKS
-#define SLHC_SPLIT_MIN_CHUNKS 2   // split bfloat16 products from this many chunks of 32 columns on (see split_products_ok)
+#define SLHC_SPLIT_MIN_CHUNKS 1   // every-tile sweeps: split bfloat16 products from this many chunks of 32 columns on
+#endif
+#ifndef SLHC_SPLIT_MIN_CHUNKS_PRUNED
+#define SLHC_SPLIT_MIN_CHUNKS_PRUNED 2   // pruned sweeps: from two chunks on (at 32 features the wider filter costs more than the multiplies save)
 #endif
 #ifndef SLHC_SPLIT_FRAGS
 #define SLHC_SPLIT_FRAGS 2      // 2: the LDS reads of a whole chunk go ahead of its multiplies; 1: those of half a chunk
@@ -2184,9 +2187,9 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
             if (!p.tile_r || !p.gap_ws) return hipErrorInvalidValue;
-            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS &&
+            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS_PRUNED &&
                 (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
-#if SLHC_SPLIT_MIN_CHUNKS < 2
+#if SLHC_SPLIT_MIN_CHUNKS_PRUNED < 2
                 if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, true, true>, grid, lds, p, stream);
 #endif
                 if (dch == 2) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 2, true, true>, grid, lds, p, stream);

@@ -605,9 +605,9 @@ def test_pruned_random_shapes(lib):
 
 # ----------------------------------------------------------------------------- tile products from split bfloat16 halves
 @pytest.mark.parametrize("kind", ["offset", "mantissa", "mixed_scale", "duplicates", "lattice", "tiny"])
-@pytest.mark.parametrize("d", [64, 96, 128, 132, 260, 784])
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 132, 260, 784])
 def test_split_bf16_filter_loses_nothing(lib, kind, d):
-    """From 64 to 128 features (multiples of 32, register-resident queries) and beyond 128 features (multiples of
+    """From 32 to 128 features (multiples of 32, register-resident queries) and beyond 128 features (multiples of
     4, streaming kernel, split copy padded to whole chunks) the every-tile sweeps form their tile products from bfloat16 halves
     (hi*hi + hi*lo + lo*hi) and widen the filter's slack by what that drops.  The filter only decides
     which pairs are evaluated exactly, so lists and trees must equal those of the float32 products bit for
