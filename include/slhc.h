@@ -97,8 +97,8 @@ typedef struct slhc_stats {
 /* Option flags of the *_opt entry points. */
 #define SLHC_PRUNE 1u   /* reorder rows spatially and skip (query panel, candidate tile) pairs whose
                            bounding balls prove that no pair can enter a list.  Results are identical
-                           to the unpruned sweep; only available for d <= 128 with d % 4 == 0 and
-                           N >= 512 (ignored otherwise).  Not in the paper, whose k-NN multiplies every tile.
+                           to the unpruned sweep; only available for d <= 128 and N >= 512 (ignored
+                           otherwise).  Not in the paper, whose k-NN multiplies every tile.
                            Building the row order reads counters back, so a call with this flag
                            is synchronous and allocates pinned host staging while it runs.      */
 #define SLHC_SPLIT_ROUNDS 2u   /* slhc_slhc_opt with SLHC_PRUNE only; a testing and tuning aid.  Every
@@ -115,11 +115,12 @@ typedef struct slhc_stats {
                            bounds of every query panel against the candidate tiles themselves, as
                            they do for row orders of more than 32768 tiles, instead of reading them
                            from the table of all tile pairs.  Same outputs.                     */
-#define SLHC_FP32_FILTER 16u   /* The every-tile sweeps accumulate their tile products in float32 (fp32 MFMA),
-                           as they always do below 64 features and up to 128 when d is not a multiple of
-                           32, instead of in split bfloat16 halves (bf16 MFMA, 16 times the rate), which
-                           is the default from 64 to 128 features (multiples of 32) and beyond 128
-                           (multiples of 4).  Only the filter differs: every
+#define SLHC_FP32_FILTER 16u   /* The sweeps accumulate their tile products in float32 (fp32 MFMA), as the
+                           pruned sweeps always do below 64 features, instead of in split bfloat16 halves
+                           (bf16 MFMA, 16 times the rate), which is the default of slhc_knn_graph* and
+                           slhc_slhc* (these work on a copy of X with zero columns appended: whole chunks of
+                           32 columns up to 128 features, a multiple of 4 beyond; a zero column changes no
+                           bit of any distance).  Only the filter differs: every
                            pair that may enter a list is re-evaluated in float32 either way, so the
                            outputs are the same bit for bit.                                     */
 

@@ -100,6 +100,49 @@ __global__ void k_zero_words(uint32_t* p, int n)
     if (i < n) p[i] = 0u;
 }
 
+// Columns the sweeps work on.  A zero column adds fma(0, 0, s) = s to a distance and to a norm, so appending
+// zero columns changes no bit of any output; it does change which kernels apply.  Up to 128 features the rows are
+// padded to whole chunks of 32 columns (register-resident queries, split bfloat16 products, tile pruning for
+// every d), beyond that to a multiple of 4 (vector loads and split products in the streaming kernel).  The
+// padded copy lives at the head of the caller's workspace.  d is kept where the padded matrix would pass the
+// 2^31-1 element limit.
+int32_t working_columns(int64_t N, int32_t d)
+{
+    const int32_t dw = d <= 128 ? (d + 31) / 32 * 32 : (d + 3) / 4 * 4;
+    return N * (int64_t)dw > 2147483647LL ? d : dw;
+}
+size_t padded_copy_bytes(int64_t N, int32_t d)
+{
+    const int32_t dw = working_columns(N, d);
+    return dw == d ? 0 : up((size_t)N * (size_t)dw * sizeof(float));
+}
+
+// out[row][c] = c < d ? X[row][c] : 0 for c < dw (dw a multiple of 4); one thread per four output columns
+__global__ void __launch_bounds__(256) k_pad_columns(const float* __restrict__ X, long long quads, int d, int dw,
+                                                     float* __restrict__ out)
+{
+    const long long q = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    const int per_row = dw >> 2;
+    const long long row = q / per_row;
+    const int c0 = 4 * (int)(q - row * per_row);
+    const float* src = X + row * d;
+    float4 v;
+    v.x = c0 < d ? src[c0] : 0.f;
+    v.y = c0 + 1 < d ? src[c0 + 1] : 0.f;
+    v.z = c0 + 2 < d ? src[c0 + 2] : 0.f;
+    v.w = c0 + 3 < d ? src[c0 + 3] : 0.f;
+    *reinterpret_cast<float4*>(out + row * dw + c0) = v;
+}
+
+int pad_columns(const float* X, int64_t N, int32_t d, int32_t dw, float* out, hipStream_t s)
+{
+    const long long quads = (long long)N * (dw >> 2);
+    hipLaunchKernelGGL(k_pad_columns, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, X, quads, d, dw, out);
+    HIP_TRY(hipGetLastError());
+    return SLHC_OK;
+}
+
 // Pinned host staging for device<->host copies (freed when the call returns).
 struct PinnedHost {
     void* p = nullptr;
@@ -793,7 +836,7 @@ int slhc_knn_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
         if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        *bytes = KnnWs(nullptr, N, d, true, k).bytes;
+        *bytes = padded_copy_bytes(N, d) + KnnWs(nullptr, N, working_columns(N, d), true, k).bytes;
         return SLHC_OK;
     });
 }
@@ -805,9 +848,16 @@ int slhc_knn_graph_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t*
         if (!X || !nbr_idx || !nbr_dist || !workspace) { set_err("NULL pointer argument"); return SLHC_INVALID_ARG; }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        KnnWs ws(workspace, N, d, true, k);
-        if (workspace_bytes < ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
-        return run_knn(X, N, d, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
+        const int32_t dw = working_columns(N, d);
+        const size_t head = padded_copy_bytes(N, d);
+        KnnWs ws(static_cast<unsigned char*>(workspace) + head, N, dw, true, k);
+        if (workspace_bytes < head + ws.bytes) { set_err("workspace %zu < %zu bytes", workspace_bytes, head + ws.bytes); return SLHC_WORKSPACE_TOO_SMALL; }
+        if (dw != d) {
+            const int rp = pad_columns(X, N, d, dw, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+            if (rp != SLHC_OK) return rp;
+            X = static_cast<const float*>(workspace);
+        }
+        return run_knn(X, N, dw, k, nbr_idx, nbr_dist, ws, static_cast<hipStream_t>(stream), flags);
     });
 }
 
@@ -1170,7 +1220,7 @@ int slhc_workspace_bytes(int64_t N, int32_t d, int32_t k, size_t* bytes)
         if (!bytes) { set_err("bytes is NULL"); return SLHC_INVALID_ARG; }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        *bytes = SlhcWs(nullptr, N, d, k, true).bytes;
+        *bytes = padded_copy_bytes(N, d) + SlhcWs(nullptr, N, working_columns(N, d), k, true).bytes;
         return SLHC_OK;
     });
 }
@@ -1198,10 +1248,17 @@ int slhc_slhc_opt(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_
         }
         const int rc = check_shape(N, d, k, true);
         if (rc != SLHC_OK) return rc;
-        const size_t need = slhc_ws_bytes(N, d, k, true);
+        const int32_t dw = working_columns(N, d);
+        const size_t head = padded_copy_bytes(N, d);
+        const size_t need = head + slhc_ws_bytes(N, dw, k, true);
         if (workspace_bytes < need) { set_err("workspace %zu < %zu bytes", workspace_bytes, need); return SLHC_WORKSPACE_TOO_SMALL; }
-        return run_slhc(X, N, d, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats, workspace,
-                        static_cast<hipStream_t>(stream), flags, true);
+        if (dw != d) {
+            const int rp = pad_columns(X, N, d, dw, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+            if (rp != SLHC_OK) return rp;
+            X = static_cast<const float*>(workspace);
+        }
+        return run_slhc(X, N, dw, k, mst_src, mst_dst, mst_w, children, heights, sizes, stats,
+                        static_cast<unsigned char*>(workspace) + head, static_cast<hipStream_t>(stream), flags, true);
     });
 }
 

@@ -603,6 +603,31 @@ def test_pruned_random_shapes(lib):
             check_slhc(np.ascontiguousarray(X), b, tie_free=not ties)
 
 
+# ----------------------------------------------------------------------------- zero columns appended by the library
+@pytest.mark.parametrize("N,d,k", [(700, 1, 3), (3000, 7, 5), (5000, 50, 16), (4000, 100, 32), (2100, 127, 64),
+                                   (3000, 130, 8), (2500, 301, 16)])
+def test_padded_columns_change_nothing(lib, N, d, k):
+    """slhc_knn_graph and slhc_slhc work on a copy of X with zero columns appended (whole chunks of 32 up to 128
+    features, a multiple of 4 beyond), which opens the register-resident-query kernel, split products and tile
+    pruning to every d.  A zero column adds nothing to a distance, so the lists must equal, bit for bit, those of
+    the entry point that never pads (slhc_knn_graph_static), the pruned path those of the every-tile path, and
+    both the oracle's."""
+    rng = np.random.default_rng(N + 7 * d)
+    centres = rng.uniform(-15, 15, size=(9, d))
+    X = (centres[rng.integers(0, 9, size=N)] + rng.standard_normal((N, d))).astype(np.float32)
+    print(f"padded columns N={N} d={d} k={k}", flush=True)
+    Xd = torch.from_numpy(X).cuda()
+    plain = (torch.empty((N, k), dtype=torch.int32, device="cuda"), torch.empty((N, k), dtype=torch.float32, device="cuda"))
+    lib.knn_graph_static(Xd, k, plain)
+    i0, d0 = lib.knn_graph(Xd, k)
+    torch.cuda.synchronize()
+    assert torch.equal(plain[0], i0) and torch.equal(plain[1], d0)
+    check_knn(X, k, i0.cpu().numpy(), d0.cpu().numpy(), min_exact=0.999)
+    b = _pruned_equals_every_tile(lib, X, k)
+    assert b["stats"]["pruned"] == (1 if d <= 128 else 0)
+    check_slhc(X, b, tie_free=True)
+
+
 # ----------------------------------------------------------------------------- tile products from split bfloat16 halves
 @pytest.mark.parametrize("kind", ["offset", "mantissa", "mixed_scale", "duplicates", "lattice", "tiny"])
 @pytest.mark.parametrize("d", [32, 64, 96, 128, 132, 260, 784])
