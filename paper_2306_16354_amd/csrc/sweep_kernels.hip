@@ -17,7 +17,7 @@
 //     load takes, and the sweep waits for its loads.  Launches of many panels go range by range
 //     (SweepParams::carry_ws): all workgroups sweep the same 32 MiB of candidates at a time, which
 //     the memory-side cache then serves, and a panel's lists travel from range to range;
-//   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32, or, from 64 to 128 features,
+//   * the tile x_c . x_q is accumulated with v_mfma_f32_32x32x2_f32, or, with whole chunks of 32 columns,
 //     from split bfloat16 halves as hi_c hi_q + hi_c lo_q + lo_c hi_q with
 //     v_mfma_f32_32x32x16_bf16 (16 times the rate; the filter's slack covers the dropped terms, and
 //     only the filter sees these products).  Candidates are the A
