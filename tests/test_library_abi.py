@@ -84,6 +84,29 @@ def test_workspace_sizes_and_shape_errors(cdll):
     assert b"k" in cdll.slhc_last_error() or cdll.slhc_last_error() != b""
 
 
+def test_workspace_holds_the_copy_with_zero_columns(cdll):
+    """The k-NN and clustering entry points work on whole chunks of 32 columns up to 128 features and on a
+    multiple of 4 beyond; the padded copy of X sits at the head of the workspace, so the size for d is the size
+    for the padded d plus N x d' floats (rounded up to the 256-byte slices), and nothing where d already fits.
+    Where the padded matrix would pass 2^31 - 1 elements the columns stay as they are."""
+    out = ctypes.c_size_t(0)
+
+    def size(fn, N, d, k):
+        assert fn(N, d, k, ctypes.byref(out)) == 0, cdll.slhc_last_error()
+        return out.value
+
+    up = lambda b: (b + 255) // 256 * 256
+    for fn in (cdll.slhc_knn_workspace_bytes, cdll.slhc_workspace_bytes):
+        for N, d, dw, k in ((50_000, 100, 128, 16), (50_000, 7, 32, 5), (3001, 33, 64, 8), (20_000, 130, 132, 8),
+                            (20_000, 785, 788, 16)):
+            assert size(fn, N, d, k) == size(fn, N, dw, k) + up(N * dw * 4), (N, d, dw)
+        # 8 columns padded to 32: 67 108 863 rows stay within the element limit and get the copy; one row more
+        # is still accepted and laid out for 8 columns (no copy, and every array of d columns is a quarter the size)
+        last = (2 ** 31 - 1) // 32
+        assert size(fn, last, 8, 3) == size(fn, last, 32, 3) + up(last * 32 * 4)
+        assert size(fn, last, 8, 3) - size(fn, last + 1, 8, 3) > last * 32 * 4
+
+
 def test_null_pointers_are_rejected_before_any_device_work(cdll):
     assert cdll.slhc_knn_graph(None, 10, 4, 2, None, None, None, 0, None) == 1
     assert cdll.slhc_slhc(None, 10, 4, 2, None, None, None, None, None, None, None, None, 0, None) == 1
