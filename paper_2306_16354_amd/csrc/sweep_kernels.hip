@@ -48,6 +48,9 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 #ifndef SLHC_SPLIT_MIN_CHUNKS_PRUNED
 #define SLHC_SPLIT_MIN_CHUNKS_PRUNED 2   // pruned sweeps: from two chunks on (at 32 features the wider filter costs more than the multiplies save)
 #endif
+#ifndef SLHC_SCAN_AHEAD
+#define SLHC_SCAN_AHEAD 4      // groups of 64 scan positions whose lower bounds a pruned sweep reads at once (see next_scan)
+#endif
 #ifndef SLHC_SPLIT_FRAGS
 #define SLHC_SPLIT_FRAGS 2      // 2: the LDS reads of a whole chunk go ahead of its multiplies; 1: those of half a chunk
 #endif
@@ -1279,15 +1282,27 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             return side_r > side_l ? centre + side_min + 1 + r : centre - side_min - 1 - r;
         };
         auto tile_of = [&](int i) -> int { return i >= nscan ? ntiles : scan_tile(i); };
+        // (SCAN_AHEAD groups of 64 positions are read at once: one group at a time the scan is a chain of dependent
+        // loads, a microsecond each, and a panel that multiplies two tiles of 20 000 spends its time there)
+        constexpr int SCAN_AHEAD = SLHC_SCAN_AHEAD;
         auto next_scan = [&](int i, float thr_max) -> int {
             if (!prune) return i;
             while (i < nscan) {
-                const int ii = i + lane;
-                bool need = false;
-                if (ii < nscan) need = gap_of(scan_tile(ii)) <= thr_max;          // false for NaN
-                const unsigned long long mask = __ballot(need);
-                if (mask) return i + __builtin_ctzll(mask);
-                i += 64;
+                // (all the votes are taken before the first is looked at: a vote cannot move into a branch, so
+                // the loads behind it cannot either)
+                float g[SCAN_AHEAD];
+#pragma unroll
+                for (int u = 0; u < SCAN_AHEAD; ++u) {
+                    const int ii = i + 64 * u + lane;
+                    g[u] = ii < nscan ? gap_of(scan_tile(ii)) : __builtin_nanf("");
+                }
+                unsigned long long mask[SCAN_AHEAD];
+#pragma unroll
+                for (int u = 0; u < SCAN_AHEAD; ++u) mask[u] = __ballot(g[u] <= thr_max);          // false for NaN
+#pragma unroll
+                for (int u = 0; u < SCAN_AHEAD; ++u)
+                    if (mask[u]) return i + 64 * u + __builtin_ctzll(mask[u]);
+                i += 64 * SCAN_AHEAD;
             }
             return nscan;
         };
