@@ -143,6 +143,26 @@ int pad_columns(const float* X, int64_t N, int32_t d, int32_t dw, float* out, hi
     return SLHC_OK;
 }
 
+// out[0], out[1] = sums of a[i] and b[i] over at most 16384 evenly spaced i < n (one workgroup, fixed order)
+__global__ void __launch_bounds__(256) k_sample_sums(const float* __restrict__ a, const float* __restrict__ b, int n,
+                                                     float* __restrict__ out)
+{
+    __shared__ float sa[256], sb[256];
+    const int samples = n < 16384 ? n : 16384;
+    float xa = 0.f, xb = 0.f;
+    for (int i = threadIdx.x; i < samples; i += 256) {
+        const long long at = (long long)i * n / samples;
+        xa += a[at]; xb += b[at];
+    }
+    sa[threadIdx.x] = xa; sb[threadIdx.x] = xb;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) { sa[threadIdx.x] += sa[threadIdx.x + w]; sb[threadIdx.x] += sb[threadIdx.x + w]; }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { out[0] = sa[0]; out[1] = sb[0]; }
+}
+
 // Pinned host staging for device<->host copies (freed when the call returns).
 struct PinnedHost {
     void* p = nullptr;
@@ -321,10 +341,14 @@ struct KnnWs {
     // every-tile sweeps on the bf16 MFMA: X split into bfloat16 halves (see SweepParams::Xq_split) and the half
     // norms with the slack that goes with it; nullptr when d does not allow it
     float* Xsplit; float* hn_split;
+    // the split copies hold the rows relative to the column means of X (a sample's): shift [d], and the scratch of
+    // the two-pass mean
+    float* shift; float* shift_scratch;
     // scratch of the every-tile sweeps that go range by range (see SweepParams::carry_ws): 2 + panels words
     unsigned int* carry_ws; long long carry_ws_words;
     bool split_ready = false;        // filled in this call
     bool order_split_ready = false;  // likewise the split copy of the reordered rows
+    bool offset_heavy = false;       // the rows' norms are mostly a common offset (see run_knn): split products everywhere
     size_t bytes;
     KnnWs(void* ws, int64_t N, int32_t d, bool with_order, int32_t k = 0)
     {
@@ -332,10 +356,12 @@ struct KnnWs {
         counters = c.take<unsigned long long>(32);
         hn = c.take<float>((size_t)N);
         part_idx = nullptr; part_dist = nullptr; part_rows = 0;
-        Xsplit = nullptr; hn_split = nullptr;
+        Xsplit = nullptr; hn_split = nullptr; shift = nullptr; shift_scratch = nullptr;
         if (split_products_ok(d) && k > 0) {
             Xsplit = c.take<float>((size_t)N * (size_t)slhc::split_row_stride(d));
             hn_split = c.take<float>((size_t)N);
+            shift = c.take<float>((size_t)d);
+            shift_scratch = c.take<float>(slhc::column_means_scratch_floats(d));
         }
         {
             // ranges x rows never exceeds the workgroup slots x 128: a sweep is only split while its panels
@@ -394,11 +420,23 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
 
 int bits_for(long long n) { int b = 1; while (b < 32 && (1LL << b) < n) ++b; return b; }
 
+// X in split bfloat16 halves, taken relative to the column means of a sample of its rows (a translation changes no
+// distance and keeps a common offset of the data out of the filter's slack), with the half norms that go with it.
+int make_split_copy(const float* X, int64_t N, int32_t d, KnnWs& ws, hipStream_t s)
+{
+    HIP_TRY(slhc::launch_column_means(X, (int)N, d, ws.shift_scratch, ws.shift, s));
+    HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, s, ws.shift));
+    HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, s, nullptr, true, ws.shift));
+    ws.split_ready = true;
+    return SLHC_OK;
+}
+
 // Nearest pivot of every row by the fused sweep (k = 1 against the P pivot rows).
-// `x_split` / `hn_split` (optional): X in split bfloat16 halves and the half norms that go with it; the pivots
+// `x_split` / `hn_split` / `shift` (optional): X in split bfloat16 halves, the half norms that go with it and the
+// shift both were taken relative to; the pivots
 // then get a split copy of their own (in the buffers of the reordered copy's, which are free until step 4).
 int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, OrderWs& o, int P, hipStream_t s,
-                     const float* x_split = nullptr, const float* hn_split = nullptr)
+                     const float* x_split = nullptr, const float* hn_split = nullptr, const float* shift = nullptr)
 {
     slhc::SweepParams p{};
     p.Xq = X; p.hq = hn; p.NQ = (int)N;
@@ -406,10 +444,10 @@ int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, Orde
     p.d = d; p.k = 1;
     p.out_idx = o.pid; p.out_dist = o.pdist;
     if (x_split && hn_split && o.Xs_split && o.hs_split) {
-        HIP_TRY(slhc::launch_split_bf16(o.Xp, P, d, o.Xs_split, s));
-        HIP_TRY(slhc::launch_half_norms(o.Xp, P, d, o.hs_split, s, nullptr, true));
-        p.Xq_split = x_split; p.hq = hn_split;
-        p.Xc_split = o.Xs_split; p.hc = o.hs_split;
+        HIP_TRY(slhc::launch_split_bf16(o.Xp, P, d, o.Xs_split, s, shift));
+        HIP_TRY(slhc::launch_half_norms(o.Xp, P, d, o.hs_split, s, nullptr, true, shift));
+        p.Xq_split = x_split; p.hq_split = hn_split;
+        p.Xc_split = o.Xs_split; p.hc_split = o.hs_split;
     }
     HIP_TRY(slhc::launch_knn_sweep(p, s));
     return SLHC_OK;
@@ -429,7 +467,7 @@ int assign_to_pivots(const float* X, int64_t N, int32_t d, const float* hn, Orde
 // `nonfinite`: device word the norm kernel set when a row is not finite; checked first, because
 // nothing below is defined for such rows.
 int build_order(const float* X, int64_t N, int32_t d, const float* hn, const unsigned int* nonfinite, OrderWs& o,
-                hipStream_t s, const float* x_split = nullptr, const float* hn_split = nullptr)
+                hipStream_t s, const float* x_split = nullptr, const float* hn_split = nullptr, const float* shift = nullptr)
 {
     const int n = (int)N;
     const int P1 = o.P1;
@@ -451,7 +489,7 @@ int build_order(const float* X, int64_t N, int32_t d, const float* hn, const uns
 
     // ---- 1. pivots and assignment
     HIP_TRY(slhc::order_pick_rows(X, hn, n, d, P1, o.Xp, o.hp, s));
-    int rc = assign_to_pivots(X, N, d, hn, o, P1, s, x_split, hn_split);
+    int rc = assign_to_pivots(X, N, d, hn, o, P1, s, x_split, hn_split, shift);
     if (rc != SLHC_OK) return rc;
     const int S = n < OrderWs::SAMPLE ? n : OrderWs::SAMPLE;
     HIP_TRY(slhc::order_pick_f32(o.pdist, n, S, o.sample, s));
@@ -611,12 +649,25 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (prune) {
         const bool split = ws.Xsplit && ws.hn_split && !(flags & SLHC_FP32_FILTER);
         if (split) {        // X in split halves: for the nearest-pivot sweep here and for every-tile sweeps later
-            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, stream));
-            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
-            ws.split_ready = true;
+            const int rs = make_split_copy(X, N, d, ws, stream);
+            if (rs != SLHC_OK) return rs;
+            if (!split_products_pruned_ok(d)) {
+                // Below 64 features the pruned sweeps multiply in float32, on the rows as they are: fine unless the
+                // rows share an offset far larger than their distances, which then fills the filter's slack and
+                // lets every pair of a tile through.  The split copy is taken relative to the column means; when
+                // that shrinks the norms eightfold or more, the pruned sweeps multiply it too.
+                PinnedHost pin;
+                HIP_TRY(pin.alloc(2 * sizeof(float)));
+                float* h_sums = static_cast<float*>(pin.p);
+                hipLaunchKernelGGL(k_sample_sums, dim3(1), dim3(256), 0, stream, ws.hn, ws.hn_split, (int)N, ws.shift_scratch);
+                HIP_TRY(hipGetLastError());
+                HIP_TRY(hipMemcpyAsync(h_sums, ws.shift_scratch, 2 * sizeof(float), hipMemcpyDeviceToHost, stream));
+                HIP_TRY(hipStreamSynchronize(stream));
+                ws.offset_heavy = h_sums[0] >= 8.f * h_sums[1];          // false when either sum is NaN
+            }
         }
         const int rc = build_order(X, N, d, ws.hn, reinterpret_cast<const unsigned int*>(ws.counters + 4), ws.order, stream,
-                                   split ? ws.Xsplit : nullptr, split ? ws.hn_split : nullptr);
+                                   split ? ws.Xsplit : nullptr, split ? ws.hn_split : nullptr, split ? ws.shift : nullptr);
         if (rc != SLHC_OK) return rc;
     }
     if (ev_order) HIP_TRY(hipEventRecord(ev_order->b, stream));
@@ -630,11 +681,11 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (prune) {
         const OrderWs& o = ws.order;
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-        if (o.Xs_split && ws.hn_split && split_products_pruned_ok(d) && !(flags & SLHC_FP32_FILTER)) {
+        if (o.Xs_split && ws.hn_split && (split_products_pruned_ok(d) || ws.offset_heavy) && !(flags & SLHC_FP32_FILTER)) {
             // the reordered copy in split halves too; its half norms are those of the rows (padding: +inf)
-            HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream));
+            HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream, ws.shift));
             HIP_TRY(slhc::order_gather_f32(ws.hn_split, o.perm, o.Ns, (int)N, __builtin_inff(), o.hs_split, stream));
-            p.Xq_split = p.Xc_split = o.Xs_split; p.hq = p.hc = o.hs_split;
+            p.Xq_split = p.Xc_split = o.Xs_split; p.hq_split = p.hc_split = o.hs_split;
             ws.order_split_ready = true;
         }
         p.q_out_row = o.perm; p.c_id = o.perm;
@@ -657,10 +708,9 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
             p.carry_fault = reinterpret_cast<unsigned int*>(ws.counters + 4);
         }
         if (ws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
-            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, ws.Xsplit, stream));
-            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, ws.hn_split, stream, nullptr, true));
-            p.Xq_split = p.Xc_split = ws.Xsplit; p.hq = p.hc = ws.hn_split;
-            ws.split_ready = true;
+            const int rs = make_split_copy(X, N, d, ws, stream);
+            if (rs != SLHC_OK) return rs;
+            p.Xq_split = p.Xc_split = ws.Xsplit; p.hq_split = p.hc_split = ws.hn_split;
         }
 #ifdef SLHC_PHASE_TIMERS
         p.phase_cycles = ws.counters + 16;
@@ -1449,7 +1499,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     if (h_cnt[6] < 0 || h_cnt[6] > (o.Ns + 127) / 128) { set_err("bad count of queried tiles %d", h_cnt[6]); return SLHC_INTERNAL; }
                     p.panel_list = o.tile_list; p.panel_list_n = h_cnt[6];
                     p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-                    if (kws.order_split_ready) { p.Xq_split = p.Xc_split = o.Xs_split; p.hq = p.hc = o.hs_split; }
+                    if (kws.order_split_ready) { p.Xq_split = p.Xc_split = o.Xs_split; p.hq_split = p.hc_split = o.hs_split; }
                     p.qcolour = p.ccolour = o.colour_s;
                     p.qslot = o.qslot;
                     p.c_id = o.perm;
@@ -1484,13 +1534,11 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     }
                     if (kws.Xsplit && !(flags & SLHC_FP32_FILTER)) {
                         if (!kws.split_ready) {          // (a pruned k-NN sweep did not need it)
-                            HIP_TRY(slhc::launch_split_bf16(X, (int)N, d, kws.Xsplit, s));
-                            HIP_TRY(slhc::launch_half_norms(X, (int)N, d, kws.hn_split, s, nullptr, true));
-                            kws.split_ready = true;
+                            const int rs = make_split_copy(X, N, d, kws, s);
+                            if (rs != SLHC_OK) return rs;
                         }
-                        // (the larger slack of these half norms also suits the streaming kernel, should the launch
-                        // below choose it: more slack only lets more pairs through to the exact evaluation)
-                        p.Xq_split = p.Xc_split = kws.Xsplit; p.hq = p.hc = kws.hn_split;
+                        // (a launch that ends in a kernel with float32 products takes hq / hc)
+                        p.Xq_split = p.Xc_split = kws.Xsplit; p.hq_split = p.hc_split = kws.hn_split;
                     }
                 }
 #ifdef SLHC_STUDY_PANEL_STEPS

@@ -19,10 +19,15 @@ struct SweepParams {
     // value split into two bfloat16 halves, hi = bf16(x) and lo = bf16(x - hi), laid out chunk by chunk: the 32
     // floats of columns 32c .. 32c+31 of a row are replaced by 32 hi values then 32 lo values (launch_split_bf16).
     // The tile products are then accumulated as hi*hi + hi*lo + lo*hi on the bf16 MFMA, which runs at 16 times
-    // the fp32 rate; hq / hc must come from launch_half_norms with split_slack_coefficient(d), whose slack
-    // covers the dropped lo*lo terms.  Only the filter changes: pairs that pass are re-evaluated from Xq / Xc.
+    // the fp32 rate.  The split copy may hold the rows translated by a common vector (launch_split_bf16's shift),
+    // so it comes with half norms of its own, hq_split / hc_split: those of the translated rows, from
+    // launch_half_norms with split_slack_coefficient(d), whose slack covers the dropped lo*lo terms.  A kernel that
+    // multiplies the split copy reads these, one that multiplies Xq / Xc reads hq / hc.  Only the filter changes:
+    // pairs that pass are re-evaluated from Xq / Xc.
     const float* Xq_split;
     const float* Xc_split;
+    const float* hq_split;
+    const float* hc_split;
     int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
     const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)
@@ -117,11 +122,16 @@ struct SweepParams {
 float filter_slack_coefficient(int d);
 float split_slack_coefficient(int d);                 // the same for products accumulated from split bf16 halves
 // X [N, d] -> the chunk-wise split copy described at SweepParams::Xq_split (d % 32 == 0)
-hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream);
+// `shift` (optional, [d] device floats, 16-byte aligned): the copy holds fl(x - shift)
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift = nullptr);
+// column means of X over a sample of its rows -> mean [d]; scratch: column_means_scratch_floats(d) device floats
+size_t column_means_scratch_floats(int d);
+hipError_t launch_column_means(const float* X, int N, int d, float* scratch, float* mean, hipStream_t stream);
 int split_row_stride(int d);                          // words per row of the split copy: d rounded up to whole chunks of 32
 // `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
+// `shift` (optional): the norms of fl(x - shift), as for launch_split_bf16
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr,
-                             bool split_slack = false);
+                             bool split_slack = false, const float* shift = nullptr);
 // Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
 // *flop receives the floating-point operations of the launch.  `sink`: one device float.
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);

@@ -46,7 +46,11 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 #define SLHC_SPLIT_MIN_CHUNKS 1   // every-tile sweeps: split bfloat16 products from this many chunks of 32 columns on
 #endif
 #ifndef SLHC_SPLIT_MIN_CHUNKS_PRUNED
-#define SLHC_SPLIT_MIN_CHUNKS_PRUNED 2   // pruned sweeps: from two chunks on (at 32 features the wider filter costs more than the multiplies save)
+#define SLHC_SPLIT_MIN_CHUNKS_PRUNED 1   // pruned sweeps: likewise, when the caller passes the split copy (at 32 features it does so only for
+                                         // data with a large common offset: there the wider filter costs more than the multiplies save)
+#endif
+#ifndef SLHC_STREAM_SPLIT_MIN_D
+#define SLHC_STREAM_SPLIT_MIN_D 0   // the streaming kernel multiplies the split copy, where there is one, from this many features on
 #endif
 #ifndef SLHC_SCAN_AHEAD
 #define SLHC_SCAN_AHEAD 4      // groups of 64 scan positions whose lower bounds a pruned sweep reads at once (see next_scan)
@@ -147,10 +151,13 @@ __device__ inline float group8_sqdist(const float* __restrict__ a_, const float*
 // h_i = (1-c)/2 * ||x_i||^2 ; one 16-lane group per row.
 // A row whose squared norm is not a finite float32 (NaN or infinity among its values, or overflow) sets
 // *nonfinite (optional) to 1.
+// `shift` (optional, [d], 16-byte aligned with VEC4): the norms are those of the rows fl(x - shift), the rows the
+// split copy holds (see split_bf16_kernel).
 template <bool VEC4>
 __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict__ X, int N, int d,
                                                         float scale, float* __restrict__ hn,
-                                                        unsigned int* __restrict__ nonfinite)
+                                                        unsigned int* __restrict__ nonfinite,
+                                                        const float* __restrict__ shift)
 {
     const int lane16 = threadIdx.x & 15;
     const long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
@@ -160,7 +167,8 @@ __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict_
         const float* x = X + (size_t)row * d;
         if (VEC4) {
             for (int t = 4 * lane16; t < d; t += 64) {
-                const v4f v = *reinterpret_cast<const v4f*>(x + t);
+                v4f v = *reinterpret_cast<const v4f*>(x + t);
+                if (shift) v -= *reinterpret_cast<const v4f*>(shift + t);
                 s = __builtin_fmaf(v[0], v[0], s);
                 s = __builtin_fmaf(v[1], v[1], s);
                 s = __builtin_fmaf(v[2], v[2], s);
@@ -169,7 +177,10 @@ __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict_
         } else {
             for (int t0 = 4 * lane16; t0 < d; t0 += 64) {
                 const int te = (t0 + 4 < d) ? t0 + 4 : d;
-                for (int t = t0; t < te; ++t) s = __builtin_fmaf(x[t], x[t], s);
+                for (int t = t0; t < te; ++t) {
+                    const float v = shift ? x[t] - shift[t] : x[t];
+                    s = __builtin_fmaf(v, v, s);
+                }
             }
         }
     }
@@ -624,8 +635,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel(SweepParams p)
     const int N = p.NC, d = p.d, k = p.k;          // N: candidate rows
     const float* __restrict__ Xq = p.Xq;
     const float* __restrict__ Xc = p.Xc;
-    const float* __restrict__ hq = p.hq;
-    const float* __restrict__ hc = p.hc;
+    const float* __restrict__ hq = SPLIT ? p.hq_split : p.hq;          // the norms that go with the rows multiplied
+    const float* __restrict__ hc = SPLIT ? p.hc_split : p.hc;
     const int nq = MASKED ? p.m : p.NQ;
     const int npanels = (nq + BM - 1) / BM;
     const int ntiles = (N + BN - 1) / BN;
@@ -962,8 +973,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     const int N = p.NC, d = p.d, k = p.k;          // N: candidate rows
     const float* __restrict__ Xq = p.Xq;
     const float* __restrict__ Xc = p.Xc;
-    const float* __restrict__ hq = p.hq;
-    const float* __restrict__ hc = p.hc;
+    const float* __restrict__ hq = SPLIT ? p.hq_split : p.hq;          // the norms that go with the rows multiplied
+    const float* __restrict__ hc = SPLIT ? p.hc_split : p.hc;
     // cross 1-NN with a slot map: panel p holds the query rows among rows 128p .. 128p+127
     const bool aligned = PRUNE && MASKED && p.qslot != nullptr;
     const int nq = (MASKED && !aligned) ? p.m : p.NQ;
@@ -2091,13 +2102,19 @@ float split_slack_coefficient(int d)
     // hi_c hi_q + hi_c lo_q + lo_c hi_q leaves out lo_c lo_q and the r terms: at most 3 * 2^-16 |x_c x_q| per
     // column, i.e. 3 * 2^-16 (n_q + n_c) / 2 per pair.  Its products are exact in float32 and there are 3 d of
     // them to accumulate, counted like the d of filter_slack_coefficient.
-    return 3.0f * 1.52587890625e-05f + (float)(3 * d + 8) * 1.1920928955078125e-07f;
+    // The split copy holds the rows fl(x - shift) (split_bf16_kernel).  A translation changes no distance, but its
+    // rounding moves each of the two rows by at most 2^-24 of its length, i.e. the squared distance by at most
+    // 2^-23 (|u| + |v|)^2 <= 2^-22 (n_q + n_c): two more units, and two to spare.
+    return 3.0f * 1.52587890625e-05f + (float)(3 * d + 12) * 1.1920928955078125e-07f;
 }
 
 // one thread per 8 columns: hi = bf16(x), lo = bf16(x - hi), both rounded to nearest even.  A row of the split
 // copy holds whole chunks of 32 columns (stride = d rounded up to a multiple of 32 words); columns past d are 0.
+// `shift` (optional, [d]): the copy holds fl(x - shift) instead of x.  The sweeps' products only feed the filter, a
+// distance does not change when both rows are translated, and the filter's slack is a fraction of the rows' squared
+// norms: with the column means taken off, a common offset of the data no longer counts towards it.
 __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ X, long long octets, int d, int stride,
-                                                         float* __restrict__ Xsplit)
+                                                         float* __restrict__ Xsplit, const float* __restrict__ shift)
 {
     const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
     if (o >= octets) return;
@@ -2109,6 +2126,10 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict
     v4f a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
     if (8 * oct + 4 <= d) a = *reinterpret_cast<const v4f*>(src);          // d is a multiple of 4
     if (8 * oct + 8 <= d) b = *reinterpret_cast<const v4f*>(src + 4);
+    if (shift) {
+        if (8 * oct + 4 <= d) a -= *reinterpret_cast<const v4f*>(shift + 8 * oct);
+        if (8 * oct + 8 <= d) b -= *reinterpret_cast<const v4f*>(shift + 8 * oct + 4);
+    }
     v8bf hi, lo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -2124,24 +2145,66 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict
 
 int split_row_stride(int d) { return (d + KC - 1) / KC * KC; }
 
-hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream)
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift)
 {
-    if (d % 4 != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit)) & 15) != 0) return hipErrorInvalidValue;
+    if (d % 4 != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit) | reinterpret_cast<uintptr_t>(shift)) & 15) != 0)
+        return hipErrorInvalidValue;
     const int stride = split_row_stride(d);
     const long long octets = (long long)N * (stride >> 3);
-    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, stride, Xsplit);
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, stride, Xsplit, shift);
     return hipGetLastError();
 }
 
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite,
-                             bool split_slack)
+                             bool split_slack, const float* shift)
 {
     const float scale = 0.5f * (1.0f - (split_slack ? split_slack_coefficient(d) : filter_slack_coefficient(d)));
     const long long threads = (long long)N * 16;
     const int blocks = (int)((threads + 255) / 256);
-    const bool vec4 = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
-    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite);
-    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite);
+    const bool vec4 = (d % 4 == 0) && (((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(shift)) & 15) == 0);
+    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift);
+    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift);
+    return hipGetLastError();
+}
+
+// Column means over a sample of at most MEAN_SAMPLE evenly spaced rows, in two passes with a fixed order of
+// additions (the same vector in every run).  Any vector serves as a shift: values that are not finite are left
+// out, and a mean that is not finite or beyond 2^50 is replaced by 0, so that taking it off a finite row overflows
+// no sooner than the row's own norm does.
+constexpr int MEAN_SAMPLE = 16384, MEAN_PARTS = 64;
+__global__ void __launch_bounds__(256) column_sums_kernel(const float* __restrict__ X, int N, int d, int samples,
+                                                          float* __restrict__ partial)
+{
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= d) return;
+    const int part = blockIdx.x;
+    const int i0 = (int)((long long)part * samples / MEAN_PARTS), i1 = (int)((long long)(part + 1) * samples / MEAN_PARTS);
+    float sum = 0.f;
+    for (int i = i0; i < i1; ++i) {
+        const long long row = (long long)i * N / samples;
+        const float v = X[row * d + c];
+        if (fabsf(v) < __builtin_inff()) sum += v;          // false for NaN as well
+    }
+    partial[(size_t)part * d + c] = sum;
+}
+__global__ void __launch_bounds__(256) column_means_kernel(const float* __restrict__ partial, int d, int samples,
+                                                           float* __restrict__ mean)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= d) return;
+    float sum = 0.f;
+    for (int part = 0; part < MEAN_PARTS; ++part) sum += partial[(size_t)part * d + c];
+    const float m = sum / (float)samples;
+    mean[c] = fabsf(m) <= 1.125899906842624e15f ? m : 0.f;       // 2^50; false for NaN
+}
+size_t column_means_scratch_floats(int d) { return (size_t)MEAN_PARTS * (size_t)d; }
+hipError_t launch_column_means(const float* X, int N, int d, float* scratch, float* mean, hipStream_t stream)
+{
+    if (N < 1 || d < 1) return hipErrorInvalidValue;
+    const int samples = N < MEAN_SAMPLE ? N : MEAN_SAMPLE;
+    const unsigned int cblocks = (unsigned int)((d + 255) / 256);
+    hipLaunchKernelGGL(column_sums_kernel, dim3(MEAN_PARTS, cblocks), dim3(256), 0, stream, X, N, d, samples, scratch);
+    hipLaunchKernelGGL(column_means_kernel, dim3(cblocks), dim3(256), 0, stream, scratch, d, samples, mean);
     return hipGetLastError();
 }
 
@@ -2202,7 +2265,7 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
         const int dch = (p.d + KC - 1) / KC;
         if (p.tile_c) {
             if (!p.tile_r || !p.gap_ws) return hipErrorInvalidValue;
-            if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS_PRUNED &&
+            if (p.Xq_split && p.Xc_split && p.hq_split && p.hc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS_PRUNED &&
                 (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
 #if SLHC_SPLIT_MIN_CHUNKS_PRUNED < 2
                 if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, true, true>, grid, lds, p, stream);
@@ -2233,7 +2296,7 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
                 grid = cus * per_cu;
             }
         }
-        if (p.Xq_split && p.Xc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS &&
+        if (p.Xq_split && p.Xc_split && p.hq_split && p.hc_split && p.d % KC == 0 && dch >= SLHC_SPLIT_MIN_CHUNKS &&
             (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0)) {
 #if SLHC_SPLIT_MIN_CHUNKS < 2
             if (dch == 1) return launch_with_lds(&sweep_kernel_qreg<KL, MASKED, 1, false, true>, grid, lds, p, stream);
@@ -2249,7 +2312,7 @@ static hipError_t launch_sweep_t(const SweepParams& p_in, hipStream_t stream)
     }
     // tile pruning and the slot map exist in the register-resident-query variant only
     if (p.tile_c || p.qslot || p.tile_colour || p.panel_counter || ranges) return hipErrorInvalidValue;
-    if (vec4 && p.Xq_split && p.Xc_split && p.d > 4 * KC &&
+    if (vec4 && p.Xq_split && p.Xc_split && p.hq_split && p.hc_split && p.d >= SLHC_STREAM_SPLIT_MIN_D &&
         (((reinterpret_cast<uintptr_t>(p.Xq_split) | reinterpret_cast<uintptr_t>(p.Xc_split)) & 15) == 0))
         return launch_with_lds(&sweep_kernel<KL, MASKED, true, true>, grid, lds, p, stream);
     if (vec4) return launch_with_lds(&sweep_kernel<KL, MASKED, true>, grid, lds, p, stream);

@@ -671,6 +671,40 @@ def test_split_bf16_filter_loses_nothing(lib, kind, d):
         assert torch.equal(ta[name_], tb[name_]), name_
 
 
+@pytest.mark.parametrize("N,d,k,offset", [(30_000, 20, 8, 1.0e4), (26_000, 3, 4, 3.0e5), (25_000, 64, 16, 1.0e3),
+                                          (6_000, 200, 8, 1.0e3)])
+def test_common_offset_stays_out_of_the_filter(lib, N, d, k, offset):
+    """The filter's slack is a fraction of the rows' squared norms.  The split copy is taken relative to the column
+    means, so an offset shared by all rows (coordinates far from the origin, all-positive features) does not count
+    towards it; below 64 features, where the pruned sweeps otherwise multiply the rows as they are in float32, they
+    switch to the split copy when the means carry most of the norms.  Same lists and trees as with float32
+    products and as the oracle on sampled rows, and about as few pairs passed on to the exact evaluation as for
+    the same data without the offset (without the shift: every pair of every multiplied tile)."""
+    rng = np.random.default_rng(N + d)
+    centres = rng.uniform(-10, 10, size=(30, d))
+    base = centres[rng.integers(0, 30, size=N)] + rng.standard_normal((N, d))
+    shift = offset * rng.standard_normal((1, d))
+    print(f"common offset N={N} d={d} k={k} offset={offset}", flush=True)
+    per_row = {}
+    for name_, X in (("plain", base.astype(np.float32)), ("offset", (base + shift).astype(np.float32))):
+        Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+        a = lib.knn_graph(Xd, k, fp32_filter=True)
+        b = lib.knn_graph(Xd, k)
+        c = lib.knn_graph(Xd, k, prune=True)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+        rows = rng.choice(N, size=100, replace=False)
+        check_knn(X, k, b[0].cpu().numpy()[rows], b[1].cpu().numpy()[rows], rows=rows, min_exact=0.9)
+        every = lib.slhc(Xd, k, prune=False)
+        pruned = lib.slhc(Xd, k, prune=True)
+        for n_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+            assert torch.equal(every[n_], pruned[n_]), n_
+        per_row[name_] = (every["stats"]["knn_filter_survivors"] / N, pruned["stats"]["knn_filter_survivors"] / N)
+        print(f"  {name_}: pairs passed per row, every tile {per_row[name_][0]:.1f}, pruned {per_row[name_][1]:.1f}", flush=True)
+    assert per_row["offset"][0] <= 3.0 * per_row["plain"][0] + 50
+    assert per_row["offset"][1] <= 3.0 * per_row["plain"][1] + 50
+
+
 def test_bf16_mfma_error_stays_within_what_the_slack_allows(lib):
     """split_slack_coefficient budgets 16 * 2^-24 of the sum of magnitudes per v_mfma_f32_32x32x16_bf16 (one unit
     per product).  Measured behaviour of the instruction: its 16 products and the accumulator are aligned to the
