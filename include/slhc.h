@@ -148,6 +148,11 @@ const char* slhc_last_error(void);              /* thread-local, never NULL  */
  * cannot enter a row's list; a pair that may enter is re-evaluated as sum_t (x_it - x_jt)^2
  * in fp32, so the reported value of (i,j) equals that of (j,i) bit for bit and duplicates are at
  * exactly 0.  A row is never its own neighbour (excluded by index, not by distance).
+ * (How many pairs reach the re-evaluation depends on the rows' squared norms against their distances.
+ * slhc_knn_graph, slhc_knn_graph_opt and slhc_slhc* multiply a copy of X taken relative to its column
+ * means, so an offset shared by all rows costs nothing; slhc_knn_graph_static, slhc_cross_1nn and
+ * slhc_fused_1nn multiply the rows as they are, and on rows whose common offset dwarfs their distances
+ * they re-evaluate most pairs: same results, far slower.  Centre such data before calling them.)
  *
  *   X         DEVICE in   [N*d]
  *   nbr_idx   DEVICE out  [N*k] row-major int32
