@@ -124,7 +124,8 @@ float split_slack_coefficient(int d);                 // the same for products a
 // X [N, d] -> the chunk-wise split copy described at SweepParams::Xq_split (d % 32 == 0)
 // `shift` (optional, [d] device floats, 16-byte aligned): the copy holds fl(x - shift)
 hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift = nullptr);
-// column means of X over a sample of its rows -> mean [d]; scratch: column_means_scratch_floats(d) device floats
+// a central value of every column of X (median of the means of 64 runs of a row sample) -> mean [d];
+// scratch: column_means_scratch_floats(d) device floats
 size_t column_means_scratch_floats(int d);
 hipError_t launch_column_means(const float* X, int N, int d, float* scratch, float* mean, hipStream_t stream);
 int split_row_stride(int d);                          // words per row of the split copy: d rounded up to whole chunks of 32

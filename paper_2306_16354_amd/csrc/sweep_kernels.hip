@@ -2167,10 +2167,12 @@ hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_
     return hipGetLastError();
 }
 
-// Column means over a sample of at most MEAN_SAMPLE evenly spaced rows, in two passes with a fixed order of
-// additions (the same vector in every run).  Any vector serves as a shift: values that are not finite are left
-// out, and a mean that is not finite or beyond 2^50 is replaced by 0, so that taking it off a finite row overflows
-// no sooner than the row's own norm does.
+// A central value of every column, from a sample of at most MEAN_SAMPLE evenly spaced rows: the sample is cut into
+// MEAN_PARTS runs, each run gives a mean, and the column's value is the median of those means (a plain mean follows
+// a single far outlier, and a shift that follows it inflates every other row's norm).  Fixed order of additions: the
+// same vector in every run.  Any vector serves as a shift: values that are not finite are left out, and a result
+// that is not finite or beyond 2^50 is replaced by 0, so that taking it off a finite row overflows no sooner than
+// the row's own norm does.
 constexpr int MEAN_SAMPLE = 16384, MEAN_PARTS = 64;
 __global__ void __launch_bounds__(256) column_sums_kernel(const float* __restrict__ X, int N, int d, int samples,
                                                           float* __restrict__ partial)
@@ -2185,16 +2187,23 @@ __global__ void __launch_bounds__(256) column_sums_kernel(const float* __restric
         const float v = X[row * d + c];
         if (fabsf(v) < __builtin_inff()) sum += v;          // false for NaN as well
     }
-    partial[(size_t)part * d + c] = sum;
+    partial[(size_t)part * d + c] = i1 > i0 ? sum / (float)(i1 - i0) : __builtin_nanf("");       // NaN: an empty run
 }
-__global__ void __launch_bounds__(256) column_means_kernel(const float* __restrict__ partial, int d, int samples,
+__global__ void __launch_bounds__(256) column_means_kernel(const float* __restrict__ partial, int d,
                                                            float* __restrict__ mean)
 {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= d) return;
-    float sum = 0.f;
-    for (int part = 0; part < MEAN_PARTS; ++part) sum += partial[(size_t)part * d + c];
-    const float m = sum / (float)samples;
+    float v[MEAN_PARTS];
+    int n = 0;
+    for (int part = 0; part < MEAN_PARTS; ++part) {
+        const float x = partial[(size_t)part * d + c];
+        if (!(fabsf(x) < __builtin_inff())) continue;       // empty run, or a mean that overflowed
+        int j = n++;
+        while (j > 0 && v[j - 1] > x) { v[j] = v[j - 1]; --j; }          // insertion sort, ascending
+        v[j] = x;
+    }
+    const float m = n == 0 ? 0.f : 0.5f * v[(n - 1) >> 1] + 0.5f * v[n >> 1];
     mean[c] = fabsf(m) <= 1.125899906842624e15f ? m : 0.f;       // 2^50; false for NaN
 }
 size_t column_means_scratch_floats(int d) { return (size_t)MEAN_PARTS * (size_t)d; }
@@ -2204,7 +2213,7 @@ hipError_t launch_column_means(const float* X, int N, int d, float* scratch, flo
     const int samples = N < MEAN_SAMPLE ? N : MEAN_SAMPLE;
     const unsigned int cblocks = (unsigned int)((d + 255) / 256);
     hipLaunchKernelGGL(column_sums_kernel, dim3(MEAN_PARTS, cblocks), dim3(256), 0, stream, X, N, d, samples, scratch);
-    hipLaunchKernelGGL(column_means_kernel, dim3(cblocks), dim3(256), 0, stream, scratch, d, samples, mean);
+    hipLaunchKernelGGL(column_means_kernel, dim3(cblocks), dim3(256), 0, stream, scratch, d, mean);
     return hipGetLastError();
 }
 

@@ -705,6 +705,28 @@ def test_common_offset_stays_out_of_the_filter(lib, N, d, k, offset):
     assert per_row["offset"][1] <= 3.0 * per_row["plain"][1] + 50
 
 
+def test_far_outlier_does_not_drag_the_shift(lib):
+    """The shift of the split copy is a median of means, not a mean: one row at 1e12 among unit-scale rows would move a
+    mean to 3e8 per column and put that into every row's norm, after which every pair passes the filter.  Same
+    lists as the entry point that multiplies the rows as they are, and about as few pairs passed as without the row."""
+    rng = np.random.default_rng(77)
+    N, d, k = 3000, 40, 6
+    base = rng.standard_normal((N, d)).astype(np.float32)
+    with_outlier = np.concatenate([base, np.full((1, d), 1.0e12, dtype=np.float32)])
+    per_row = []
+    for X in (base, with_outlier):
+        Xd = torch.from_numpy(np.ascontiguousarray(X)).cuda()
+        n = X.shape[0]
+        plain = (torch.empty((n, k), dtype=torch.int32, device="cuda"), torch.empty((n, k), dtype=torch.float32, device="cuda"))
+        lib.knn_graph_static(Xd, k, plain)
+        got = lib.knn_graph(Xd, k)
+        torch.cuda.synchronize()
+        assert torch.equal(plain[0], got[0]) and torch.equal(plain[1], got[1])
+        per_row.append(lib.slhc(Xd, k, prune=False)["stats"]["knn_filter_survivors"] / n)
+    print(f"  pairs passed per row: {per_row[0]:.1f} without the outlier, {per_row[1]:.1f} with it", flush=True)
+    assert per_row[1] <= 2.0 * per_row[0] + 20
+
+
 def test_bf16_mfma_error_stays_within_what_the_slack_allows(lib):
     """split_slack_coefficient budgets 16 * 2^-24 of the sum of magnitudes per v_mfma_f32_32x32x16_bf16 (one unit
     per product).  Measured behaviour of the instruction: its 16 products and the accumulator are aligned to the
