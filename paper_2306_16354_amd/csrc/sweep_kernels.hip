@@ -52,6 +52,9 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 #ifndef SLHC_STREAM_SPLIT_MIN_D
 #define SLHC_STREAM_SPLIT_MIN_D 0   // the streaming kernel multiplies the split copy, where there is one, from this many features on
 #endif
+#ifndef SLHC_SEGMENT_HANDICAP
+#define SLHC_SEGMENT_HANDICAP 1.18   // see sweep_segments_for
+#endif
 #ifndef SLHC_SCAN_AHEAD
 #define SLHC_SCAN_AHEAD 4      // groups of 64 scan positions whose lower bounds a pruned sweep reads at once (see next_scan)
 #endif
@@ -2377,7 +2380,7 @@ int sweep_segments_for(int m, int NC, bool fast_unsegmented)
     const double bar = 0.9 * best_cost;
     for (int seg = 2; seg <= 16 && ntiles / seg >= 16; ++seg) {
         double cost = passes(seg) * (1.0 + 0.004 * seg);   // per-item set-up and the merge of the minima
-        if (fast_unsegmented) cost *= 1.18;
+        if (fast_unsegmented) cost *= SLHC_SEGMENT_HANDICAP;
         if (cost < bar && cost < best_cost) { best = seg; best_cost = cost; }
     }
     return best;
