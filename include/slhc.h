@@ -124,6 +124,13 @@ typedef struct slhc_stats {
                            pair that may enter a list is re-evaluated in float32 either way, so the
                            outputs are the same bit for bit.                                     */
 
+#define SLHC_ONE_SHIFT 64u     /* with SLHC_PRUNE only; a testing and tuning aid.  The pruned k-NN sweep otherwise runs
+                           as two launches where its products come from split bfloat16 halves (64 to 128
+                           features): the candidate tiles of a row panel's own region (a run of tiles whose
+                           centres stay close: a cluster) from a copy taken relative to a centre of that
+                           region, which keeps the cluster's position out of the filter's slack, then the
+                           other tiles from the copy relative to the column means.  With this flag: one launch,
+                           all tiles from the latter copy.  Same outputs.                              */
 #define SLHC_PANEL_ORDER 32u   /* A testing and tuning aid.  Every-tile sweeps of many query panels (from 4 panels
                            per workgroup slot on, d <= 128) otherwise hand out their work range by range:
                            the candidate tiles are cut into ranges of about 2 MiB, all workgroups sweep the

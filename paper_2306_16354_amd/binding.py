@@ -38,6 +38,7 @@ SLHC_SPLIT_SCANS = 4
 SLHC_NO_TILE_TABLE = 8
 SLHC_FP32_FILTER = 16
 SLHC_PANEL_ORDER = 32
+SLHC_ONE_SHIFT = 64
 SLHC_STATIC_MAX_ROWS = 1048576
 
 
@@ -134,7 +135,8 @@ def slhc_workspace_bytes(N, d, k):
     return out.value
 
 
-def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32_filter=False, panel_order=False):
+def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32_filter=False, panel_order=False,
+              one_shift=False):
     """slhc_knn_graph (prune=False) / slhc_knn_graph_opt with SLHC_PRUNE: returns (idx int32 [N,k],
     dist float32 [N,k]) device tensors.  Asynchronous on the current stream."""
     X = _device_matrix(X)
@@ -150,7 +152,8 @@ def knn_graph(X, k, out=None, workspace=None, prune=False, tile_table=True, fp32
     _check(lib.slhc_knn_graph_opt(X.data_ptr(), N, d, k, idx.data_ptr(), dist.data_ptr(),
                                   workspace.data_ptr(), workspace.numel(), _stream(),
                                   (SLHC_PRUNE if prune else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
-                                  (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0)))
+                                  (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0) |
+                                  (SLHC_ONE_SHIFT if one_shift else 0)))
     return idx, dist
 
 
@@ -223,7 +226,7 @@ def cross_1nn(X, colour, rows=None, m=None):
 
 
 def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_scans=False, tile_table=True,
-         fp32_filter=False, panel_order=False):
+         fp32_filter=False, panel_order=False, one_shift=False):
     """slhc_slhc: exact single-linkage MST and dendrogram.  Returns a dict of device tensors
     (mst_src, mst_dst, mst_w, children [N-1,2], heights, sizes) plus ``stats`` (a dict).
     ``workspace`` and ``out`` (a dict from an earlier call) may be passed in to reuse memory.
@@ -257,7 +260,8 @@ def slhc(X, k, workspace=None, out=None, prune=True, split_rounds=False, split_s
                                  workspace.numel(), _stream(),
                                  (SLHC_PRUNE if prune else 0) | (SLHC_SPLIT_ROUNDS if split_rounds else 0) |
                                  (SLHC_SPLIT_SCANS if split_scans else 0) | (0 if tile_table else SLHC_NO_TILE_TABLE) |
-                                 (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0)))
+                                 (SLHC_FP32_FILTER if fp32_filter else 0) | (SLHC_PANEL_ORDER if panel_order else 0) |
+                                  (SLHC_ONE_SHIFT if one_shift else 0)))
     out["stats"] = {name: getattr(st, name) for name, _ in _Stats._fields_ if not name.startswith("reserved")}
     return out
 

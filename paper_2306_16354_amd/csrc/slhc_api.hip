@@ -143,6 +143,60 @@ int pad_columns(const float* X, int64_t N, int32_t d, int32_t dw, float* out, hi
     return SLHC_OK;
 }
 
+// Regions of the reordered copy: runs of consecutive tiles whose centres stay close.  boundary[t] = 1 when tile t
+// starts a region: the first tile, a tile without valid rows (radius < 0) or next to one, or a tile whose centre lies
+// farther from the previous tile's than twice the larger of the two radii.
+__global__ void __launch_bounds__(256) k_region_boundaries(const float* __restrict__ tile_c, const float* __restrict__ tile_r,
+                                                           int T, int d, int32_t* __restrict__ boundary)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    int b = 1;
+    if (t > 0) {
+        const float r0 = tile_r[t - 1], r1 = tile_r[t];
+        if (r0 >= 0.f && r1 >= 0.f) {
+            const float* c0 = tile_c + (size_t)(t - 1) * d;
+            const float* c1 = tile_c + (size_t)t * d;
+            float s2 = 0.f;
+            for (int j = 0; j < d; ++j) { const float e = c1[j] - c0[j]; s2 = __builtin_fmaf(e, e, s2); }
+            const float reach = 2.f * fmaxf(r0, r1);
+            b = (s2 <= reach * reach) ? 0 : 1;           // NaN: a boundary
+        }
+    }
+    boundary[t] = b;
+}
+// region[t] = number of the region tile t lies in, first[t] = the first tile of that region (one workgroup)
+__global__ void __launch_bounds__(1024) k_region_scan(const int32_t* __restrict__ boundary, int T, int32_t* __restrict__ region,
+                                                      int32_t* __restrict__ first)
+{
+    __shared__ int cnt[1024], last[1024];
+    const int tid = threadIdx.x;
+    const int per = (T + 1023) / 1024;
+    const int t0 = tid * per < T ? tid * per : T, t1 = t0 + per < T ? t0 + per : T;
+    int c = 0, l = -1;
+    for (int t = t0; t < t1; ++t) if (boundary[t]) { ++c; l = t; }
+    cnt[tid] = c; last[tid] = l;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        const int cv = tid >= off ? cnt[tid - off] : 0, lv = tid >= off ? last[tid - off] : -1;
+        __syncthreads();
+        cnt[tid] += cv; last[tid] = last[tid] > lv ? last[tid] : lv;
+        __syncthreads();
+    }
+    int rc = tid > 0 ? cnt[tid - 1] : 0, rl = tid > 0 ? last[tid - 1] : -1;
+    for (int t = t0; t < t1; ++t) {
+        if (boundary[t]) { ++rc; rl = t; }
+        region[t] = rc > 0 ? rc - 1 : 0;
+        first[t] = rl >= 0 ? rl : 0;
+    }
+}
+// h[i] = +inf for the padding rows of the reordered copy (perm[i] < 0)
+__global__ void __launch_bounds__(256) k_mask_padding(const int32_t* __restrict__ perm, int n, float* __restrict__ h)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n && perm[i] < 0) h[i] = __builtin_inff();
+}
+
 // out[0], out[1] = sums of a[i] and b[i] over at most 16384 evenly spaced i < n (one workgroup, fixed order)
 __global__ void __launch_bounds__(256) k_sample_sums(const float* __restrict__ a, const float* __restrict__ b, int n,
                                                      float* __restrict__ out)
@@ -285,6 +339,10 @@ bool split_products_pruned_ok(int32_t d) { return d % 32 == 0 && d >= 64 && d <=
 struct OrderWs {
     float *Xp, *hp, *pdist, *sample, *Xs, *hs, *tile_c, *tile_r, *gap_ws, *tile_gap, *n_w, *n_heights;
     float *Xs_split, *hs_split;      // the reordered copy in split bfloat16 halves and its half norms (nullptr: d does not allow it)
+    // a second split copy, every tile relative to the centre of the first tile of its region, with its half norms;
+    // region number, first tile and boundary flag per tile (see run_knn; nullptr: the pruned sweeps keep float32 products)
+    float *Xs_local, *hs_local;
+    int32_t *tile_region, *tile_first, *tile_boundary;
     int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *tile_list, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
     uint32_t *tmp_a, *tmp_b, *tmp_c;
@@ -308,6 +366,12 @@ struct OrderWs {
         Xs = c.take<float>(nm * d); hs = c.take<float>(nm);
         Xs_split = nullptr; hs_split = nullptr;
         if (split_products_ok(d)) { Xs_split = c.take<float>(nm * d); hs_split = c.take<float>(nm); }
+        Xs_local = nullptr; hs_local = nullptr; tile_region = nullptr; tile_first = nullptr; tile_boundary = nullptr;
+        if (split_products_pruned_ok(d)) {
+            Xs_local = c.take<float>(nm * d); hs_local = c.take<float>(nm);
+            tile_region = c.take<int32_t>((size_t)Tmax); tile_first = c.take<int32_t>((size_t)Tmax);
+            tile_boundary = c.take<int32_t>((size_t)Tmax);
+        }
         tile_c = c.take<float>((size_t)Tmax * d); tile_r = c.take<float>((size_t)Tmax);
         int grid = slhc::sweep_grid_limit();
         if (grid < 1) grid = 512;
@@ -715,6 +779,32 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
 #ifdef SLHC_PHASE_TIMERS
         p.phase_cycles = ws.counters + 16;
 #endif
+    }
+    if (prune && ws.order_split_ready && ws.order.Xs_local && !(flags & SLHC_ONE_SHIFT)) {
+        // Two launches (see SweepParams::region_mode).  The rows of a cluster share their centre as an offset that
+        // the common shift does not remove, and the filter's slack is a fraction of the squared norms: 1M x 128
+        // passes 660 pairs per row on to the exact evaluation for 217 list updates.  The row order keeps a cluster
+        // in consecutive tiles, so the tiles are cut into regions where consecutive centres part (farther than
+        // twice the larger radius), a second split copy takes every tile relative to the centre of its region's
+        // first tile, and the first launch multiplies that copy for the tiles of the panel's own region; the
+        // second launch starts from those lists and visits the other tiles with the common shift.
+        const OrderWs& o = ws.order;
+        const int T = (o.Ns + 127) / 128;
+        hipLaunchKernelGGL(k_region_boundaries, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, stream, o.tile_c, o.tile_r, T, d,
+                           o.tile_boundary);
+        hipLaunchKernelGGL(k_region_scan, dim3(1), dim3(1024), 0, stream, o.tile_boundary, T, o.tile_region, o.tile_first);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_local, stream, o.tile_c, o.tile_first));
+        HIP_TRY(slhc::launch_half_norms(o.Xs, o.Ns, d, o.hs_local, stream, nullptr, true, o.tile_c, o.tile_first));
+        hipLaunchKernelGGL(k_mask_padding, dim3((unsigned)((o.Ns + 255) / 256)), dim3(256), 0, stream, o.perm, o.Ns, o.hs_local);
+        HIP_TRY(hipGetLastError());
+        slhc::SweepParams own = p;
+        own.Xq_split = own.Xc_split = o.Xs_local; own.hq_split = own.hc_split = o.hs_local;
+        own.tile_region = o.tile_region; own.region_mode = 1;
+        HIP_TRY(slhc::launch_knn_sweep(own, stream));
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, p.panel_counter, 2);
+        HIP_TRY(hipGetLastError());
+        p.tile_region = o.tile_region; p.region_mode = 2;
     }
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));

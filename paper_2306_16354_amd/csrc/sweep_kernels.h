@@ -28,6 +28,15 @@ struct SweepParams {
     const float* Xc_split;
     const float* hq_split;
     const float* hc_split;
+    // Pruned k-NN sweeps of a self-join in the reordered copy (own_tile_first) may run as two launches over the
+    // same output lists.  tile_region [tiles]: a region number per candidate tile (= per query panel).
+    // region_mode 1: a panel only visits the tiles of its own region, for which the caller passes a split copy
+    // taken relative to a vector of that region's own (rows of one cluster share their centre as an offset, which
+    // a shift common to all rows does not remove: local coordinates keep it out of the filter's slack);
+    // region_mode 2: a panel starts from the lists the first launch wrote and visits the other tiles only,
+    // with the split copy relative to the common shift.  0: one launch, all tiles.
+    const int32_t* tile_region;
+    int region_mode;
     int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
     const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)
@@ -123,7 +132,9 @@ float filter_slack_coefficient(int d);
 float split_slack_coefficient(int d);                 // the same for products accumulated from split bf16 halves
 // X [N, d] -> the chunk-wise split copy described at SweepParams::Xq_split (d % 32 == 0)
 // `shift` (optional, [d] device floats, 16-byte aligned): the copy holds fl(x - shift)
-hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift = nullptr);
+// `shift_tile` (optional, with shift): shift is a matrix [*, d] and the rows of tile t = row / 128 take its row shift_tile[t]
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift = nullptr,
+                             const int* shift_tile = nullptr);
 // a central value of every column of X (median of the means of 64 runs of a row sample) -> mean [d];
 // scratch: column_means_scratch_floats(d) device floats
 size_t column_means_scratch_floats(int d);
@@ -132,7 +143,7 @@ int split_row_stride(int d);                          // words per row of the sp
 // `nonfinite` (optional device word, zero at launch): set to 1 when a row's squared norm is not a finite float32
 // `shift` (optional): the norms of fl(x - shift), as for launch_split_bf16
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite = nullptr,
-                             bool split_slack = false, const float* shift = nullptr);
+                             bool split_slack = false, const float* shift = nullptr, const int* shift_tile = nullptr);
 // Launches the register-only fp32 MFMA loop (2 workgroups per CU, `iters` x 16 instructions per wavefront);
 // *flop receives the floating-point operations of the launch.  `sink`: one device float.
 hipError_t launch_mfma_probe(int iters, float* sink, hipStream_t stream, double* flop);

@@ -155,12 +155,13 @@ __device__ inline float group8_sqdist(const float* __restrict__ a_, const float*
 // A row whose squared norm is not a finite float32 (NaN or infinity among its values, or overflow) sets
 // *nonfinite (optional) to 1.
 // `shift` (optional, [d], 16-byte aligned with VEC4): the norms are those of the rows fl(x - shift), the rows the
-// split copy holds (see split_bf16_kernel).
+// split copy holds (see split_bf16_kernel); with `shift_tile` a matrix of shifts, one row of it per tile of 128 rows.
 template <bool VEC4>
 __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict__ X, int N, int d,
                                                         float scale, float* __restrict__ hn,
                                                         unsigned int* __restrict__ nonfinite,
-                                                        const float* __restrict__ shift)
+                                                        const float* __restrict__ shift_,
+                                                        const int* __restrict__ shift_tile)
 {
     const int lane16 = threadIdx.x & 15;
     const long long row = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 4;
@@ -168,6 +169,8 @@ __global__ void __launch_bounds__(256) half_norm_kernel(const float* __restrict_
     float s = 0.f;
     if (active) {
         const float* x = X + (size_t)row * d;
+        // (shift_tile: the rows of tile t = row / 128 take row shift_tile[t] of the matrix `shift`)
+        const float* shift = (shift_ && shift_tile) ? shift_ + (size_t)shift_tile[row >> 7] * d : shift_;
         if (VEC4) {
             for (int t = 4 * lane16; t < d; t += 64) {
                 v4f v = *reinterpret_cast<const v4f*>(x + t);
@@ -1024,6 +1027,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
     // workgroup that took the predecessor is running and waits only for still earlier items, so every wait
     // ends; it is bounded all the same, and a wait that runs out is reported in carry_fault).
     constexpr bool CAN_CARRY = !PRUNE;
+    constexpr bool REGIONS = PRUNE && !MASKED;          // p.region_mode applies
     const int ncarry = (CAN_CARRY && p.carry_ranges > 1 && p.carry_ws != nullptr) ? p.carry_ranges : 1;
     const int nitems = ncarry > 1 ? npanels * ncarry : (listed_panels ? p.panel_list_n : npanels) * nparts;
     unsigned int* hand_out = ncarry > 1 ? p.carry_ws : (PRUNE ? p.panel_counter : nullptr);
@@ -1077,9 +1081,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         }
         // a panel without a single query has nothing to do (every wavefront reads the same qid)
         if (!__any(qid[lane] >= 0 || qid[lane + 64] >= 0)) continue;
-        if (CAN_CARRY && crange > 0) {
+        // Pruned k-NN sweeps in two launches (p.region_mode, see SweepParams): the second starts from the lists the
+        // first wrote, like an item of a later range
+        const bool lists_in = (CAN_CARRY && crange > 0) || (REGIONS && p.region_mode == 2 && p.tile_region != nullptr && panel < ntiles);
+        if (lists_in) {
             // the lists item (crange - 1, panel) left in the output arrays, and the thresholds they imply
-            if (tid == 0) {
+            if (CAN_CARRY && tid == 0) {
                 int spins = 0;
                 while (__hip_atomic_load(p.carry_ws + 2 + panel, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (unsigned int)crange) {
                     __builtin_amdgcn_s_sleep(16);
@@ -1198,9 +1205,13 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         // (a row of the table knows nothing of colours: tiles in the colour of all the panel's queries are
         // sorted out where the bounds are read)
         const bool own_colour_test = MASKED && table_row && p.tile_colour != nullptr && panel_colour >= 0;
+        // p.region_mode 1: only the candidate tiles of the panel's own region are of use; 2: only the others
+        const int region_mode = (REGIONS && p.tile_region != nullptr && panel < ntiles) ? p.region_mode : 0;
+        const int my_region = region_mode ? p.tile_region[panel] : 0;
         auto gap_of = [&](int t) -> float {
             float g = gap[t];
             if (own_colour_test && p.tile_colour[t] == panel_colour) g = __builtin_nanf("");
+            if (REGIONS && region_mode && ((p.tile_region[t] == my_region) != (region_mode == 1))) g = __builtin_nanf("");
             return g;
         };
         PHASE_MARK(1);
@@ -1270,9 +1281,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         // thresholds tighten early and the gap test skips more of what follows.
         // `scan` indices count positions in that order; every lane of every wavefront evaluates
         // next_scan on the same data, so its result is workgroup-uniform.
-        const int own_tile = (PRUNE && !MASKED && p.own_tile_first && panel < ntiles) ? panel : -1;
+        // (the second launch of a sweep by regions has no use for the panel's own tile; its scan still starts there)
+        const bool rows_in_own_tile = PRUNE && !MASKED && p.own_tile_first && panel < ntiles;
+        const int own_tile = (rows_in_own_tile && !(REGIONS && region_mode == 2)) ? panel : -1;
         int centre = 0;
         if (own_tile >= 0) centre = own_tile;
+        else if (rows_in_own_tile) centre = panel;
         else if (aligned) centre = panel < ntiles ? panel : 0;
         else if (prune && MASKED && qid[0] >= 0) centre = qid[0] / BN;
         if (centre >= ntiles) centre = ntiles - 1;
@@ -1360,18 +1374,6 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
         };
 
-        v16f acc[4];
-        int scan_from = 0;                 // scan indices below this one are done or skipped
-        int tile = own_tile;
-        if (own_tile < 0) {
-            const int first = next_scan(0, __builtin_inff());
-            tile = tile_of(first);
-            scan_from = first + 1;
-        }
-        float ahead_gap = __builtin_nanf("");          // lower bound of scan position scan_from + lane (NaN: none)
-        if (prune) ahead_gap = scan_from + lane < nscan ? gap_of(scan_tile(scan_from + lane)) : __builtin_nanf("");
- if (tile < ntiles) gload(tile, 0);
-        PHASE_MARK(2);
         // largest threshold of this wavefront's 32 queries, from their bounds: thr = 2 (h_q - bound)
         auto refresh_wave_thr = [&]() {
             float t = (my_qrow >= 0) ? 2.f * (hqs[my_q_local] - bound) : 0.f;
@@ -1388,6 +1390,27 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 8));
             wave_thr_max = fmaxf(wave_thr_max, __shfl_xor(wave_thr_max, 16));
         };
+        // a launch that starts from lists already written: their thresholds decide from the first tile on
+        float first_thr = __builtin_inff();
+        if (REGIONS && lists_in) {
+            refresh_wave_thr();
+            if (lane == 0) { L.wmax[wave] = wave_thr_max; L.wmax[4 + wave] = wave_thr_max; }
+            __syncthreads();
+            first_thr = fmaxf(fmaxf(L.wmax[0], L.wmax[1]), fmaxf(L.wmax[2], L.wmax[3]));
+        }
+
+        v16f acc[4];
+        int scan_from = 0;                 // scan indices below this one are done or skipped
+        int tile = own_tile;
+        if (own_tile < 0) {
+            const int first = next_scan(0, first_thr);
+            tile = tile_of(first);
+            scan_from = first + 1;
+        }
+        float ahead_gap = __builtin_nanf("");          // lower bound of scan position scan_from + lane (NaN: none)
+        if (prune) ahead_gap = scan_from + lane < nscan ? gap_of(scan_tile(scan_from + lane)) : __builtin_nanf("");
+ if (tile < ntiles) gload(tile, 0);
+        PHASE_MARK(2);
         // split scans: this query's slot in p.out_key, the entry last published there, the word last read
         int part_slot = 0;
         unsigned long long part_published = LIST_SENTINEL, part_seen = LIST_SENTINEL;
@@ -1545,7 +1568,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             }
 
             // ---- first tile of a 1-NN panel: seed the thresholds (see seed_block) ----
-            if (k == 1 && step == 0 && crange == 0) {
+            if (k == 1 && step == 0 && !lists_in) {
                 const int seed_tag = MASKED ? my_qcol : (p.exclude_self ? my_qrow : -1);
                 SeedPick pick{-__builtin_inff(), -1};
                 pick = seed_block<KL, MASKED>(acc[0], 0, pick, seed_tag, col0, tpar, N);
@@ -1607,7 +1630,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                     // First tile of a k-NN panel (k > 1): fill the lists from its best candidates (see
                     // seed_range).  Later tiles were tried too and gain nothing: what passes there are
                     // mostly real list updates.
-                    if (!MASKED && k > 1 && step == 0 && crange == 0) {
+                    if (!MASKED && k > 1 && step == 0 && !lists_in) {
                         SeedRange range{__builtin_inff(), -__builtin_inff()};
                         range = seed_range(acc[0], range);
                         range = seed_range(acc[1], range);
@@ -2117,7 +2140,8 @@ float split_slack_coefficient(int d)
 // distance does not change when both rows are translated, and the filter's slack is a fraction of the rows' squared
 // norms: with the column means taken off, a common offset of the data no longer counts towards it.
 __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict__ X, long long octets, int d, int stride,
-                                                         float* __restrict__ Xsplit, const float* __restrict__ shift)
+                                                         float* __restrict__ Xsplit, const float* __restrict__ shift_,
+                                                         const int* __restrict__ shift_tile)
 {
     const long long o = (long long)blockIdx.x * 256 + threadIdx.x;
     if (o >= octets) return;
@@ -2129,7 +2153,8 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict
     v4f a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
     if (8 * oct + 4 <= d) a = *reinterpret_cast<const v4f*>(src);          // d is a multiple of 4
     if (8 * oct + 8 <= d) b = *reinterpret_cast<const v4f*>(src + 4);
-    if (shift) {
+    if (shift_) {
+        const float* shift = shift_tile ? shift_ + (size_t)shift_tile[row >> 7] * d : shift_;
         if (8 * oct + 4 <= d) a -= *reinterpret_cast<const v4f*>(shift + 8 * oct);
         if (8 * oct + 8 <= d) b -= *reinterpret_cast<const v4f*>(shift + 8 * oct + 4);
     }
@@ -2148,25 +2173,26 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(const float* __restrict
 
 int split_row_stride(int d) { return (d + KC - 1) / KC * KC; }
 
-hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift)
+hipError_t launch_split_bf16(const float* X, int N, int d, float* Xsplit, hipStream_t stream, const float* shift,
+                             const int* shift_tile)
 {
     if (d % 4 != 0 || ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Xsplit) | reinterpret_cast<uintptr_t>(shift)) & 15) != 0)
         return hipErrorInvalidValue;
     const int stride = split_row_stride(d);
     const long long octets = (long long)N * (stride >> 3);
-    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, stride, Xsplit, shift);
+    hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned int)((octets + 255) / 256)), dim3(256), 0, stream, X, octets, d, stride, Xsplit, shift, shift_tile);
     return hipGetLastError();
 }
 
 hipError_t launch_half_norms(const float* X, int N, int d, float* hn, hipStream_t stream, unsigned int* nonfinite,
-                             bool split_slack, const float* shift)
+                             bool split_slack, const float* shift, const int* shift_tile)
 {
     const float scale = 0.5f * (1.0f - (split_slack ? split_slack_coefficient(d) : filter_slack_coefficient(d)));
     const long long threads = (long long)N * 16;
     const int blocks = (int)((threads + 255) / 256);
     const bool vec4 = (d % 4 == 0) && (((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(shift)) & 15) == 0);
-    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift);
-    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift);
+    if (vec4) hipLaunchKernelGGL(half_norm_kernel<true>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift, shift_tile);
+    else hipLaunchKernelGGL(half_norm_kernel<false>, dim3(blocks), dim3(256), 0, stream, X, N, d, scale, hn, nonfinite, shift, shift_tile);
     return hipGetLastError();
 }
 

@@ -705,6 +705,51 @@ def test_common_offset_stays_out_of_the_filter(lib, N, d, k, offset):
     assert per_row["offset"][1] <= 3.0 * per_row["plain"][1] + 50
 
 
+@pytest.mark.parametrize("kind", ["blobs", "one_cluster", "tiny_clusters", "uniform", "chain"])
+@pytest.mark.parametrize("d", [64, 100, 128])
+def test_pruned_knn_by_regions_is_identical(lib, kind, d):
+    """From 64 to 128 features the pruned k-NN sweep runs as two launches: the tiles of a panel's own region (a run
+    of tiles of the row order whose centres stay close) from a split copy relative to a centre of that region,
+    then all other tiles, starting from the lists of the first launch, from the copy relative to the column
+    means.  Only the filter's slack differs, so the lists must equal, bit for bit, those of the single launch
+    (SLHC_ONE_SHIFT), of the every-tile sweep and of the entry point that never reorders or shifts, on data with
+    one region, with regions of a tile or two, with none to speak of, and with clusters strung along a line so
+    that a region's first tile lies far from its last."""
+    rng = np.random.default_rng(len(kind) * 100 + d)
+    N = int(rng.integers(6000, 14000))
+    k = int(rng.choice([1, 7, 32]))
+    if kind == "blobs":
+        centres = rng.uniform(-40, 40, size=(12, d))
+        X = centres[rng.integers(0, 12, size=N)] + rng.standard_normal((N, d))
+    elif kind == "one_cluster":
+        X = 300.0 + rng.standard_normal((N, d))
+    elif kind == "tiny_clusters":
+        centres = rng.uniform(-500, 500, size=(N // 40, d))
+        X = centres[rng.integers(0, N // 40, size=N)] + 0.05 * rng.standard_normal((N, d))
+    elif kind == "uniform":
+        X = rng.uniform(-1, 1, size=(N, d))
+    else:
+        t = rng.uniform(0, 400, size=(N, 1))
+        X = t * np.ones((1, d)) / np.sqrt(d) + 0.5 * rng.standard_normal((N, d))
+    X = np.ascontiguousarray(X.astype(np.float32))
+    Xd = torch.from_numpy(X).cuda()
+    print(f"pruned k-NN by regions: {kind} N={N} d={d} k={k}", flush=True)
+    plain = (torch.empty((N, k), dtype=torch.int32, device="cuda"), torch.empty((N, k), dtype=torch.float32, device="cuda"))
+    lib.knn_graph_static(Xd, k, plain)
+    two = lib.knn_graph(Xd, k, prune=True)
+    one = lib.knn_graph(Xd, k, prune=True, one_shift=True)
+    torch.cuda.synchronize()
+    assert torch.equal(plain[0], two[0]) and torch.equal(plain[1], two[1])
+    assert torch.equal(plain[0], one[0]) and torch.equal(plain[1], one[1])
+    a = lib.slhc(Xd, min(k, 16), prune=True)
+    b = lib.slhc(Xd, min(k, 16), prune=True, one_shift=True)
+    c = lib.slhc(Xd, min(k, 16), prune=False)
+    for name_ in ("mst_src", "mst_dst", "mst_w", "children", "heights", "sizes"):
+        assert torch.equal(a[name_], b[name_]) and torch.equal(a[name_], c[name_]), name_
+    print(f"  pairs passed per row: {a['stats']['knn_filter_survivors'] / N:.1f} by regions, "
+          f"{b['stats']['knn_filter_survivors'] / N:.1f} in one launch", flush=True)
+
+
 def test_far_outlier_does_not_drag_the_shift(lib):
     """The shift of the split copy is a median of means, not a mean: one row at 1e12 among unit-scale rows would move a
     mean to 3e8 per column and put that into every row's norm, after which every pair passes the filter.  Same
