@@ -367,7 +367,7 @@ struct OrderWs {
         Xs_split = nullptr; hs_split = nullptr;
         if (split_products_ok(d)) { Xs_split = c.take<float>(nm * d); hs_split = c.take<float>(nm); }
         Xs_local = nullptr; hs_local = nullptr; tile_region = nullptr; tile_first = nullptr; tile_boundary = nullptr;
-        if (split_products_pruned_ok(d)) {
+        if (split_products_ok(d) && d <= 128) {
             Xs_local = c.take<float>(nm * d); hs_local = c.take<float>(nm);
             tile_region = c.take<int32_t>((size_t)Tmax); tile_first = c.take<int32_t>((size_t)Tmax);
             tile_boundary = c.take<int32_t>((size_t)Tmax);
@@ -413,6 +413,7 @@ struct KnnWs {
     bool split_ready = false;        // filled in this call
     bool order_split_ready = false;  // likewise the split copy of the reordered rows
     bool offset_heavy = false;       // the rows' norms are mostly a common offset (see run_knn): split products everywhere
+    bool order_split_connect = false;   // the pruned connection sweeps multiply the split copy of the reordered rows too
     size_t bytes;
     KnnWs(void* ws, int64_t N, int32_t d, bool with_order, int32_t k = 0)
     {
@@ -745,12 +746,17 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
     if (prune) {
         const OrderWs& o = ws.order;
         p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-        if (o.Xs_split && ws.hn_split && (split_products_pruned_ok(d) || ws.offset_heavy) && !(flags & SLHC_FP32_FILTER)) {
+        if (o.Xs_split && ws.hn_split && (split_products_pruned_ok(d) || ws.offset_heavy || (o.Xs_local && !(flags & SLHC_ONE_SHIFT))) &&
+            !(flags & SLHC_FP32_FILTER)) {
             // the reordered copy in split halves too; its half norms are those of the rows (padding: +inf)
             HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_split, stream, ws.shift));
             HIP_TRY(slhc::order_gather_f32(ws.hn_split, o.perm, o.Ns, (int)N, __builtin_inff(), o.hs_split, stream));
             p.Xq_split = p.Xc_split = o.Xs_split; p.hq_split = p.hc_split = o.hs_split;
             ws.order_split_ready = true;
+            // (at 32 features the connection sweeps keep float32 products unless the data has a large common offset:
+            // the wider filter costs them more than the multiplies save; the k-NN sweep, in local coordinates for the
+            // tiles that matter, gains)
+            ws.order_split_connect = split_products_pruned_ok(d) || ws.offset_heavy;
         }
         p.q_out_row = o.perm; p.c_id = o.perm;
         p.tile_c = o.tile_c; p.tile_r = o.tile_r; p.gap_ws = o.gap_ws;
@@ -1589,7 +1595,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
                     if (h_cnt[6] < 0 || h_cnt[6] > (o.Ns + 127) / 128) { set_err("bad count of queried tiles %d", h_cnt[6]); return SLHC_INTERNAL; }
                     p.panel_list = o.tile_list; p.panel_list_n = h_cnt[6];
                     p.Xq = p.Xc = o.Xs; p.hq = p.hc = o.hs; p.NQ = p.NC = o.Ns;
-                    if (kws.order_split_ready) { p.Xq_split = p.Xc_split = o.Xs_split; p.hq_split = p.hc_split = o.hs_split; }
+                    if (kws.order_split_connect) { p.Xq_split = p.Xc_split = o.Xs_split; p.hq_split = p.hc_split = o.hs_split; }
                     p.qcolour = p.ccolour = o.colour_s;
                     p.qslot = o.qslot;
                     p.c_id = o.perm;

@@ -2211,29 +2211,45 @@ __global__ void __launch_bounds__(256) column_sums_kernel(const float* __restric
     const int part = blockIdx.x;
     const int i0 = (int)((long long)part * samples / MEAN_PARTS), i1 = (int)((long long)(part + 1) * samples / MEAN_PARTS);
     float sum = 0.f;
-    for (int i = i0; i < i1; ++i) {
-        const long long row = (long long)i * N / samples;
-        const float v = X[row * d + c];
-        if (fabsf(v) < __builtin_inff()) sum += v;          // false for NaN as well
+    for (int i = i0; i < i1; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {          // eight loads in flight; the additions keep their order
+            const int iu = i + u < i1 ? i + u : i1 - 1;
+            v[u] = X[((long long)iu * N / samples) * d + c];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i + u < i1 && fabsf(v[u]) < __builtin_inff()) sum += v[u];          // false for NaN as well
     }
     partial[(size_t)part * d + c] = i1 > i0 ? sum / (float)(i1 - i0) : __builtin_nanf("");       // NaN: an empty run
 }
+// one wavefront per column: lane p holds the mean of run p and finds its rank among the valid ones by comparing with
+// all 64 (ties broken by run number); the two middle ranks give the median
 __global__ void __launch_bounds__(256) column_means_kernel(const float* __restrict__ partial, int d,
                                                            float* __restrict__ mean)
 {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= d) return;
-    float v[MEAN_PARTS];
-    int n = 0;
-    for (int part = 0; part < MEAN_PARTS; ++part) {
-        const float x = partial[(size_t)part * d + c];
-        if (!(fabsf(x) < __builtin_inff())) continue;       // empty run, or a mean that overflowed
-        int j = n++;
-        while (j > 0 && v[j - 1] > x) { v[j] = v[j - 1]; --j; }          // insertion sort, ascending
-        v[j] = x;
+    static_assert(MEAN_PARTS == 64, "one lane per run");
+    const int lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int cc = c < d ? c : d - 1;                    // whole wavefronts stay in step; the surplus ones store nothing
+    const float x = partial[(size_t)lane * d + cc];
+    const bool valid = fabsf(x) < __builtin_inff();      // not an empty run, not a mean that overflowed
+    const int n = __popcll(__ballot(valid));
+    int rank = 0;
+    for (int q = 0; q < 64; ++q) {
+        const float y = __shfl(x, q);
+        const bool yvalid = __shfl((int)valid, q) != 0;
+        if (yvalid && (y < x || (y == x && q < lane))) ++rank;
     }
-    const float m = n == 0 ? 0.f : 0.5f * v[(n - 1) >> 1] + 0.5f * v[n >> 1];
-    mean[c] = fabsf(m) <= 1.125899906842624e15f ? m : 0.f;       // 2^50; false for NaN
+    float pick = 0.f;
+    if (valid && n > 0) {
+        if (rank == ((n - 1) >> 1)) pick += 0.5f * x;
+        if (rank == (n >> 1)) pick += 0.5f * x;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) pick += __shfl_xor(pick, o);          // two non-zero terms at most: exact order is immaterial
+    if (lane == 0 && c < d) mean[c] = fabsf(pick) <= 1.125899906842624e15f ? pick : 0.f;       // 2^50; false for NaN
 }
 size_t column_means_scratch_floats(int d) { return (size_t)MEAN_PARTS * (size_t)d; }
 hipError_t launch_column_means(const float* X, int N, int d, float* scratch, float* mean, hipStream_t stream)
@@ -2242,7 +2258,7 @@ hipError_t launch_column_means(const float* X, int N, int d, float* scratch, flo
     const int samples = N < MEAN_SAMPLE ? N : MEAN_SAMPLE;
     const unsigned int cblocks = (unsigned int)((d + 255) / 256);
     hipLaunchKernelGGL(column_sums_kernel, dim3(MEAN_PARTS, cblocks), dim3(256), 0, stream, X, N, d, samples, scratch);
-    hipLaunchKernelGGL(column_means_kernel, dim3(cblocks), dim3(256), 0, stream, scratch, d, mean);
+    hipLaunchKernelGGL(column_means_kernel, dim3((unsigned int)((d + 3) / 4)), dim3(256), 0, stream, scratch, d, mean);
     return hipGetLastError();
 }
 
