@@ -133,9 +133,9 @@ typedef struct slhc_stats {
                            all tiles from the latter copy.  Same outputs.                              */
 #define SLHC_PANEL_ORDER 32u   /* A testing and tuning aid.  Every-tile sweeps of many query panels (from 4 panels
                            per workgroup slot on, d <= 128) otherwise hand out their work range by range:
-                           the candidate tiles are cut into ranges of about 2 MiB, all workgroups sweep the
-                           same range at a time (served by every XCD's L2 instead of being fetched from
-                           memory once per panel), and a panel's lists and thresholds travel from range to
+                           the candidate tiles are cut into ranges of about 32 MiB, all workgroups sweep the
+                           same range at a time (served by the memory-side cache instead of being fetched
+                           from memory once per panel), and a panel's lists and thresholds travel from range to
                            range through the output arrays.  With this flag every workgroup sweeps all
                            candidates for one panel at a time, as the smaller launches do.  Same outputs.
                            (Going range by range, a work item waits for the item that wrote its panel's

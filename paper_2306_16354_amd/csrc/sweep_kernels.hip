@@ -1018,8 +1018,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
                      : (CAN_RANGE && p.segments > 1 && p.part_idx != nullptr && p.part_dist != nullptr) ? p.segments : 1;
     const bool listed_panels = PRUNE && MASKED && aligned && p.panel_list != nullptr;
     // Every-tile sweeps of many panels, range by range (p.carry_ranges, set by the launcher): the candidate tiles
-    // are cut into ranges of a few megabytes and the work items (range, panel) are handed out in that order, so
-    // that all workgroups in flight sweep the same range and its tiles are served by the L2 of every XCD instead
+    // are cut into ranges of 32 MiB and the work items (range, panel) are handed out in that order, so
+    // that all workgroups in flight sweep the same range and its tiles are served by the memory-side cache instead
     // of being fetched from memory once per panel.  A panel's lists travel from range to range through the
     // output arrays: item (r, panel) starts from what item (r - 1, panel) wrote, thresholds included, so no
     // list is filled twice.  Item (r - 1, panel) was handed out a whole round of panels earlier and has long
@@ -2284,8 +2284,9 @@ __global__ void __launch_bounds__(256) zero_words_kernel(unsigned int* __restric
 #ifndef SLHC_CARRY_MIN_ROUNDS
 #define SLHC_CARRY_MIN_ROUNDS 4
 #endif
-// candidate bytes per range of a sweep that goes range by range: half of an XCD's 4 MiB L2, so that the range
-// the workgroups are in and the one the first of them move on to both fit
+// candidate bytes per range of a sweep that goes range by range: a small share of the 256 MiB memory-side cache, so
+// that the range the workgroups are in and the one the first of them move on to both stay there.  (Ranges of 2 MiB,
+// half of an XCD's L2, cut the fabric traffic five times but pay more per work item than they save: measured.)
 constexpr long long CARRY_RANGE_BYTES = SLHC_CARRY_RANGE_BYTES;
 // ... and only with at least this many panels per workgroup slot: a panel's item in range r + 1 is handed out
 // that many rounds of items after its item in range r, which therefore has finished by then
