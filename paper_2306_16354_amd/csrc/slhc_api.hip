@@ -1435,6 +1435,10 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     KnnWs kws(ws.knn_ws, N, d, with_order, k);   // half norms and row order are reused by the connection sweeps
     rc = run_knn(X, N, d, k, ws.nbr_idx, ws.nbr_dist, kws, s, flags, &pruned, &ev_norm, &ev_order, &ev_knn);
     if (rc != SLHC_OK) return rc;
+    // The pinned staging of the dendrogram pass is taken here, while the k-NN sweep runs: pinning 28 bytes per row
+    // takes the host 2 to 3 ms at a million rows, which would otherwise stand between the edge sort and the pass.
+    PinnedHost pin_edges;
+    HIP_TRY(pin_edges.alloc((7 * (size_t)(N - 1) + 16) * sizeof(int32_t)));
     PinnedHost pin_surv;
     HIP_TRY(pin_surv.alloc(64));
     unsigned long long* h_surv = static_cast<unsigned long long*>(pin_surv.p);
@@ -1824,9 +1828,7 @@ int run_slhc(const float* X, int64_t N, int32_t d, int32_t k, int32_t* mst_src, 
     // host staging: end points (grouped part in list order, then the rest in edge order), keys and merge numbers
     // of the grouped part, children and sizes in the same two parts
     const size_t Rz = (size_t)R, Tz = E - Rz;
-    PinnedHost pin_edges;
-    HIP_TRY(pin_edges.alloc((5 * E + 2 * Rz + 16) * sizeof(int32_t)));
-    int32_t* h_lo = static_cast<int32_t*>(pin_edges.p);     // [R] grouped, [E - R] rest
+    int32_t* h_lo = static_cast<int32_t*>(pin_edges.p);     // [R] grouped, [E - R] rest (5 E + 2 R words in all)
     int32_t* h_hi = h_lo + E;
     int32_t* h_children = h_hi + E;                         // 2E entries, same two parts
     int32_t* h_sizes = h_children + 2 * E;
