@@ -190,6 +190,18 @@ __global__ void __launch_bounds__(1024) k_region_scan(const int32_t* __restrict_
         first[t] = rl >= 0 ? rl : 0;
     }
 }
+// last[t] = the last tile of tile t's region: the thread of a region's last tile writes the whole run
+__global__ void __launch_bounds__(256) k_region_last(const int32_t* __restrict__ boundary, const int32_t* __restrict__ first, int T,
+                                                     int32_t* __restrict__ last)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T) return;
+    if (t == T - 1 || boundary[t + 1] != 0) {
+        int u = first[t];
+        if (u < 0) u = 0;
+        for (; u <= t; ++u) last[u] = t;
+    }
+}
 // h[i] = +inf for the padding rows of the reordered copy (perm[i] < 0)
 __global__ void __launch_bounds__(256) k_mask_padding(const int32_t* __restrict__ perm, int n, float* __restrict__ h)
 {
@@ -342,7 +354,7 @@ struct OrderWs {
     // a second split copy, every tile relative to the centre of the first tile of its region, with its half norms;
     // region number, first tile and boundary flag per tile (see run_knn; nullptr: the pruned sweeps keep float32 products)
     float *Xs_local, *hs_local;
-    int32_t *tile_region, *tile_first, *tile_boundary;
+    int32_t *tile_region, *tile_first, *tile_last, *tile_boundary;
     int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *tile_list, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
     uint32_t *tmp_a, *tmp_b, *tmp_c;
@@ -366,10 +378,11 @@ struct OrderWs {
         Xs = c.take<float>(nm * d); hs = c.take<float>(nm);
         Xs_split = nullptr; hs_split = nullptr;
         if (split_products_ok(d)) { Xs_split = c.take<float>(nm * d); hs_split = c.take<float>(nm); }
-        Xs_local = nullptr; hs_local = nullptr; tile_region = nullptr; tile_first = nullptr; tile_boundary = nullptr;
+        Xs_local = nullptr; hs_local = nullptr; tile_region = nullptr; tile_first = nullptr; tile_last = nullptr; tile_boundary = nullptr;
         if (split_products_ok(d) && d <= 128) {
             Xs_local = c.take<float>(nm * d); hs_local = c.take<float>(nm);
             tile_region = c.take<int32_t>((size_t)Tmax); tile_first = c.take<int32_t>((size_t)Tmax);
+            tile_last = c.take<int32_t>((size_t)Tmax);
             tile_boundary = c.take<int32_t>((size_t)Tmax);
         }
         tile_c = c.take<float>((size_t)Tmax * d); tile_r = c.take<float>((size_t)Tmax);
@@ -799,6 +812,8 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         hipLaunchKernelGGL(k_region_boundaries, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, stream, o.tile_c, o.tile_r, T, d,
                            o.tile_boundary);
         hipLaunchKernelGGL(k_region_scan, dim3(1), dim3(1024), 0, stream, o.tile_boundary, T, o.tile_region, o.tile_first);
+        hipLaunchKernelGGL(k_region_last, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, stream, o.tile_boundary, o.tile_first, T,
+                           o.tile_last);
         HIP_TRY(hipGetLastError());
         HIP_TRY(slhc::launch_split_bf16(o.Xs, o.Ns, d, o.Xs_local, stream, o.tile_c, o.tile_first));
         HIP_TRY(slhc::launch_half_norms(o.Xs, o.Ns, d, o.hs_local, stream, nullptr, true, o.tile_c, o.tile_first));
@@ -807,6 +822,7 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         slhc::SweepParams own = p;
         own.Xq_split = own.Xc_split = o.Xs_local; own.hq_split = own.hc_split = o.hs_local;
         own.tile_region = o.tile_region; own.region_mode = 1;
+        own.tile_first = o.tile_first; own.tile_last = o.tile_last;
         HIP_TRY(slhc::launch_knn_sweep(own, stream));
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, p.panel_counter, 2);
         HIP_TRY(hipGetLastError());

@@ -37,6 +37,8 @@ struct SweepParams {
     // with the split copy relative to the common shift.  0: one launch, all tiles.
     const int32_t* tile_region;
     int region_mode;
+    const int32_t* tile_first;  // optional, with region_mode 1: first and last tile of every tile's region (regions are
+    const int32_t* tile_last;   // runs of consecutive tiles), which bound the scan
     int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
     const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)

@@ -1291,7 +1291,17 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         else if (prune && MASKED && qid[0] >= 0) centre = qid[0] / BN;
         if (centre >= ntiles) centre = ntiles - 1;
         const int with_centre = own_tile >= 0 ? 0 : 1;        // the scan itself begins at the centre tile
-        const int nscan_all = own_tile >= 0 ? ntiles - 1 : ntiles;
+        int nscan_all = own_tile >= 0 ? ntiles - 1 : ntiles;
+        if (REGIONS && region_mode == 1 && p.tile_first != nullptr && p.tile_last != nullptr) {
+            // the tiles of the panel's own region are a run around it, and the scan moves outwards from the centre:
+            // it ends where the run does (a panel of a small cluster otherwise reads its whole row of lower bounds
+            // to find nothing)
+            const int left = panel - p.tile_first[panel], right = p.tile_last[panel] - panel;
+            const int reach = left > right ? left : right;
+            const int to_r = ntiles - 1 - centre, to_l = centre;
+            const int within = (reach < to_l ? reach : to_l) + (reach < to_r ? reach : to_r) + (own_tile >= 0 ? 0 : 1);
+            if (reach >= 0 && within < nscan_all) nscan_all = within;
+        }
         // positions of this work item: part, part + nparts, ... of the panel's scan order
         const bool ranged = (CAN_RANGE && nparts > 1) || (CAN_CARRY && ncarry > 1);
         const int range_at = ncarry > 1 ? crange : part, range_count = ncarry > 1 ? ncarry : nparts;
