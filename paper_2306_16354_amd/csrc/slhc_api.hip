@@ -202,6 +202,28 @@ __global__ void __launch_bounds__(256) k_region_last(const int32_t* __restrict__
         for (; u <= t; ++u) last[u] = t;
     }
 }
+// out[row] = the smallest lower bound in row `row` of the table of tile pairs among the tiles of other regions
+// (+inf: none; NaN entries mark tiles that are never needed)
+__global__ void __launch_bounds__(256) k_region_other_min(const float* __restrict__ tile_gap, const int32_t* __restrict__ region,
+                                                          int T, float* __restrict__ out)
+{
+    __shared__ float part[256];
+    const int row = blockIdx.x;
+    const int mine = region[row];
+    const float* g = tile_gap + (size_t)row * T;
+    float m = __builtin_inff();
+    for (int t = threadIdx.x; t < T; t += 256) {
+        const float v = g[t];
+        if (region[t] != mine && v < m) m = v;          // false for NaN
+    }
+    part[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] = fminf(part[threadIdx.x], part[threadIdx.x + w]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[row] = part[0];
+}
 // h[i] = +inf for the padding rows of the reordered copy (perm[i] < 0)
 __global__ void __launch_bounds__(256) k_mask_padding(const int32_t* __restrict__ perm, int n, float* __restrict__ h)
 {
@@ -353,7 +375,7 @@ struct OrderWs {
     float *Xs_split, *hs_split;      // the reordered copy in split bfloat16 halves and its half norms (nullptr: d does not allow it)
     // a second split copy, every tile relative to the centre of the first tile of its region, with its half norms;
     // region number, first tile and boundary flag per tile (see run_knn; nullptr: the pruned sweeps keep float32 products)
-    float *Xs_local, *hs_local;
+    float *Xs_local, *hs_local, *region_other_min;
     int32_t *tile_region, *tile_first, *tile_last, *tile_boundary;
     int32_t *pid, *perm, *inv, *colour_s, *qslot, *tile_colour, *tile_list, *counts, *rank, *shift, *far_count;
     int32_t *n_src, *n_dst, *n_children, *n_sizes;
@@ -378,11 +400,12 @@ struct OrderWs {
         Xs = c.take<float>(nm * d); hs = c.take<float>(nm);
         Xs_split = nullptr; hs_split = nullptr;
         if (split_products_ok(d)) { Xs_split = c.take<float>(nm * d); hs_split = c.take<float>(nm); }
-        Xs_local = nullptr; hs_local = nullptr; tile_region = nullptr; tile_first = nullptr; tile_last = nullptr; tile_boundary = nullptr;
+        Xs_local = nullptr; hs_local = nullptr; region_other_min = nullptr; tile_region = nullptr; tile_first = nullptr; tile_last = nullptr; tile_boundary = nullptr;
         if (split_products_ok(d) && d <= 128) {
             Xs_local = c.take<float>(nm * d); hs_local = c.take<float>(nm);
             tile_region = c.take<int32_t>((size_t)Tmax); tile_first = c.take<int32_t>((size_t)Tmax);
             tile_last = c.take<int32_t>((size_t)Tmax);
+            region_other_min = c.take<float>((size_t)Tmax);
             tile_boundary = c.take<int32_t>((size_t)Tmax);
         }
         tile_c = c.take<float>((size_t)Tmax * d); tile_r = c.take<float>((size_t)Tmax);
@@ -827,6 +850,11 @@ int run_knn(const float* X, int64_t N, int32_t d, int32_t k, int32_t* nbr_idx, f
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, p.panel_counter, 2);
         HIP_TRY(hipGetLastError());
         p.tile_region = o.tile_region; p.region_mode = 2;
+        if (p.tile_gap) {
+            hipLaunchKernelGGL(k_region_other_min, dim3((unsigned)T), dim3(256), 0, stream, p.tile_gap, o.tile_region, T, o.region_other_min);
+            HIP_TRY(hipGetLastError());
+            p.region_other_min = o.region_other_min;
+        }
     }
     HIP_TRY(slhc::launch_knn_sweep(p, stream));
     if (ev_sweep) HIP_TRY(hipEventRecord(ev_sweep->b, stream));

@@ -39,6 +39,8 @@ struct SweepParams {
     int region_mode;
     const int32_t* tile_first;  // optional, with region_mode 1: first and last tile of every tile's region (regions are
     const int32_t* tile_last;   // runs of consecutive tiles), which bound the scan
+    const float* region_other_min;   // optional, with region_mode 2 and tile_gap: per panel, the smallest lower bound of a tile
+                                     // outside its region; a panel whose thresholds are all below it is left alone
     int32_t* out_idx;      // k-NN: [*, k] at row q_out_row[q] (or q); cross 1-NN: [m]
     float* out_dist;       // same shape
     const int32_t* q_out_row;   // k-NN only: output row of query row q (nullptr: q itself)

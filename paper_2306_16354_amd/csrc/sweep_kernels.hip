@@ -1408,12 +1408,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
             __syncthreads();
             first_thr = fmaxf(fmaxf(L.wmax[0], L.wmax[1]), fmaxf(L.wmax[2], L.wmax[3]));
         }
+        // ... and when even the nearest tile outside the panel's region lies beyond them (its lower bound, taken from
+        // the table's row), the launch has nothing to add to this panel: no scan
+        const bool nothing_outside = REGIONS && lists_in && table_row && p.region_other_min != nullptr &&
+                                     p.region_other_min[panel] > first_thr;
 
         v16f acc[4];
         int scan_from = 0;                 // scan indices below this one are done or skipped
         int tile = own_tile;
         if (own_tile < 0) {
-            const int first = next_scan(0, first_thr);
+            const int first = nothing_outside ? nscan : next_scan(0, first_thr);
             tile = tile_of(first);
             scan_from = first + 1;
         }
