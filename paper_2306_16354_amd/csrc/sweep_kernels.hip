@@ -55,6 +55,9 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 #ifndef SLHC_SEGMENT_HANDICAP
 #define SLHC_SEGMENT_HANDICAP 1.18   // see sweep_segments_for
 #endif
+#ifndef SLHC_SCAN_AHEAD_1NN
+#define SLHC_SCAN_AHEAD_1NN 4   // the same in the connection sweeps (8 and 16 measured: no gain at 2M x 32, 1-5 % slower at 1M x 128)
+#endif
 #ifndef SLHC_SCAN_AHEAD
 #define SLHC_SCAN_AHEAD 4      // groups of 64 scan positions whose lower bounds a pruned sweep reads at once (see next_scan)
 #endif
@@ -1322,7 +1325,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sweep_kernel_qreg(SweepParams p
         auto tile_of = [&](int i) -> int { return i >= nscan ? ntiles : scan_tile(i); };
         // (SCAN_AHEAD groups of 64 positions are read at once: one group at a time the scan is a chain of dependent
         // loads, a microsecond each, and a panel that multiplies two tiles of 20 000 spends its time there)
-        constexpr int SCAN_AHEAD = SLHC_SCAN_AHEAD;
+        constexpr int SCAN_AHEAD = MASKED ? SLHC_SCAN_AHEAD_1NN : SLHC_SCAN_AHEAD;
         auto next_scan = [&](int i, float thr_max) -> int {
             if (!prune) return i;
             while (i < nscan) {
