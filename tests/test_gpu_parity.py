@@ -578,6 +578,10 @@ def test_pruned_random_shapes(lib):
         centres = rng.uniform(-spread, spread, size=(nb, d))
         X = (centres[rng.integers(0, nb, size=N)] + sigma * rng.standard_normal((N, d))).astype(np.float32)
         ties = False
+        if case % 6 == 5:
+            # a common offset (the split copy is taken relative to the column means) on rows that come sorted along
+            # one axis (regions of the row order that follow the input order)
+            X = (X + np.float32(1.0e4))[np.argsort(X[:, 0], kind="stable")]
         if rng.random() < 0.3:
             m = N // 10
             X[rng.integers(0, N, size=m)] = X[rng.integers(0, N, size=m)]
